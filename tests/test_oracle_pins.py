@@ -1,0 +1,213 @@
+"""Pins of the CPU oracle against things other than itself.
+
+The oracle is the definition C = A x B (Section 3.2) and the direct 3x3 / pad 1
+convolution (Section 3.6).  It is pinned by hand-worked fixtures, brute-force
+dense products, closed forms and invariants, chosen so that a dropped term, a
+wrong sign or index, or a transposed operand fails at least one of them.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2008_11849_amd import synth
+
+TINY = [1, 2, 3, 5, 8, 17, 33]
+
+
+def _csr_of(A):
+    A = np.asarray(A)
+    return synth.csr_from_mask(A, A != 0)
+
+
+def _spmm(csr, B, **kw):
+    return ref.spmm(csr.M, csr.K, B.shape[1], csr.row_ptr, csr.col_idx, csr.vals, B, **kw)
+
+
+def test_hand_worked_spmm(golden):
+    g = golden("spmm_hand_3x4.txt")
+    C, S = _spmm(_csr_of(g["A"]), g["B"])
+    assert np.array_equal(C, g["C"])
+    assert np.array_equal(S, np.abs(g["A"]) @ np.abs(g["B"]))
+    assert not np.signbit(C[1]).any()  # empty row gives +0.0
+
+
+@pytest.mark.parametrize("M,K", list(itertools.product(TINY, TINY)))
+def test_brute_force_tiny(M, K):
+    rng = np.random.default_rng(M * 100 + K)
+    for N in (1, 3, 49, 63, 64, 65, 196):
+        A = rng.standard_normal((M, K)) * (rng.random((M, K)) < 0.4)
+        B = rng.standard_normal((K, N))
+        C, S = _spmm(_csr_of(A), B)
+        assert np.allclose(C, A @ B, rtol=0, atol=1e-12 * max(1.0, np.abs(A).sum()))
+        assert np.allclose(S, np.abs(A) @ np.abs(B), rtol=1e-13, atol=0)
+
+
+def test_sparsity_zero_is_dense_gemm():
+    rng = np.random.default_rng(7)
+    A = rng.standard_normal((37, 29)) + 3.0  # no zeros
+    B = rng.standard_normal((29, 70))
+    C, _ = _spmm(_csr_of(A), B)
+    assert np.allclose(C, np.matmul(A, B), rtol=1e-13, atol=1e-13)
+
+
+def test_identity_permutation_and_power_of_two_scaling_are_bit_exact():
+    rng = np.random.default_rng(11)
+    K, N = 41, 67
+    B = rng.standard_normal((K, N)).astype(np.float32)
+    C, _ = _spmm(_csr_of(np.eye(K)), B)
+    assert np.array_equal(C, B.astype(np.float64))
+    perm = rng.permutation(K)
+    P = np.zeros((K, K))
+    P[np.arange(K), perm] = 1.0
+    C, _ = _spmm(_csr_of(P), B)
+    assert np.array_equal(C, B[perm].astype(np.float64))
+    e = rng.integers(-6, 7, size=K)
+    C, _ = _spmm(_csr_of(np.diag(2.0 ** e)), B)
+    assert np.array_equal(C, np.ldexp(B.astype(np.float64), e[:, None]))
+
+
+def test_all_zero_matrix_gives_positive_zero():
+    M, K, N = 5, 7, 9
+    row_ptr = np.zeros(M + 1, dtype=np.int32)
+    C, S = ref.spmm(M, K, N, row_ptr, np.zeros(0, np.int32), np.zeros(0), np.ones((K, N)))
+    assert np.array_equal(C, np.zeros((M, N))) and not np.signbit(C).any()
+    assert np.array_equal(S, np.zeros((M, N)))
+
+
+def test_column_independence():
+    rng = np.random.default_rng(3)
+    csr = synth.uniform_csr(19, 23, 0.7, 5)
+    B1 = rng.standard_normal((23, 31))
+    B2 = rng.standard_normal((23, 31))
+    B2[:, 13] = B1[:, 13]
+    C1, _ = _spmm(csr, B1)
+    C2, _ = _spmm(csr, B2)
+    assert np.array_equal(C1[:, 13], C2[:, 13])
+    assert not np.array_equal(C1[:, 12], C2[:, 12])
+
+
+def test_linearity_is_exact_on_integers():
+    csr = synth.small_int_csr(21, 34, 0.6, 9)
+    B1 = synth.small_int_dense(34, 50, 1).astype(np.float64)
+    B2 = synth.small_int_dense(34, 50, 2).astype(np.float64)
+    Ca, _ = _spmm(csr, B1 + B2)
+    Cb = _spmm(csr, B1)[0] + _spmm(csr, B2)[0]
+    assert np.array_equal(Ca, Cb)
+    assert np.array_equal(Ca, csr.todense() @ (B1 + B2))
+
+
+def test_explicit_zero_and_stored_order_are_honoured():
+    # an explicitly stored 0.0 is a legal entry and contributes nothing
+    row_ptr = np.array([0, 3], dtype=np.int32)
+    cols = np.array([0, 2, 3], dtype=np.int32)
+    vals = np.array([1.5, 0.0, -2.0])
+    B = np.arange(8, dtype=np.float64).reshape(4, 2)
+    C, _ = ref.spmm(1, 4, 2, row_ptr, cols, vals, B)
+    assert np.array_equal(C, np.array([[1.5 * 0 - 2.0 * 6, 1.5 * 1 - 2.0 * 7]]))
+
+
+def test_half_inputs_are_consumed_exactly():
+    csr = synth.uniform_csr(9, 12, 0.5, 4, dtype=np.float16)
+    B = synth.normal_dense(12, 20, 5, dtype=np.float16)
+    C, _ = _spmm(csr, B)
+    A = csr.todense()
+    assert np.allclose(C, A @ B.astype(np.float64), rtol=1e-14, atol=1e-14)
+
+
+# --------------------------------------------------------------- convolution
+
+def test_conv_all_ones_counts_taps(golden):
+    Yg = golden("conv_ones_4x5.txt")["Y"]
+    Y, S = ref.conv3x3(np.ones((1, 1, 3, 3)), np.ones((1, 1, 4, 5)))
+    assert np.array_equal(Y[0, 0], Yg) and np.array_equal(S[0, 0], Yg)
+
+
+def test_conv_hand_shift(golden):
+    g = golden("conv_shift_3x3.txt")
+    Y, _ = ref.conv3x3(g["W"].reshape(1, 1, 3, 3), g["X"].reshape(1, 1, 3, 3))
+    assert np.array_equal(Y[0, 0], g["Y"])
+
+
+def test_conv_hand_two_channels(golden):
+    g = golden("conv_two_channel_2x2.txt")
+    W = np.stack([g["W0"], g["W1"]])[None]
+    X = np.stack([g["X0"], g["X1"]])[None]
+    Y, _ = ref.conv3x3(W, X)
+    assert np.array_equal(Y[0, 0], g["Y"])
+
+
+@pytest.mark.parametrize("r,s", list(itertools.product(range(3), range(3))))
+def test_conv_single_tap_is_a_zero_filled_shift(r, s):
+    rng = np.random.default_rng(r * 3 + s)
+    H, W = 6, 7
+    X = rng.standard_normal((1, 1, H, W)).astype(np.float32)
+    Wt = np.zeros((1, 1, 3, 3))
+    Wt[0, 0, r, s] = 1.0
+    Y, _ = ref.conv3x3(Wt, X)
+    pad = np.zeros((H + 2, W + 2))
+    pad[1:-1, 1:-1] = X[0, 0]
+    assert np.array_equal(Y[0, 0], pad[r:r + H, s:s + W])  # Y[oh,ow] = Xpad[oh+r, ow+s]
+
+
+def test_conv_channel_additivity_and_batch():
+    rng = np.random.default_rng(2)
+    W = rng.integers(-3, 4, size=(4, 3, 3, 3)).astype(np.float64)
+    X = rng.integers(-5, 6, size=(2, 3, 5, 4)).astype(np.float64)
+    Y, _ = ref.conv3x3(W, X)
+    parts = sum(ref.conv3x3(W[:, c:c + 1], X[:, c:c + 1])[0] for c in range(3))
+    assert np.array_equal(Y, parts)
+    assert np.array_equal(Y[1:2], ref.conv3x3(W, X[1:2])[0])
+
+
+def test_conv_direct_equals_spmm_on_explicit_im2col():
+    csr, Wd = synth.conv_weights_csr(6, 5, 0.7, 21)
+    X = synth.normal_dense(5, 7 * 9, 22).reshape(1, 5, 7, 9)
+    Y, S = ref.conv3x3(Wd, X)
+    Bcol = ref.im2col3x3(X[0])
+    # k = c*9 + r*3 + s, n = oh*W + ow
+    assert Bcol[2 * 9 + 0 * 3 + 2, 3 * 9 + 4] == X[0, 2, 3 - 1, 4 + 1]
+    C, S2 = ref.spmm(6, 45, 63, csr.row_ptr, csr.col_idx, csr.vals, Bcol)
+    assert np.allclose(C.reshape(Y.shape), Y, rtol=1e-13, atol=1e-13)
+    assert np.allclose(S2.reshape(S.shape), S, rtol=1e-13, atol=1e-13)
+
+
+def test_conv_matches_library_cross_correlation():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(5)
+    W = rng.standard_normal((7, 4, 3, 3))
+    X = rng.standard_normal((2, 4, 9, 6))
+    Y, _ = ref.conv3x3(W, X)
+    Yt = torch.nn.functional.conv2d(torch.from_numpy(X), torch.from_numpy(W), padding=1).numpy()
+    assert np.allclose(Y, Yt, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------- generators / metric
+
+def test_generators_hit_exact_counts():
+    assert synth.exact_nnz(256, 256, 0.90) == 6554
+    assert synth.exact_nnz(512, 512, 0.90) == 26214
+    assert synth.exact_nnz(3072, 768, 0.95) == 117965
+    assert synth.exact_nnz(256, 2304, 0.90) == 58982
+    c = synth.config("c1")
+    assert c.csr.nnz == 6554 and c.B.shape == (256, 1024)
+    for m in range(c.csr.M):
+        cols = c.csr.col_idx[c.csr.row_ptr[m]:c.csr.row_ptr[m + 1]]
+        assert np.all(np.diff(cols) > 0)
+    sk = synth.skewed_csr(256, 256, 0.98, 3)
+    nn = np.diff(sk.row_ptr)
+    assert nn.max() > 20 * max(1, np.median(nn)) and (nn == 0).any()
+
+
+def test_error_metric_flags_a_planted_mistake():
+    c = synth.config("c1")
+    C, S = _spmm(c.csr, c.B)
+    good = C.astype(np.float32)
+    m = ref.error_metrics(good, C, S)
+    assert m["componentwise"] < 1e-6 and m["exact_on_zero_scale"]
+    # drop one term of one output: far above the fp32 tolerance
+    p = c.csr.row_ptr[3]
+    bad = good.copy()
+    bad[3, 10] -= np.float32(c.csr.vals[p]) * c.B[c.csr.col_idx[p], 10]
+    assert ref.error_metrics(bad, C, S)["componentwise"] > 1e-4 or abs(c.B[c.csr.col_idx[p], 10]) < 1e-3
