@@ -1,0 +1,186 @@
+/*
+ * sparsert.h - C ABI of the MI355X (gfx950) SpMM / sparse 3x3 convolution library.
+ *
+ * The library follows the inspector-executor split of the paper (Section 2.3):
+ * the sparse weight matrix A is fully known ahead of time, so it is analysed
+ * once on the host (`sparsert_inspect`) and the resulting immutable plan is
+ * executed many times against changing dense activations (`sparsert_spmm`,
+ * `sparsert_conv3x3`).
+ *
+ * Conventions used by every entry point
+ *   - Matrices are C-style row-major and dense-pitched (Section 3.2): B is
+ *     K x N with N contiguous, C is M x N with N contiguous, no leading
+ *     dimension argument.
+ *   - "HOST" pointers are ordinary CPU memory; "DEVICE" pointers are HIP
+ *     device memory on the device that was current when the plan was made.
+ *   - Every function returns a status code (sparsert_status: 0 = ok, negative = error) and
+ *     never aborts; sparsert_last_error() gives a thread-local message.
+ *   - No torch / C++ types cross this boundary.
+ */
+#ifndef SPARSERT_H
+#define SPARSERT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sparsert_plan sparsert_plan; /* opaque; immutable after inspect */
+
+typedef enum sparsert_status {
+    SPARSERT_OK = 0,
+    SPARSERT_EINVAL = -1,       /* bad argument / malformed CSR / misaligned pointer */
+    SPARSERT_ENOMEM = -2,       /* host or device allocation failed */
+    SPARSERT_EHIP = -3,         /* a HIP runtime call or kernel launch failed */
+    SPARSERT_EUNSUPPORTED = -4, /* legal request outside what is implemented */
+    SPARSERT_ECOMPILE = -5      /* run-time compilation of a specialised kernel failed */
+} sparsert_status;
+
+/* Storage type of vals, B/X and C/Y.  Accumulation is always IEEE binary32;
+ * with SPARSERT_F16 each product of two halves is exact in binary32 and the
+ * sum is rounded to half once, at the store. */
+typedef enum sparsert_dtype { SPARSERT_F32 = 0, SPARSERT_F16 = 1 } sparsert_dtype;
+
+/* Executor families (options.kernel / INFO[SPARSERT_INFO_KERNEL]). */
+typedef enum sparsert_kernel {
+    SPARSERT_KERNEL_AUTO = 0,
+    SPARSERT_KERNEL_ROWS = 1,  /* one wave per row, B read straight from L2/HBM */
+    SPARSERT_KERNEL_SPEC = 2   /* per-matrix generated code (Section 3.5), via hiprtc */
+} sparsert_kernel;
+
+/* Zero-initialise, then set what you need.  All-zero = fp32 SpMM, automatic tiling. */
+typedef struct sparsert_options {
+    int32_t dtype;           /* sparsert_dtype */
+    int32_t kernel;          /* sparsert_kernel; AUTO lets the inspector choose */
+    int32_t conv;            /* 0: SpMM plan.  1: 3x3 / pad 1 / stride 1 convolution plan */
+    int32_t Cin, H, W;       /* conv only: K must equal 9*Cin and N must equal H*W */
+    int32_t batch;           /* conv only: must be 1 (0 is read as 1) */
+    int32_t host_only;       /* 1: analyse only; no HIP call is made, the plan can be
+                                exported but not executed */
+    int32_t vec;             /* columns of C per lane; 0 = automatic, else 1,2,4 (,8 for f16) */
+    int32_t split_threshold; /* rows with at least this many nonzeros are split over the
+                                waves of a workgroup; 0 = automatic */
+    int32_t reserved[6];     /* must be zero */
+} sparsert_options;
+
+/*
+ * Inspector (Sections 2.3, 3.4).  Analyses the fixed sparsity pattern of A and
+ * builds the plan: per-row nonzero counts and their histogram, the row
+ * permutation and bins used for wavefront load balance, the permuted CSR, the
+ * split of long rows over the waves of a workgroup so that every wave but the
+ * last gets the same number of nonzeros, and the packed nonzero stream the
+ * executor reads.  Integer work only: values are moved, never altered.
+ *
+ *   row_ptr  HOST int32[M+1], row_ptr[0] == 0, non-decreasing
+ *   col_idx  HOST int32[nnz], 0 <= col < K, strictly ascending inside each row
+ *   vals     HOST float[nnz] (SPARSERT_F32) or IEEE half[nnz] (SPARSERT_F16);
+ *            explicit zeros, -0.0, NaN payloads are kept bit for bit
+ *   M, K, N  > 0.  N is part of the plan (it fixes tiling and B row offsets).
+ *   opt      may be NULL (= all zero)
+ *   out      receives the plan on success, is set to NULL on failure
+ *
+ * The CSR is deep-copied; the caller may free its arrays at once.  Unless
+ * opt->host_only is set the plan's device arrays are allocated and uploaded
+ * here (synchronously) on the current HIP device.
+ * Errors: EINVAL for null pointers, non-positive sizes, malformed CSR, bad
+ * options; EUNSUPPORTED for batch > 1 or for B, C or X of 2 GiB and more;
+ * ENOMEM / EHIP from allocation and upload.
+ */
+int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
+                     int32_t M, int32_t K, int32_t N,
+                     const sparsert_options *opt, sparsert_plan **out);
+
+/*
+ * Executor, SpMM (Section 3.2 statement of the problem; Section 3.5, the
+ * per-thread-group loop): C = A x B, C fully overwritten (no alpha/beta); a
+ * row of A without nonzeros yields +0.0.
+ *
+ *   B_dev  DEVICE, K x N row-major, plan's dtype, 16-byte aligned, read only
+ *   C_dev  DEVICE, M x N row-major, plan's dtype, 16-byte aligned, written
+ *   stream a hipStream_t (NULL = the null stream)
+ *
+ * Asynchronous on `stream`; allocates nothing; does not synchronise.  The plan
+ * is read only, so concurrent calls on different streams are legal provided
+ * their C buffers differ.  B and C are borrowed and must not overlap.
+ * Errors: EINVAL (null/misaligned pointer, conv plan, host-only plan), EHIP.
+ */
+int sparsert_spmm(const sparsert_plan *plan, const void *B_dev, void *C_dev, void *stream);
+
+/*
+ * Executor, sparse 3x3 convolution (Section 3.6): padding 1, stride 1,
+ * cross-correlation, batch 1.  The filter bank [Cout, Cin, 3, 3] is the plan's
+ * A with M = Cout and column k = c*9 + r*3 + s; the im2col matrix is never
+ * built - every reference to B[k, oh*W+ow] reads X[c, oh+r-1, ow+s-1] and the
+ * padding test is resolved per (r,s) group by the inspector's ordering, not per
+ * multiply.
+ *
+ *   X_dev  DEVICE, [1, Cin, H, W] contiguous, plan's dtype, 16-byte aligned
+ *   Y_dev  DEVICE, [1, Cout, H, W] contiguous, plan's dtype, 16-byte aligned
+ *
+ * Same asynchrony, ownership and error rules as sparsert_spmm; EINVAL if the
+ * plan was not made with opt->conv = 1.
+ */
+int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, void *stream);
+
+/* Arrays of the plan that sparsert_plan_export can copy out (HOST side). */
+typedef enum sparsert_field {
+    SPARSERT_FIELD_INFO = 0,      /* int32[SPARSERT_INFO_COUNT], see below */
+    SPARSERT_FIELD_ROW_NNZ = 1,   /* int32[M]   nonzeros per original row */
+    SPARSERT_FIELD_HIST = 2,      /* int32[33]  rows per bin; bin(0)=0, bin(x)=1+floor(log2 x) */
+    SPARSERT_FIELD_PERM = 3,      /* int32[M]   slot -> original row: stable sort by nnz descending */
+    SPARSERT_FIELD_INV_PERM = 4,  /* int32[M]   original row -> slot */
+    SPARSERT_FIELD_P_ROW_PTR = 5, /* int32[M+1] row pointer of the permuted CSR */
+    SPARSERT_FIELD_P_COL_IDX = 6, /* int32[nnz] columns, rows gathered by PERM, ascending per row */
+    SPARSERT_FIELD_P_VALS = 7,    /* dtype[nnz] values, bit copies */
+    SPARSERT_FIELD_BINS = 8,      /* int32[nbins][4]: bin id, first slot, rows, nonzeros */
+    SPARSERT_FIELD_STREAM = 9,    /* uint32[nnz][2]: what the executor reads per nonzero:
+                                     {operand byte offset as int32, value as binary32 bits}.
+                                     SpMM: offset = col*N*sizeof(dtype), permuted-CSR order.
+                                     Conv: offset = (c*H*W + (r-1)*W + (s-1))*sizeof(dtype)
+                                     (may be negative), each slot ordered by (r*3+s, c) */
+    SPARSERT_FIELD_CONV_SEG = 10, /* conv only, int32[M][10]: stream positions where each
+                                     (r,s) group of a slot starts; [9] = end of the slot */
+    SPARSERT_FIELD_SEGMENTS = 11  /* int32[n_split][Gy+1]: stream positions bounding the
+                                     share of each wave of a split row */
+} sparsert_field;
+
+enum {
+    SPARSERT_INFO_M = 0, SPARSERT_INFO_K, SPARSERT_INFO_N, SPARSERT_INFO_NNZ,
+    SPARSERT_INFO_DTYPE, SPARSERT_INFO_CONV, SPARSERT_INFO_CIN, SPARSERT_INFO_H,
+    SPARSERT_INFO_W, SPARSERT_INFO_KERNEL,
+    SPARSERT_INFO_VEC,            /* V: columns of C per lane */
+    SPARSERT_INFO_LANES_PER_TILE, /* lanes of a wave that own columns */
+    SPARSERT_INFO_N_TILES,        /* column tiles; a wave covers LANES_PER_TILE*V columns */
+    SPARSERT_INFO_GY,             /* waves per workgroup */
+    SPARSERT_INFO_SPLIT_THRESHOLD,
+    SPARSERT_INFO_N_SPLIT,        /* slots [0, N_SPLIT) are split rows */
+    SPARSERT_INFO_N_WG_ROWS,      /* workgroups along M: N_SPLIT + ceil((M-N_SPLIT)/GY) */
+    SPARSERT_INFO_N_BINS,
+    SPARSERT_INFO_COUNT = 24      /* remaining entries are zero */
+};
+
+/*
+ * Copies one plan array to HOST memory.  `need` (may be NULL) receives the size
+ * in bytes; if `buf` is NULL only the size is reported; if `cap` is smaller
+ * than the size nothing is copied and EINVAL is returned.
+ */
+int sparsert_plan_export(const sparsert_plan *plan, int32_t field,
+                         void *buf, size_t cap, size_t *need);
+
+/* Frees the plan's host and device memory.  NULL is ignored.  The caller must
+ * make sure no launch that uses the plan is still in flight. */
+void sparsert_plan_destroy(sparsert_plan *plan);
+
+/* Message of the last failing call on this thread ("" if none).  The pointer
+ * stays valid until the next failing call on the same thread. */
+const char *sparsert_last_error(void);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t sparsert_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSERT_H */

@@ -86,7 +86,9 @@ def error_metrics(got, ref, scale) -> dict:
     componentwise: max |got-ref| / S   with S = |A|*|B| (Higham-style bound; the
                    gate), entries with S == 0 must match exactly;
     normwise:      max |got-ref| / max |ref|;
-    relative:      max |got-ref| / |ref| over entries with |ref| >= 1e-3 * rms(ref).
+    relative:      max |got-ref| / |ref| over entries with |ref| >= 1e-2 * rms(ref)
+                   (below that floor cancellation makes |ref| arbitrarily small and even a
+                   correctly rounded fp32 sum exceeds any fixed relative bound).
     """
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
@@ -98,7 +100,7 @@ def error_metrics(got, ref, scale) -> dict:
     ref_max = float(np.max(np.abs(ref))) if ref.size else 0.0
     normwise = float(np.max(diff) / ref_max) if ref_max > 0 else float(np.max(diff, initial=0.0))
     rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
-    big = np.abs(ref) >= 1e-3 * rms
+    big = np.abs(ref) >= 1e-2 * rms
     rel = float(np.max(diff[big] / np.abs(ref[big]))) if (rms > 0 and big.any()) else 0.0
     return {"componentwise": comp, "normwise": normwise, "relative": rel,
             "exact_on_zero_scale": exact_on_zero}

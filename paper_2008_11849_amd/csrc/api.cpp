@@ -1,0 +1,119 @@
+// extern "C" boundary: argument checks, error strings, plan export.
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "plan.h"
+
+namespace {
+thread_local std::string g_err;
+int fail(int code, const std::string &msg) { g_err = msg; return code; }
+}  // namespace
+
+extern "C" {
+
+int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
+                     int32_t M, int32_t K, int32_t N,
+                     const sparsert_options *opt, sparsert_plan **out) {
+    if (!out) return fail(SPARSERT_EINVAL, "out is NULL");
+    *out = nullptr;
+    sparsert_options o;
+    if (opt) o = *opt; else std::memset(&o, 0, sizeof(o));
+    sparsert_plan *plan = new (std::nothrow) sparsert_plan();
+    if (!plan) return fail(SPARSERT_ENOMEM, "out of host memory");
+    std::string err;
+    int rc;
+    try {
+        rc = sparsert::build_host_plan(row_ptr, col_idx, vals, M, K, N, o, plan->host, err);
+    } catch (const std::bad_alloc &) {
+        rc = SPARSERT_ENOMEM; err = "out of host memory";
+    }
+    if (rc == SPARSERT_OK && !o.host_only) {
+        rc = sparsert::upload_plan(plan->host, plan->dev, err);
+        plan->on_device = (rc == SPARSERT_OK);
+    }
+    if (rc != SPARSERT_OK) {
+        sparsert::free_device_plan(plan->dev);
+        delete plan;
+        return fail(rc, err);
+    }
+    *out = plan;
+    return SPARSERT_OK;
+}
+
+static int check_exec(const sparsert_plan *plan, const void *in, void *outp, bool conv) {
+    if (!plan) return fail(SPARSERT_EINVAL, "plan is NULL");
+    if (!in || !outp) return fail(SPARSERT_EINVAL, "device pointer is NULL");
+    if (((uintptr_t)in | (uintptr_t)outp) & 15u) return fail(SPARSERT_EINVAL, "device pointers must be 16-byte aligned");
+    if (!plan->on_device) return fail(SPARSERT_EINVAL, "plan was made with host_only and cannot be executed");
+    if ((plan->host.conv != 0) != conv)
+        return fail(SPARSERT_EINVAL, conv ? "plan is not a convolution plan" : "plan is a convolution plan; use sparsert_conv3x3");
+    return SPARSERT_OK;
+}
+
+int sparsert_spmm(const sparsert_plan *plan, const void *B_dev, void *C_dev, void *stream) {
+    if (int rc = check_exec(plan, B_dev, C_dev, false)) return rc;
+    std::string err;
+    int rc = sparsert::launch_rows(plan->host, plan->dev, B_dev, C_dev, stream, err);
+    return rc == SPARSERT_OK ? rc : fail(rc, err);
+}
+
+int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, void *stream) {
+    if (int rc = check_exec(plan, X_dev, Y_dev, true)) return rc;
+    std::string err;
+    int rc = sparsert::launch_rows(plan->host, plan->dev, X_dev, Y_dev, stream, err);
+    return rc == SPARSERT_OK ? rc : fail(rc, err);
+}
+
+int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, size_t cap, size_t *need) {
+    if (!plan) return fail(SPARSERT_EINVAL, "plan is NULL");
+    const sparsert::HostPlan &h = plan->host;
+    int32_t info[SPARSERT_INFO_COUNT] = {0};
+    const void *src = nullptr;
+    size_t bytes = 0;
+    auto vec32 = [&](const std::vector<int32_t> &v) { src = v.data(); bytes = v.size() * 4; };
+    switch (field) {
+    case SPARSERT_FIELD_INFO:
+        info[SPARSERT_INFO_M] = h.M; info[SPARSERT_INFO_K] = h.K; info[SPARSERT_INFO_N] = h.N;
+        info[SPARSERT_INFO_NNZ] = h.nnz; info[SPARSERT_INFO_DTYPE] = h.dtype;
+        info[SPARSERT_INFO_CONV] = h.conv; info[SPARSERT_INFO_CIN] = h.Cin;
+        info[SPARSERT_INFO_H] = h.H; info[SPARSERT_INFO_W] = h.W;
+        info[SPARSERT_INFO_KERNEL] = h.kernel; info[SPARSERT_INFO_VEC] = h.vec;
+        info[SPARSERT_INFO_LANES_PER_TILE] = h.lanes_per_tile;
+        info[SPARSERT_INFO_N_TILES] = h.n_tiles; info[SPARSERT_INFO_GY] = h.gy;
+        info[SPARSERT_INFO_SPLIT_THRESHOLD] = h.split_threshold;
+        info[SPARSERT_INFO_N_SPLIT] = h.n_split; info[SPARSERT_INFO_N_WG_ROWS] = h.n_wg_rows;
+        info[SPARSERT_INFO_N_BINS] = (int32_t)(h.bins.size() / 4);
+        src = info; bytes = sizeof(info);
+        break;
+    case SPARSERT_FIELD_ROW_NNZ: vec32(h.row_nnz); break;
+    case SPARSERT_FIELD_HIST: vec32(h.hist); break;
+    case SPARSERT_FIELD_PERM: vec32(h.perm); break;
+    case SPARSERT_FIELD_INV_PERM: vec32(h.inv_perm); break;
+    case SPARSERT_FIELD_P_ROW_PTR: vec32(h.p_row_ptr); break;
+    case SPARSERT_FIELD_P_COL_IDX: vec32(h.p_col_idx); break;
+    case SPARSERT_FIELD_P_VALS: src = h.p_vals.data(); bytes = h.p_vals.size(); break;
+    case SPARSERT_FIELD_BINS: vec32(h.bins); break;
+    case SPARSERT_FIELD_STREAM: src = h.stream.data(); bytes = h.stream.size() * 4; break;
+    case SPARSERT_FIELD_CONV_SEG: vec32(h.conv_seg); break;
+    case SPARSERT_FIELD_SEGMENTS: vec32(h.segments); break;
+    default: return fail(SPARSERT_EINVAL, "unknown plan field");
+    }
+    if (need) *need = bytes;
+    if (!buf) return SPARSERT_OK;
+    if (cap < bytes) return fail(SPARSERT_EINVAL, "export buffer too small");
+    if (bytes) std::memcpy(buf, src, bytes);
+    return SPARSERT_OK;
+}
+
+void sparsert_plan_destroy(sparsert_plan *plan) {
+    if (!plan) return;
+    sparsert::free_device_plan(plan->dev);
+    delete plan;
+}
+
+const char *sparsert_last_error(void) { return g_err.c_str(); }
+
+int32_t sparsert_version(void) { return 100; }
+
+}  // extern "C"

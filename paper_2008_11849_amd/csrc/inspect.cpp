@@ -1,0 +1,219 @@
+// Host-side inspector (Sections 2.3 and 3.4): integer analysis of the fixed
+// sparsity pattern.  Nothing here touches a value arithmetically.
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+
+#include "plan.h"
+
+namespace sparsert {
+
+static inline int bin_of(int32_t x) {
+    int b = 0;
+    while (x > 0) { ++b; x >>= 1; }
+    return b;  // 0 for x == 0, else 1 + floor(log2 x)
+}
+
+// IEEE binary16 -> binary32, exact for every input (subnormals, inf, NaN payload kept).
+static inline uint32_t half_bits_to_float_bits(uint16_t h) {
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t exp = (h >> 10) & 0x1fu;
+    uint32_t man = h & 0x3ffu;
+    if (exp == 0x1fu) return sign | 0x7f800000u | (man << 13);
+    if (exp == 0) {
+        if (man == 0) return sign;
+        int shift = 0;
+        while (!(man & 0x400u)) { man <<= 1; ++shift; }
+        man &= 0x3ffu;
+        exp = 1 - shift;
+        return sign | ((exp + 112u) << 23) | (man << 13);
+    }
+    return sign | ((exp + 112u) << 23) | (man << 13);
+}
+
+static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
+                    int32_t M, int32_t K, int32_t N, const sparsert_options &opt,
+                    std::string &err) {
+    if (!row_ptr) { err = "row_ptr is NULL"; return SPARSERT_EINVAL; }
+    if (M <= 0 || K <= 0 || N <= 0) { err = "M, K and N must be positive"; return SPARSERT_EINVAL; }
+    if (opt.dtype != SPARSERT_F32 && opt.dtype != SPARSERT_F16) { err = "unknown dtype"; return SPARSERT_EINVAL; }
+    if (opt.kernel < SPARSERT_KERNEL_AUTO || opt.kernel > SPARSERT_KERNEL_SPEC) { err = "unknown kernel family"; return SPARSERT_EINVAL; }
+    for (int i = 0; i < 6; ++i)
+        if (opt.reserved[i] != 0) { err = "reserved option fields must be zero"; return SPARSERT_EINVAL; }
+    if (row_ptr[0] != 0) { err = "row_ptr[0] must be 0"; return SPARSERT_EINVAL; }
+    for (int32_t m = 0; m < M; ++m)
+        if (row_ptr[m + 1] < row_ptr[m]) { err = "row_ptr must be non-decreasing"; return SPARSERT_EINVAL; }
+    const int32_t nnz = row_ptr[M];
+    if (nnz > 0 && (!col_idx || !vals)) { err = "col_idx / vals is NULL"; return SPARSERT_EINVAL; }
+    for (int32_t m = 0; m < M; ++m) {
+        for (int32_t p = row_ptr[m]; p < row_ptr[m + 1]; ++p) {
+            const int32_t c = col_idx[p];
+            if (c < 0 || c >= K) { err = "column index out of range"; return SPARSERT_EINVAL; }
+            if (p > row_ptr[m] && c <= col_idx[p - 1]) {
+                err = "columns must be strictly ascending inside a row";
+                return SPARSERT_EINVAL;
+            }
+        }
+    }
+    const int vmax = opt.dtype == SPARSERT_F16 ? 8 : 4;
+    if (opt.vec != 0) {
+        const int v = opt.vec;
+        if (!(v == 1 || v == 2 || v == 4 || v == 8) || v > vmax) { err = "vec must be 0,1,2,4 (8 for f16)"; return SPARSERT_EINVAL; }
+        if (N % v != 0) { err = "N must be a multiple of vec"; return SPARSERT_EINVAL; }
+        if (opt.conv && v != 1) { err = "conv plans use vec = 1"; return SPARSERT_EINVAL; }
+    }
+    if (opt.split_threshold < 0) { err = "split_threshold must be >= 0"; return SPARSERT_EINVAL; }
+    const int64_t esz = opt.dtype == SPARSERT_F16 ? 2 : 4;
+    if (opt.conv) {
+        if (opt.conv != 1) { err = "conv must be 0 or 1"; return SPARSERT_EINVAL; }
+        if (opt.Cin <= 0 || opt.H <= 0 || opt.W <= 0) { err = "conv needs Cin, H, W > 0"; return SPARSERT_EINVAL; }
+        if ((int64_t)K != 9ll * opt.Cin) { err = "conv needs K == 9*Cin"; return SPARSERT_EINVAL; }
+        if ((int64_t)N != (int64_t)opt.H * opt.W) { err = "conv needs N == H*W"; return SPARSERT_EINVAL; }
+        if (opt.batch > 1) { err = "conv batch > 1 is not implemented"; return SPARSERT_EUNSUPPORTED; }
+        if (opt.batch < 0) { err = "batch must be >= 0"; return SPARSERT_EINVAL; }
+        if (((int64_t)opt.Cin * opt.H * opt.W + opt.W + 1) * esz >= (1ll << 31)) {
+            err = "conv input too large for 32-bit operand offsets"; return SPARSERT_EUNSUPPORTED;
+        }
+    } else if ((int64_t)K * N * esz >= (1ll << 31) || (int64_t)M * N * esz >= (1ll << 31)) {
+        err = "B or C reaches 2 GiB: operand offsets are 32-bit"; return SPARSERT_EUNSUPPORTED;
+    }
+    return SPARSERT_OK;
+}
+
+// Columns of C per lane.  A wave covers n_tiles(V) = ceil(N/(64 V)) tiles and
+// issues V multiply-adds per nonzero per tile, so work(V) = n_tiles(V) * V.
+// Among the V dividing N whose work is within 7 % of the least, take the
+// largest that still leaves kFullTasks wave tasks; if none does, the smallest.
+static int choose_vec(int32_t M, int32_t N, int vmax) {
+    int cand[4], nc = 0;
+    int64_t work[4], wmin = INT64_MAX;
+    for (int v = 1; v <= vmax; v *= 2) {
+        if (N % v) continue;
+        const int64_t tiles = ((int64_t)N / v + kWave - 1) / kWave;
+        cand[nc] = v; work[nc] = tiles * v; wmin = std::min(wmin, work[nc]); ++nc;
+    }
+    int best = -1, smallest = -1;
+    for (int i = 0; i < nc; ++i) {
+        if (work[i] * 100 > wmin * 107) continue;
+        if (smallest < 0) smallest = cand[i];
+        const int64_t tiles = ((int64_t)N / cand[i] + kWave - 1) / kWave;
+        if ((int64_t)M * tiles >= kFullTasks) best = cand[i];
+    }
+    return best > 0 ? best : smallest;
+}
+
+int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
+                    int32_t M, int32_t K, int32_t N, const sparsert_options &opt,
+                    HostPlan &h, std::string &err) {
+    if (int rc = validate(row_ptr, col_idx, vals, M, K, N, opt, err)) return rc;
+    h.M = M; h.K = K; h.N = N; h.nnz = row_ptr[M];
+    h.dtype = opt.dtype; h.conv = opt.conv ? 1 : 0;
+    h.Cin = h.conv ? opt.Cin : 0; h.H = h.conv ? opt.H : 0; h.W = h.conv ? opt.W : 0;
+    h.kernel = opt.kernel == SPARSERT_KERNEL_AUTO ? SPARSERT_KERNEL_ROWS : opt.kernel;
+    const int esz = h.elem_size();
+
+    // Row histogram and the nnz-descending stable row order.
+    h.row_nnz.resize(M);
+    h.hist.assign(kBins, 0);
+    for (int32_t m = 0; m < M; ++m) {
+        h.row_nnz[m] = row_ptr[m + 1] - row_ptr[m];
+        ++h.hist[bin_of(h.row_nnz[m])];
+    }
+    h.perm.resize(M);
+    std::iota(h.perm.begin(), h.perm.end(), 0);
+    std::stable_sort(h.perm.begin(), h.perm.end(),
+                     [&](int32_t a, int32_t b) { return h.row_nnz[a] > h.row_nnz[b]; });
+    h.inv_perm.resize(M);
+    for (int32_t i = 0; i < M; ++i) h.inv_perm[h.perm[i]] = i;
+
+    // Permuted CSR: rows gathered by perm, values copied bit for bit.
+    h.p_row_ptr.resize(M + 1);
+    h.p_col_idx.resize(h.nnz);
+    h.p_vals.resize((size_t)h.nnz * esz);
+    h.p_row_ptr[0] = 0;
+    const uint8_t *vsrc = static_cast<const uint8_t *>(vals);
+    for (int32_t i = 0; i < M; ++i) {
+        const int32_t r = h.perm[i], n = h.row_nnz[r], dst = h.p_row_ptr[i];
+        if (n) {
+            std::memcpy(&h.p_col_idx[dst], col_idx + row_ptr[r], (size_t)n * sizeof(int32_t));
+            std::memcpy(&h.p_vals[(size_t)dst * esz], vsrc + (size_t)row_ptr[r] * esz, (size_t)n * esz);
+        }
+        h.p_row_ptr[i + 1] = dst + n;
+    }
+
+    // Bins: maximal runs of slots whose rows share a bin id.
+    h.bins.clear();
+    for (int32_t i = 0; i < M;) {
+        const int b = bin_of(h.row_nnz[h.perm[i]]);
+        int32_t j = i;
+        while (j < M && bin_of(h.row_nnz[h.perm[j]]) == b) ++j;
+        h.bins.insert(h.bins.end(), {b, i, j - i, h.p_row_ptr[j] - h.p_row_ptr[i]});
+        i = j;
+    }
+
+    // Column tiling.
+    const int vmax = h.conv ? 1 : (h.dtype == SPARSERT_F16 ? 8 : 4);
+    h.vec = opt.vec ? opt.vec : choose_vec(M, N, vmax);
+    const int32_t nvc = N / h.vec;  // vector columns
+    h.n_tiles = (nvc + kWave - 1) / kWave;
+    h.lanes_per_tile = (nvc + h.n_tiles - 1) / h.n_tiles;
+    h.gy = kGy;
+
+    // Long rows are split over the waves of one workgroup.
+    if (opt.split_threshold) h.split_threshold = opt.split_threshold;
+    else h.split_threshold = ((int64_t)M * h.n_tiles < kFullTasks) ? 64 : 512;
+    h.n_split = 0;
+    while (h.n_split < M && h.row_nnz[h.perm[h.n_split]] >= h.split_threshold) ++h.n_split;
+    h.n_wg_rows = h.n_split + (M - h.n_split + h.gy - 1) / h.gy;
+    h.segments.resize((size_t)h.n_split * (h.gy + 1));
+    for (int32_t i = 0; i < h.n_split; ++i) {
+        const int32_t start = h.p_row_ptr[i], n = h.p_row_ptr[i + 1] - start;
+        const int32_t share = (n + h.gy - 1) / h.gy;  // every wave but the last gets `share`
+        for (int g = 0; g <= h.gy; ++g)
+            h.segments[(size_t)i * (h.gy + 1) + g] = start + std::min<int64_t>((int64_t)g * share, n);
+    }
+
+    // The nonzero stream the executor reads: {operand byte offset, value as binary32 bits}.
+    h.stream.resize((size_t)h.nnz * 2);
+    auto value_bits = [&](int32_t p) -> uint32_t {
+        if (h.dtype == SPARSERT_F16) {
+            uint16_t hb; std::memcpy(&hb, &h.p_vals[(size_t)p * 2], 2);
+            return half_bits_to_float_bits(hb);
+        }
+        uint32_t fb; std::memcpy(&fb, &h.p_vals[(size_t)p * 4], 4);
+        return fb;
+    };
+    if (!h.conv) {
+        for (int32_t p = 0; p < h.nnz; ++p) {
+            h.stream[2 * (size_t)p] = (uint32_t)((uint64_t)h.p_col_idx[p] * (uint64_t)N * esz);
+            h.stream[2 * (size_t)p + 1] = value_bits(p);
+        }
+    } else {
+        // Section 3.6: each reference to B[k, oh*W+ow], k = c*9 + r*3 + s, is the input
+        // element X[c, oh+r-1, ow+s-1].  Relative to pixel (oh,ow) of channel 0 that is the
+        // fixed (possibly negative) displacement c*H*W + (r-1)*W + (s-1).
+        // Inside a slot the nonzeros are grouped by tap (r,s) so that the padding test is
+        // made once per group instead of once per multiply-add.
+        h.conv_seg.resize((size_t)M * 10);
+        const int32_t HW = h.H * h.W;
+        for (int32_t i = 0; i < M; ++i) {
+            const int32_t s0 = h.p_row_ptr[i], s1 = h.p_row_ptr[i + 1];
+            int32_t count[9] = {0};
+            for (int32_t p = s0; p < s1; ++p) ++count[h.p_col_idx[p] % 9];
+            int32_t pos[10];
+            pos[0] = s0;
+            for (int t = 0; t < 9; ++t) pos[t + 1] = pos[t] + count[t];
+            for (int t = 0; t < 10; ++t) h.conv_seg[(size_t)i * 10 + t] = pos[t];
+            for (int32_t p = s0; p < s1; ++p) {  // ascending k => ascending c inside a group
+                const int32_t k = h.p_col_idx[p], c = k / 9, rs = k % 9, r = rs / 3, s = rs % 3;
+                const int32_t q = pos[rs]++;
+                const int64_t off = (int64_t)c * HW + (r - 1) * h.W + (s - 1);
+                h.stream[2 * (size_t)q] = (uint32_t)(int32_t)(off * esz);
+                h.stream[2 * (size_t)q + 1] = value_bits(p);
+            }
+        }
+    }
+    return SPARSERT_OK;
+}
+
+}  // namespace sparsert

@@ -1,0 +1,267 @@
+// gfx950 executor kernels: row-walk SpMM and implicit-im2col 3x3 convolution.
+//
+// Mapping (Section 3.3 keeps N across the threads of a group and broadcasts
+// the A operand; the same idea is laid out here for 64-wide wavefronts):
+//   - lanes of a wave own V adjacent columns of C each, so B rows and C rows
+//     are read and written as contiguous, coalesced segments;
+//   - the nonzeros of a row form a wave-uniform stream {operand offset, value}
+//     that is fetched with scalar loads and broadcast from SGPRs;
+//   - accumulators live in VGPRs and are indexed statically, because a wave
+//     owns one row at a time (the paper needs full unrolling for that,
+//     Section 3.5; a row-per-wave walk gets it for free);
+//   - rows at or above the split threshold are shared by the Gy waves of a
+//     workgroup (Section 3.4, thread-group balance) and summed through LDS in a
+//     fixed order, so results are reproducible run to run.
+#include <hip/hip_runtime.h>
+
+#include "plan.h"
+
+namespace sparsert {
+
+template <typename T, int V> struct VecOf { typedef T type __attribute__((ext_vector_type(V))); };
+template <typename T> struct VecOf<T, 1> { typedef T type; };
+
+// Global (address space 1) byte pointer: keeps the loads on the global path with a
+// scalar base and a 32-bit per-lane offset.
+typedef const char __attribute__((address_space(1))) *gbytes;
+
+template <typename T, int V>
+__device__ __forceinline__ void load_cols(gbytes p, float (&out)[V]) {
+    typedef typename VecOf<T, V>::type vec_t;
+    const vec_t v = *reinterpret_cast<const vec_t __attribute__((address_space(1))) *>(p);
+    if constexpr (V == 1) {
+        out[0] = (float)v;
+    } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) out[j] = (float)v[j];
+    }
+}
+
+template <typename T, int V>
+__device__ __forceinline__ void store_cols(T *dst, const float (&acc)[V]) {
+    typedef typename VecOf<T, V>::type vec_t;
+    vec_t v;
+    if constexpr (V == 1) {
+        v = (T)acc[0];
+    } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) v[j] = (T)acc[j];  // f16: one round-to-nearest-even here
+    }
+    *reinterpret_cast<vec_t *>(dst) = v;
+}
+
+// acc[:] += sum over stream positions [p0, p1) of value * operand(in + offset + lane_off).
+// p0, p1, the stream and `in` are wave-uniform: the {offset, value} pairs arrive through
+// scalar loads, in + offset is a scalar address, lane_off the only per-lane part.
+template <typename T, int V>
+__device__ __forceinline__ void walk(const uint2 *__restrict__ stream, int p0, int p1,
+                                     gbytes in, uint32_t lane_off, float (&acc)[V]) {
+    constexpr int U = 8;
+    int p = p0;
+    for (; p + U <= p1; p += U) {
+        uint2 e[U];
+        float b[U][V];
+#pragma unroll
+        for (int i = 0; i < U; ++i) e[i] = stream[p + i];
+#pragma unroll
+        for (int i = 0; i < U; ++i) load_cols<T, V>(in + (int32_t)e[i].x + lane_off, b[i]);
+#pragma unroll
+        for (int i = 0; i < U; ++i)
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[j] = __builtin_fmaf(__uint_as_float(e[i].y), b[i][j], acc[j]);
+    }
+    for (; p < p1; ++p) {
+        const uint2 e = stream[p];
+        float b[V];
+        load_cols<T, V>(in + (int32_t)e.x + lane_off, b);
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = __builtin_fmaf(__uint_as_float(e.y), b[j], acc[j]);
+    }
+}
+
+struct RowsArgs {
+    const int32_t *p_row_ptr;
+    const int32_t *perm;
+    const uint2 *stream;
+    const int32_t *segments;
+    const int32_t *conv_seg;
+    const void *in;   // B [K,N] or X [Cin,H,W]
+    void *out;        // C [M,N] or Y [Cout,H,W]
+    int32_t M, N;
+    int32_t n_vec_cols, lanes_per_tile, n_tiles;
+    int32_t n_split, n_wg_rows;
+    int32_t n_tasks, tasks_per_xcd;
+    int32_t H, W;
+};
+
+template <typename T, int V, bool CONV>
+__global__ __launch_bounds__(kGy *kWave) void rows_kernel(const RowsArgs a) {
+    // Workgroups are handed to the 8 XCDs round-robin.  Remap so that each XCD works on a
+    // contiguous run of tasks; tasks are ordered column-tile major, so the B column slab
+    // of a tile is pulled into as few of the per-XCD L2s as possible.
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int task = xcd * a.tasks_per_xcd + idx;
+    if (task >= a.n_tasks) return;
+    const int tile = task / a.n_wg_rows;
+    const int wg_row = task - tile * a.n_wg_rows;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & (kWave - 1);
+
+    // Column ownership.  Lanes past the tile's share redo the tile's first column (their
+    // loads stay in bounds, their results are dropped).
+    const int vc0 = tile * a.lanes_per_tile;
+    const int vc = vc0 + lane;
+    const bool owns = lane < a.lanes_per_tile && vc < a.n_vec_cols;
+    const int col = (owns ? vc : vc0) * V;
+
+    const gbytes in = (gbytes)a.in;
+    const uint32_t lane_off = (uint32_t)col * (uint32_t)sizeof(T);
+    unsigned tap_ok = 0x1ff;
+    if constexpr (CONV) {
+        // Pixel (oh, ow) = col; bit r*3+s of tap_ok says whether (oh+r-1, ow+s-1) is inside.
+        const int oh = col / a.W, ow = col - oh * a.W;
+        tap_ok = 0;
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const int ih = oh + r - 1, iw = ow + s - 1;
+                if (ih >= 0 && ih < a.H && iw >= 0 && iw < a.W) tap_ok |= 1u << (r * 3 + s);
+            }
+    }
+
+    float acc[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc[j] = 0.0f;
+
+    int slot, p0, p1;
+    const bool split = wg_row < a.n_split;
+    if (split) {
+        slot = wg_row;
+        p0 = a.segments[slot * (kGy + 1) + wave];
+        p1 = a.segments[slot * (kGy + 1) + wave + 1];
+    } else {
+        slot = a.n_split + (wg_row - a.n_split) * kGy + wave;
+        if (slot >= a.M) return;  // whole wave leaves; no barrier follows on this path
+        p0 = a.p_row_ptr[slot];
+        p1 = a.p_row_ptr[slot + 1];
+    }
+
+    if constexpr (CONV) {
+        const int32_t *seg = a.conv_seg + slot * 10;
+        for (int t = 0; t < 9; ++t) {
+            const int q0 = max(p0, seg[t]), q1 = min(p1, seg[t + 1]);
+            if (q0 < q1 && ((tap_ok >> t) & 1u)) walk<T, 1>(a.stream, q0, q1, in, lane_off, acc);
+        }
+    } else {
+        walk<T, V>(a.stream, p0, p1, in, lane_off, acc);
+    }
+
+    if (split) {
+        // Section 3.3: partial tiles of the groups are reduced through shared memory at the
+        // end.  Summed by wave 0 in wave order: deterministic, no atomics.
+        __shared__ float red[kGy][V][kWave];
+#pragma unroll
+        for (int j = 0; j < V; ++j) red[wave][j][lane] = acc[j];
+        __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float s = red[0][j][lane];
+#pragma unroll
+            for (int g = 1; g < kGy; ++g) s += red[g][j][lane];
+            acc[j] = s;
+        }
+    }
+    if (owns) {
+        const int row = a.perm[slot];
+        store_cols<T, V>(static_cast<T *>(a.out) + (size_t)row * a.N + col, acc);
+    }
+}
+
+#define HIP_TRY(call)                                                        \
+    do {                                                                     \
+        hipError_t e_ = (call);                                              \
+        if (e_ != hipSuccess) {                                              \
+            err = std::string(#call) + ": " + hipGetErrorString(e_);         \
+            return e_ == hipErrorOutOfMemory ? SPARSERT_ENOMEM : SPARSERT_EHIP; \
+        }                                                                    \
+    } while (0)
+
+template <typename U>
+static int to_device(const U *src, size_t count, U **dst, std::string &err) {
+    *dst = nullptr;
+    const size_t bytes = (count ? count : 1) * sizeof(U);  // never a zero-sized allocation
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(dst), bytes));
+    if (count) HIP_TRY(hipMemcpy(*dst, src, count * sizeof(U), hipMemcpyHostToDevice));
+    return SPARSERT_OK;
+}
+
+int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err) {
+    HIP_TRY(hipGetDevice(&d.device));
+    if (int rc = to_device(h.p_row_ptr.data(), h.p_row_ptr.size(), &d.p_row_ptr, err)) return rc;
+    if (int rc = to_device(h.perm.data(), h.perm.size(), &d.perm, err)) return rc;
+    if (int rc = to_device(h.stream.data(), h.stream.size(), &d.stream, err)) return rc;
+    if (int rc = to_device(h.segments.data(), h.segments.size(), &d.segments, err)) return rc;
+    if (int rc = to_device(h.conv_seg.data(), h.conv_seg.size(), &d.conv_seg, err)) return rc;
+    return SPARSERT_OK;
+}
+
+void free_device_plan(DevicePlan &d) {
+    if (d.p_row_ptr) (void)hipFree(d.p_row_ptr);
+    if (d.perm) (void)hipFree(d.perm);
+    if (d.stream) (void)hipFree(d.stream);
+    if (d.segments) (void)hipFree(d.segments);
+    if (d.conv_seg) (void)hipFree(d.conv_seg);
+    d = DevicePlan();
+}
+
+template <typename T, int V, bool CONV>
+static int launch_one(const RowsArgs &a, hipStream_t s, std::string &err) {
+    const unsigned grid = (unsigned)a.tasks_per_xcd * 8u;
+    hipLaunchKernelGGL((rows_kernel<T, V, CONV>), dim3(grid), dim3(kGy * kWave), 0, s, a);
+    HIP_TRY(hipGetLastError());
+    return SPARSERT_OK;
+}
+
+int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *out,
+                void *stream, std::string &err) {
+    // Host-side shape checks: the kernel assumes exactly these relations.
+    const int64_t nvc = h.N / h.vec;
+    if (h.vec < 1 || h.N % h.vec || h.gy != kGy || h.lanes_per_tile < 1 || h.lanes_per_tile > kWave ||
+        (int64_t)h.n_tiles * h.lanes_per_tile < nvc || h.n_split < 0 || h.n_split > h.M ||
+        (int64_t)(h.n_tiles - 1) * h.lanes_per_tile >= nvc ||
+        h.n_wg_rows != h.n_split + (h.M - h.n_split + kGy - 1) / kGy) {
+        err = "plan geometry is inconsistent";
+        return SPARSERT_EINVAL;
+    }
+    const int64_t n_tasks = (int64_t)h.n_wg_rows * h.n_tiles;
+    if (n_tasks <= 0 || n_tasks > (1ll << 30)) { err = "too many workgroups"; return SPARSERT_EUNSUPPORTED; }
+    RowsArgs a;
+    a.p_row_ptr = d.p_row_ptr; a.perm = d.perm;
+    a.stream = reinterpret_cast<const uint2 *>(d.stream);
+    a.segments = d.segments; a.conv_seg = d.conv_seg;
+    a.in = in; a.out = out;
+    a.M = h.M; a.N = h.N;
+    a.n_vec_cols = (int32_t)nvc; a.lanes_per_tile = h.lanes_per_tile; a.n_tiles = h.n_tiles;
+    a.n_split = h.n_split; a.n_wg_rows = h.n_wg_rows;
+    a.n_tasks = (int32_t)n_tasks; a.tasks_per_xcd = (int32_t)((n_tasks + 7) / 8);
+    a.H = h.H; a.W = h.W;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool f16 = h.dtype == SPARSERT_F16;
+    if (h.conv) {
+        if (h.vec != 1) { err = "conv plans use vec = 1"; return SPARSERT_EINVAL; }
+        return f16 ? launch_one<_Float16, 1, true>(a, s, err) : launch_one<float, 1, true>(a, s, err);
+    }
+    switch (h.vec) {
+    case 1: return f16 ? launch_one<_Float16, 1, false>(a, s, err) : launch_one<float, 1, false>(a, s, err);
+    case 2: return f16 ? launch_one<_Float16, 2, false>(a, s, err) : launch_one<float, 2, false>(a, s, err);
+    case 4: return f16 ? launch_one<_Float16, 4, false>(a, s, err) : launch_one<float, 4, false>(a, s, err);
+    case 8:
+        if (f16) return launch_one<_Float16, 8, false>(a, s, err);
+        [[fallthrough]];
+    default: err = "unsupported vec for this dtype"; return SPARSERT_EINVAL;
+    }
+}
+
+}  // namespace sparsert

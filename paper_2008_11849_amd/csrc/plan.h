@@ -1,0 +1,59 @@
+// Internal representation of a plan.  Host arrays mirror exactly what
+// sparsert_plan_export hands out; device arrays are what the kernels read.
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/sparsert.h"
+
+namespace sparsert {
+
+constexpr int kWave = 64;       // lanes per wavefront on gfx950
+constexpr int kGy = 4;          // waves per workgroup (one per SIMD of a CU)
+constexpr int kBins = 33;       // bin(0)=0, bin(x)=1+floor(log2 x), x < 2^31
+constexpr int kFullTasks = 2048;  // wave tasks wanted before widening per-lane vectors
+
+struct HostPlan {
+    int32_t M = 0, K = 0, N = 0, nnz = 0;
+    int32_t dtype = 0, conv = 0, Cin = 0, H = 0, W = 0, kernel = 0;
+    int32_t vec = 1, lanes_per_tile = 0, n_tiles = 0, gy = kGy;
+    int32_t split_threshold = 0, n_split = 0, n_wg_rows = 0;
+
+    std::vector<int32_t> row_nnz, hist, perm, inv_perm, p_row_ptr, p_col_idx;
+    std::vector<uint8_t> p_vals;       // nnz * elem_size bytes, bit copies
+    std::vector<int32_t> bins;         // [nbins][4]
+    std::vector<uint32_t> stream;      // [nnz][2]
+    std::vector<int32_t> conv_seg;     // [M][10], conv only
+    std::vector<int32_t> segments;     // [n_split][gy+1]
+
+    int elem_size() const { return dtype == SPARSERT_F16 ? 2 : 4; }
+};
+
+struct DevicePlan {
+    int device = -1;
+    int32_t *p_row_ptr = nullptr;
+    int32_t *perm = nullptr;
+    uint32_t *stream = nullptr;
+    int32_t *conv_seg = nullptr;
+    int32_t *segments = nullptr;
+};
+
+// Host analysis.  Returns SPARSERT_OK or an error code with `err` filled in.
+int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
+                    int32_t M, int32_t K, int32_t N, const sparsert_options &opt,
+                    HostPlan &out, std::string &err);
+
+// Device side (kernels.hip).
+int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err);
+void free_device_plan(DevicePlan &d);
+int launch_rows(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
+                void *stream, std::string &err);
+
+}  // namespace sparsert
+
+struct sparsert_plan {
+    sparsert::HostPlan host;
+    sparsert::DevicePlan dev;
+    bool on_device = false;
+};

@@ -1,0 +1,155 @@
+"""Thin ctypes binding over libsparsert.so: argument marshalling only.
+
+Every step of the hot path runs inside the library's HIP kernels.  There is no
+fallback: if the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsparsert.so")
+
+OK, EINVAL, ENOMEM, EHIP, EUNSUPPORTED, ECOMPILE = 0, -1, -2, -3, -4, -5
+F32, F16 = 0, 1
+KERNEL_AUTO, KERNEL_ROWS, KERNEL_SPEC = 0, 1, 2
+(FIELD_INFO, FIELD_ROW_NNZ, FIELD_HIST, FIELD_PERM, FIELD_INV_PERM, FIELD_P_ROW_PTR,
+ FIELD_P_COL_IDX, FIELD_P_VALS, FIELD_BINS, FIELD_STREAM, FIELD_CONV_SEG,
+ FIELD_SEGMENTS) = range(12)
+INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", "vec",
+              "lanes_per_tile", "n_tiles", "gy", "split_threshold", "n_split", "n_wg_rows",
+              "n_bins"]
+INFO_COUNT = 24
+
+EXPORTED = ["sparsert_inspect", "sparsert_spmm", "sparsert_conv3x3", "sparsert_plan_export",
+            "sparsert_plan_destroy", "sparsert_last_error", "sparsert_version"]
+
+
+class Options(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("kernel", ctypes.c_int32), ("conv", ctypes.c_int32),
+                ("Cin", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
+                ("batch", ctypes.c_int32), ("host_only", ctypes.c_int32),
+                ("vec", ctypes.c_int32), ("split_threshold", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 6)]
+
+
+class SparseRTError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"sparsert status {status}: {message}")
+        self.status = status
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` to build the HIP library")
+
+_lib = ctypes.CDLL(LIB_PATH)
+_vp, _i32 = ctypes.c_void_p, ctypes.c_int32
+_lib.sparsert_inspect.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, ctypes.POINTER(Options),
+                                  ctypes.POINTER(_vp)]
+_lib.sparsert_inspect.restype = ctypes.c_int
+_lib.sparsert_spmm.argtypes = [_vp, _vp, _vp, _vp]
+_lib.sparsert_spmm.restype = ctypes.c_int
+_lib.sparsert_conv3x3.argtypes = [_vp, _vp, _vp, _vp]
+_lib.sparsert_conv3x3.restype = ctypes.c_int
+_lib.sparsert_plan_export.argtypes = [_vp, _i32, _vp, ctypes.c_size_t,
+                                      ctypes.POINTER(ctypes.c_size_t)]
+_lib.sparsert_plan_export.restype = ctypes.c_int
+_lib.sparsert_plan_destroy.argtypes = [_vp]
+_lib.sparsert_plan_destroy.restype = None
+_lib.sparsert_last_error.restype = ctypes.c_char_p
+_lib.sparsert_version.restype = _i32
+
+
+def last_error() -> str:
+    return _lib.sparsert_last_error().decode()
+
+
+def version() -> int:
+    return int(_lib.sparsert_version())
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise SparseRTError(rc, last_error())
+
+
+_FIELD_DTYPE = {FIELD_STREAM: np.uint32}
+
+
+class Plan:
+    """Owner of a sparsert_plan handle."""
+
+    def __init__(self, handle: int, dtype: int):
+        self.handle = handle
+        self.dtype = dtype
+
+    def export(self, field: int) -> np.ndarray:
+        need = ctypes.c_size_t(0)
+        _check(_lib.sparsert_plan_export(self.handle, field, None, 0, ctypes.byref(need)))
+        if field == FIELD_P_VALS:
+            dt = np.float16 if self.dtype == F16 else np.float32
+        else:
+            dt = _FIELD_DTYPE.get(field, np.int32)
+        out = np.empty(need.value // np.dtype(dt).itemsize, dtype=dt)
+        _check(_lib.sparsert_plan_export(self.handle, field, out.ctypes.data_as(_vp),
+                                         out.nbytes, None))
+        return out
+
+    def info(self) -> dict:
+        raw = self.export(FIELD_INFO)
+        return {k: int(raw[i]) for i, k in enumerate(INFO_NAMES)}
+
+    def destroy(self):
+        if self.handle:
+            _lib.sparsert_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[int] = None,
+            conv: Optional[Tuple[int, int, int]] = None, batch: int = 0, host_only: bool = False,
+            vec: int = 0, split_threshold: int = 0, kernel: int = KERNEL_AUTO) -> Plan:
+    """sparsert_inspect.  `vals` must already be float32 or float16; it is not converted."""
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals)
+    if dtype is None:
+        if vals.dtype == np.float16:
+            dtype = F16
+        elif vals.dtype == np.float32:
+            dtype = F32
+        else:
+            raise TypeError("vals must be float32 or float16")
+    opt = Options()
+    opt.dtype, opt.kernel, opt.host_only = dtype, kernel, int(host_only)
+    opt.vec, opt.split_threshold, opt.batch = vec, split_threshold, batch
+    if conv is not None:
+        opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
+    handle = _vp()
+    _check(_lib.sparsert_inspect(row_ptr.ctypes.data_as(_vp), col_idx.ctypes.data_as(_vp),
+                                 vals.ctypes.data_as(_vp), M, K, N, ctypes.byref(opt),
+                                 ctypes.byref(handle)))
+    return Plan(handle.value, dtype)
+
+
+def spmm(plan: Plan, B_dev: int, C_dev: int, stream: int = 0):
+    """sparsert_spmm: device addresses and a hipStream_t as integers."""
+    _check(_lib.sparsert_spmm(plan.handle, B_dev, C_dev, stream))
+
+
+def conv3x3(plan: Plan, X_dev: int, Y_dev: int, stream: int = 0):
+    """sparsert_conv3x3: device addresses and a hipStream_t as integers."""
+    _check(_lib.sparsert_conv3x3(plan.handle, X_dev, Y_dev, stream))
+
+
+# Raw entry points for callers that time launches without Python argument handling.
+raw = _lib

@@ -1,0 +1,58 @@
+"""Helpers for the GPU parity tests: device buffers through torch, calls through the C ABI."""
+import numpy as np
+import torch
+
+from oracle import ref
+from paper_2008_11849_amd import sparsert as sp
+
+TOL = {np.dtype(np.float32): 1e-4, np.dtype(np.float16): 2e-2}
+
+
+def _tdtype(dt):
+    return torch.float16 if np.dtype(dt) == np.float16 else torch.float32
+
+
+def run_spmm(csr, B, **opts):
+    dev = torch.device("cuda:0")
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, B.shape[1], **opts)
+    Bd = torch.from_numpy(np.ascontiguousarray(B)).to(dev)
+    # poison the output so unwritten elements are caught
+    Cd = torch.full((csr.M, B.shape[1]), float("nan"), dtype=_tdtype(B.dtype), device=dev)
+    sp.spmm(plan, Bd.data_ptr(), Cd.data_ptr(), torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    out = Cd.cpu().numpy()
+    info = plan.info()
+    plan.destroy()
+    return out, info
+
+
+def run_conv(csr, X, Cout, **opts):
+    dev = torch.device("cuda:0")
+    _, Cin, H, W = X.shape
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, Cout, 9 * Cin, H * W,
+                      conv=(Cin, H, W), **opts)
+    Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
+    Yd = torch.full((1, Cout, H, W), float("nan"), dtype=_tdtype(X.dtype), device=dev)
+    sp.conv3x3(plan, Xd.data_ptr(), Yd.data_ptr(), torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    out = Yd.cpu().numpy()
+    info = plan.info()
+    plan.destroy()
+    return out, info
+
+
+def check(got, ref_c, scale, dtype, gate_relative=False):
+    """Error figures must be under the tolerance of the storage type: max relative error
+    1e-4 for fp32, 2e-2 for fp16 (fp32 accumulation).  The componentwise and normwise
+    figures gate every case; the plain element-wise relative error (entries above 1e-2 rms)
+    gates the named configurations only, since with several hundred terms per output even a
+    correctly rounded sequential fp32 sum reaches 1e-4 on entries that nearly cancel."""
+    tol = TOL[np.dtype(dtype)]
+    assert not np.isnan(got).any(), "unwritten or NaN outputs"
+    m = ref.error_metrics(got, ref_c, scale)
+    assert m["exact_on_zero_scale"], m
+    assert m["componentwise"] <= tol, m
+    assert m["normwise"] <= tol, m
+    if gate_relative:
+        assert m["relative"] <= tol, m
+    return m

@@ -1,0 +1,191 @@
+"""Host-side tests: the C-ABI library loads and exports what include/sparsert.h declares,
+argument validation returns error codes, and the exported plan equals the NumPy statement
+of the plan specification byte for byte.  No GPU is touched (host_only plans)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import plan_ref
+from paper_2008_11849_amd import sparsert as sp
+from paper_2008_11849_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+FIELDS = {"row_nnz": sp.FIELD_ROW_NNZ, "hist": sp.FIELD_HIST, "perm": sp.FIELD_PERM,
+          "inv_perm": sp.FIELD_INV_PERM, "p_row_ptr": sp.FIELD_P_ROW_PTR,
+          "p_col_idx": sp.FIELD_P_COL_IDX, "p_vals": sp.FIELD_P_VALS, "bins": sp.FIELD_BINS,
+          "stream": sp.FIELD_STREAM, "conv_seg": sp.FIELD_CONV_SEG,
+          "segments": sp.FIELD_SEGMENTS}
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sparsert.h")).read()
+    declared = set(re.findall(r"\b(sparsert_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(sp.EXPORTED)
+    lib = ctypes.CDLL(sp.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sp.version() >= 100
+
+
+def test_options_struct_matches_header_layout():
+    assert ctypes.sizeof(sp.Options) == 16 * 4
+
+
+def _host_plan(csr, N, **kw):
+    return sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, host_only=True, **kw)
+
+
+def _assert_plan_equal(plan, refp):
+    info = plan.info()
+    for k, v in refp["info"].items():
+        assert info[k] == v, (k, info[k], v)
+    for name, fid in FIELDS.items():
+        got, want = plan.export(fid), refp[name]
+        assert got.dtype == want.dtype, name
+        assert got.tobytes() == want.tobytes(), name
+
+
+CASES = [
+    ("uniform", 64, 48, 100, 0.9, np.float32),
+    ("uniform", 33, 17, 49, 0.5, np.float32),
+    ("uniform", 256, 256, 1024, 0.9, np.float32),
+    ("magnitude", 512, 512, 196, 0.9, np.float32),
+    ("skewed", 300, 700, 64, 0.9, np.float32),
+    ("skewed", 256, 2048, 784, 0.98, np.float16),
+    ("uniform", 128, 96, 3136, 0.8, np.float16),
+    ("uniform", 1, 1, 1, 0.0, np.float32),
+]
+
+
+@pytest.mark.parametrize("kind,M,K,N,sp_,dt", CASES)
+def test_plan_is_bit_exact_against_numpy_spec(kind, M, K, N, sp_, dt):
+    csr = {"uniform": synth.uniform_csr, "skewed": synth.skewed_csr,
+           "magnitude": lambda *a, **k: synth.magnitude_csr(a[0], a[1], a[2], a[3], 1.0, **k)}[kind](
+        M, K, sp_, 7, dtype=dt)
+    plan = _host_plan(csr, N)
+    _assert_plan_equal(plan, plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, M, K, N))
+    plan.destroy()
+
+
+@pytest.mark.parametrize("vec,thr", [(1, 1), (2, 8), (4, 100000)])
+def test_plan_overrides(vec, thr):
+    csr = synth.skewed_csr(100, 200, 0.8, 3)
+    plan = _host_plan(csr, 64, vec=vec, split_threshold=thr)
+    _assert_plan_equal(plan, plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, 100, 200, 64,
+                                           vec=vec, split_threshold=thr))
+
+
+@pytest.mark.parametrize("Cin,Cout,H,W,dt", [(5, 7, 6, 9, np.float32), (16, 24, 14, 14, np.float16),
+                                            (64, 64, 7, 7, np.float32)])
+def test_conv_plan_is_bit_exact(Cin, Cout, H, W, dt):
+    csr, _ = synth.conv_weights_csr(Cout, Cin, 0.8, 11, dtype=dt)
+    plan = _host_plan(csr, H * W, conv=(Cin, H, W))
+    _assert_plan_equal(plan, plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, Cout, 9 * Cin, H * W,
+                                           conv=(Cin, H, W)))
+
+
+def test_plan_invariants_and_round_trip():
+    csr = synth.skewed_csr(257, 300, 0.95, 5)
+    # plant special bit patterns: they must come back untouched
+    bits = csr.vals.view(np.uint32)
+    bits[0], bits[1], bits[2] = 0x80000000, 0x7FC12345, 0x00000000  # -0.0, NaN payload, +0.0
+    plan = _host_plan(csr, 128)
+    perm, inv = plan.export(sp.FIELD_PERM), plan.export(sp.FIELD_INV_PERM)
+    assert sorted(perm.tolist()) == list(range(257))
+    assert np.array_equal(inv[perm], np.arange(257))
+    prp, pci = plan.export(sp.FIELD_P_ROW_PTR), plan.export(sp.FIELD_P_COL_IDX)
+    pv = plan.export(sp.FIELD_P_VALS)
+    nn = np.diff(prp)
+    assert np.all(nn[:-1] >= nn[1:])  # descending nnz
+    bins = plan.export(sp.FIELD_BINS).reshape(-1, 4)
+    assert bins[:, 2].sum() == 257 and bins[:, 3].sum() == csr.nnz
+    assert np.array_equal(bins[:, 1], np.concatenate([[0], np.cumsum(bins[:, 2])[:-1]]))
+    assert plan.export(sp.FIELD_HIST).sum() == 257
+    # un-permuting reproduces the input CSR byte for byte
+    rp = np.zeros(258, dtype=np.int32)
+    rp[1:] = np.cumsum(nn[inv])
+    assert rp.tobytes() == csr.row_ptr.tobytes()
+    cols = np.concatenate([pci[prp[inv[m]]:prp[inv[m] + 1]] for m in range(257)])
+    vals = np.concatenate([pv[prp[inv[m]]:prp[inv[m] + 1]] for m in range(257)])
+    assert cols.tobytes() == csr.col_idx.tobytes()
+    assert vals.tobytes() == csr.vals.tobytes()
+    # split segments: every wave but the last gets the same share (Section 3.4)
+    info = plan.info()
+    seg = plan.export(sp.FIELD_SEGMENTS).reshape(info["n_split"], info["gy"] + 1)
+    for s in range(info["n_split"]):
+        assert seg[s, 0] == prp[s] and seg[s, -1] == prp[s + 1]
+        d = np.diff(seg[s])
+        assert np.all(d[:-1] == d[0]) or np.all(np.diff(d) <= 0)
+        assert np.all(d >= 0)
+
+
+def test_tiling_example_shares(golden):
+    # Section 3.3 worked example: an extent divided into equal parts; the plan's
+    # per-wave share of a split row uses the same ceil-division.
+    for extent, parts, share in golden("tiling_example.txt")["split"].astype(int):
+        assert -(-extent // parts) == share
+    rp = np.array([0, 3056], dtype=np.int32)
+    cols = np.arange(3056, dtype=np.int32)
+    plan = sp.inspect(rp, cols, np.ones(3056, np.float32), 1, 3056, 512, host_only=True)
+    seg = plan.export(sp.FIELD_SEGMENTS)
+    assert np.array_equal(np.diff(seg), [764] * 4)  # 3056 / 4 waves
+
+
+def _inspect_rc(row_ptr, col_idx, vals, M, K, N, **kw):
+    try:
+        sp.inspect(row_ptr, col_idx, vals, M, K, N, host_only=True, **kw).destroy()
+        return 0
+    except sp.SparseRTError as e:
+        assert str(e)
+        return e.status
+
+
+def test_validation_errors():
+    rp = np.array([0, 2, 3], dtype=np.int32)
+    ci = np.array([0, 2, 1], dtype=np.int32)
+    v = np.ones(3, dtype=np.float32)
+    assert _inspect_rc(rp, ci, v, 2, 3, 8) == 0
+    assert _inspect_rc(rp, ci, v, 0, 3, 8) == sp.EINVAL
+    assert _inspect_rc(rp, ci, v, 2, 3, 0) == sp.EINVAL
+    assert _inspect_rc(np.array([1, 2, 3], np.int32), ci, v, 2, 3, 8) == sp.EINVAL  # row_ptr[0]
+    assert _inspect_rc(np.array([0, 3, 2], np.int32), ci, v, 2, 3, 8) == sp.EINVAL  # decreasing
+    assert _inspect_rc(rp, np.array([0, 3, 1], np.int32), v, 2, 3, 8) == sp.EINVAL  # col >= K
+    assert _inspect_rc(rp, np.array([0, -1, 1], np.int32), v, 2, 3, 8) == sp.EINVAL
+    assert _inspect_rc(rp, np.array([2, 0, 1], np.int32), v, 2, 3, 8) == sp.EINVAL  # unsorted
+    assert _inspect_rc(rp, np.array([1, 1, 1], np.int32), v, 2, 3, 8) == sp.EINVAL  # duplicate
+    assert _inspect_rc(rp, ci, v, 2, 3, 8, vec=3) == sp.EINVAL
+    assert _inspect_rc(rp, ci, v, 2, 3, 9, vec=2) == sp.EINVAL
+    assert _inspect_rc(rp, ci, v, 2, 3, 8, vec=8) == sp.EINVAL  # 8 is f16 only
+    assert _inspect_rc(rp, ci, v, 2, 3, 8, dtype=7) == sp.EINVAL
+    assert _inspect_rc(rp, ci, v, 2, 3, 8, conv=(1, 2, 4)) == sp.EINVAL  # K != 9*Cin
+    assert _inspect_rc(rp, ci, v, 2, 9, 8, conv=(1, 2, 4)) == 0
+    assert _inspect_rc(rp, ci, v, 2, 9, 8, conv=(1, 2, 4), batch=2) == sp.EUNSUPPORTED
+    assert _inspect_rc(rp, ci, v, 2, 9, 7, conv=(1, 2, 4)) == sp.EINVAL  # N != H*W
+    assert _inspect_rc(rp, ci, v, 2, 70000, 70000) == sp.EUNSUPPORTED  # >= 2 GiB operands
+
+
+def test_null_pointers_and_host_only_execution_are_rejected():
+    lib = sp.raw
+    out = ctypes.c_void_p(123)
+    assert lib.sparsert_inspect(None, None, None, 1, 1, 1, None, ctypes.byref(out)) == sp.EINVAL
+    assert out.value is None
+    assert lib.sparsert_inspect(None, None, None, 1, 1, 1, None, None) == sp.EINVAL
+    assert lib.sparsert_spmm(None, 16, 16, None) == sp.EINVAL
+    csr = synth.uniform_csr(8, 8, 0.5, 1)
+    plan = _host_plan(csr, 8)
+    assert lib.sparsert_spmm(plan.handle, 4096, 8192, None) == sp.EINVAL  # host-only plan
+    assert "host_only" in sp.last_error()
+    assert lib.sparsert_spmm(plan.handle, 4097, 8192, None) == sp.EINVAL  # misaligned
+    assert lib.sparsert_spmm(plan.handle, None, 8192, None) == sp.EINVAL
+    assert lib.sparsert_conv3x3(plan.handle, 4096, 8192, None) == sp.EINVAL
+    need = ctypes.c_size_t()
+    assert lib.sparsert_plan_export(plan.handle, 99, None, 0, ctypes.byref(need)) == sp.EINVAL
+    assert lib.sparsert_plan_export(plan.handle, sp.FIELD_PERM, None, 0, ctypes.byref(need)) == 0
+    assert need.value == 32
+    buf = (ctypes.c_int32 * 4)()
+    assert lib.sparsert_plan_export(plan.handle, sp.FIELD_PERM, buf, 16, None) == sp.EINVAL
+    lib.sparsert_plan_destroy(None)
