@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpMM / sparse-conv hot path on one MI355X.
+
+A "step" is one pass of the hot path over one batch of synthetic input for the chosen
+workload.  Default workload c3 = the Transformer FC pair at 95 % sparsity: the 3072x768
+projection and its transposed 768x3072 partner, both against N = 1024 activation columns
+(batch 8 x 128 tokens).  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: effective GFLOP/s (2*nnz*N / time), the speedup over a dense GEMM of
+the same shape on the same GPU, the roofline position of the dominant kernel (timed live
+with HIP events on the launch stream) and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+FP32_VECTOR_PEAK_TF = 157.3  # MI355X vector fp32
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--dtype", default="f32", choices=["f32", "f16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cases", action="store_true", help="skip the side table of the other configs")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "rows", "spec"])
+    return ap.parse_args()
+
+
+class Layer:
+    """One sparse layer resident on the GPU: plan, input, output and its dense twin."""
+
+    def __init__(self, case, torch, sp, kernel=0):
+        import numpy as np
+        self.case, self.torch, self.sp = case, torch, sp
+        csr = case.csr
+        dev = torch.device("cuda:0")
+        self.is_conv = case.conv is not None
+        self.M, self.K, self.N, self.nnz = csr.M, csr.K, case.N, csr.nnz
+        self.plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N,
+                               conv=case.conv, kernel=kernel)
+        self.info = self.plan.info()
+        tdt = torch.float16 if csr.vals.dtype == np.float16 else torch.float32
+        self.esize = 2 if tdt == torch.float16 else 4
+        if self.is_conv:
+            self.inp = torch.from_numpy(case.X).to(dev)
+            self.out = torch.empty((1, csr.M, case.conv[1], case.conv[2]), dtype=tdt, device=dev)
+            self.Wd = torch.from_numpy(case.Wdense).to(dev)
+            self.fn = sp.raw.sparsert_conv3x3
+        else:
+            self.inp = torch.from_numpy(case.B).to(dev)
+            self.out = torch.empty((csr.M, case.N), dtype=tdt, device=dev)
+            self.Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
+            self.fn = sp.raw.sparsert_spmm
+        self.args = (ctypes.c_void_p(self.plan.handle), ctypes.c_void_p(self.inp.data_ptr()),
+                     ctypes.c_void_p(self.out.data_ptr()))
+
+    @property
+    def flops(self):
+        return 2.0 * self.nnz * self.N
+
+    @property
+    def algorithmic_bytes(self):
+        """Compulsory HBM traffic of one launch: the dense operand read once, the output
+        written once, the nonzero stream (8 B per nonzero) and the row pointers read once."""
+        e = self.esize
+        dense_in = (self.case.conv[0] * self.N if self.is_conv else self.K * self.N) * e
+        return dense_in + self.M * self.N * e + 8 * self.nnz + 4 * (self.M + 1)
+
+    def launch(self, stream):
+        rc = self.fn(self.args[0], self.args[1], self.args[2], stream)
+        if rc != 0:
+            raise RuntimeError(self.sp.last_error())
+
+    def dense(self):
+        if self.is_conv:
+            return self.torch.nn.functional.conv2d(self.inp, self.Wd, padding=1)
+        return self.torch.matmul(self.Ad, self.inp)
+
+
+def time_loop(torch, fn, iters, warmup):
+    """Average milliseconds per call of fn, HIP events on torch's current stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def load_traffic(kernel_tag):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(cases):
+    """The CPU oracle as it stands, on the host cores, on the same workload (best of 3)."""
+    from oracle import ref
+    threads = min(ref.max_threads(), len(os.sched_getaffinity(0)))
+    best, flops = float("inf"), 0.0
+    for rep in range(3):
+        t0 = time.perf_counter()
+        flops = 0.0
+        for case in cases:
+            csr = case.csr
+            if case.conv is not None:
+                ref.conv3x3(case.Wdense, case.X, want_scale=False, threads=threads)
+            else:
+                ref.spmm(csr.M, csr.K, case.N, csr.row_ptr, csr.col_idx, csr.vals, case.B,
+                         want_scale=False, threads=threads)
+            flops += 2.0 * csr.nnz * case.N
+        best = min(best, time.perf_counter() - t0)
+    return {"value": flops / best / 1e9, "unit": "GFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "the whole step (every layer of the workload, all rows), float64 oracle, "
+                      "best of 3 passes, %.3f s per pass" % best}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second GPU",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2008_11849_amd import sparsert as sp, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.backends.cuda.matmul.allow_tf32 = False
+    torch.backends.cudnn.allow_tf32 = False
+    dt = np.float16 if args.dtype == "f16" else np.float32
+    kernel = {"auto": 0, "rows": 1, "spec": 2}[args.kernel]
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    names = {"c1": ["c1"], "c2": ["c2"], "c3": ["c3", "c3t"], "c4": ["c4"]}[args.workload]
+    cases = [synth.config(n, dt) for n in names]
+    layers = [Layer(c, torch, sp, kernel) for c in cases]
+
+    def step():
+        for L in layers:
+            L.launch(stream)
+
+    # ---- the timed region: exactly --steps steps between two synchronisations
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    flops_step = sum(L.flops for L in layers)
+
+    # ---- per-kernel durations, live, HIP events on the launch stream
+    iters = max(200, min(args.steps, 2000))
+    per_layer = []
+    for L in layers:
+        ms = time_loop(torch, lambda L=L: L.launch(stream), iters, 50)
+        ms_dense = time_loop(torch, L.dense, max(50, iters // 10), 10)
+        per_layer.append({"layer": L.case.name, "M": L.M, "K": L.K, "N": L.N, "nnz": L.nnz,
+                          "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
+                          "dense_us": ms_dense * 1e3, "speedup_vs_dense": ms_dense / ms,
+                          "vec": L.info["vec"], "n_split": L.info["n_split"]})
+    kernel_ms = sum(p["us"] for p in per_layer) / 1e3 / len(layers)       # average launch
+    alg_bytes = sum(L.algorithmic_bytes for L in layers) / len(layers)    # average launch
+    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    dense_ms = sum(p["dense_us"] for p in per_layer) / 1e3
+    sparse_ms = sum(p["us"] for p in per_layer) / 1e3
+    tag = f"rows_kernel_{args.workload}_{args.dtype}"
+    out = {
+        "metric": "effective GFLOP/s (2*nnz*N)",
+        "value": flops_step / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": {
+            "c1": "c1: 256x256 @ 90% uniform, N=1024",
+            "c2": "c2: MobileNet-like 1x1 conv 512x512 @ 90% magnitude-pruned, N=196",
+            "c3": "c3: Transformer FC 3072x768 and transposed 768x3072 @ 95% magnitude-pruned, N=1024",
+            "c4": "c4: 3x3 conv 256->256 @ 90%, 14x14, pad 1, implicit im2col"}[args.workload],
+            "layers_per_step": len(layers), "kernel": args.kernel},
+        "speedup_vs_dense": dense_ms / sparse_ms,
+        "dense_ms_per_step": dense_ms,
+        "kernel_ms_per_step": sparse_ms,
+        "layers": per_layer,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(tag),
+                     "kernel": "sparsert::rows_kernel", "avg_launch_us": kernel_ms * 1e3,
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "alu_frac_of_fp32_vector_peak":
+                         flops_step / len(layers) / (kernel_ms * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TF},
+    }
+
+    if not args.no_cases:
+        side = []
+        for n in ["c1", "c2", "c3", "c3t", "c4"]:
+            if n in names:
+                continue
+            L = Layer(synth.config(n, dt), torch, sp, kernel)
+            ms = time_loop(torch, lambda L=L: L.launch(stream), 500, 50)
+            msd = time_loop(torch, L.dense, 100, 10)
+            side.append({"layer": n, "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
+                         "dense_us": msd * 1e3, "speedup_vs_dense": msd / ms})
+            L.plan.destroy()
+        out["other_configs"] = side
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cases)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -43,6 +43,15 @@ class SparseRTError(RuntimeError):
         self.status = status
 
 
+# Load torch's HIP runtime first when torch is present: the library asks for
+# libamdhip64.so.7 by soname, and a process must not end up with two HIP runtimes
+# (the second one finds no device).  torch itself is used by callers for device
+# memory and streams only.
+try:
+    import torch  # noqa: F401
+except ImportError:  # pure ctypes / C callers use the system runtime
+    torch = None
+
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` to build the HIP library")
 
