@@ -35,7 +35,7 @@ typedef enum sparsert_status {
     SPARSERT_ENOMEM = -2,       /* host or device allocation failed */
     SPARSERT_EHIP = -3,         /* a HIP runtime call or kernel launch failed */
     SPARSERT_EUNSUPPORTED = -4, /* legal request outside what is implemented */
-    SPARSERT_ECOMPILE = -5      /* run-time compilation of a specialised kernel failed */
+    SPARSERT_ECOMPILE = -5      /* assembling or loading a generated kernel failed */
 } sparsert_status;
 
 /* Storage type of vals, B/X and C/Y.  Accumulation is always IEEE binary32;
@@ -47,7 +47,8 @@ typedef enum sparsert_dtype { SPARSERT_F32 = 0, SPARSERT_F16 = 1 } sparsert_dtyp
 typedef enum sparsert_kernel {
     SPARSERT_KERNEL_AUTO = 0,
     SPARSERT_KERNEL_ROWS = 1,  /* one wave per row, B read straight from L2/HBM */
-    SPARSERT_KERNEL_SPEC = 2   /* per-matrix generated code (Section 3.5), via hiprtc */
+    SPARSERT_KERNEL_SPEC = 2   /* per-matrix generated gfx950 code with the nonzeros of A as
+                                  instruction constants (Section 3.5); fp32 SpMM only */
 } sparsert_kernel;
 
 /* Zero-initialise, then set what you need.  All-zero = fp32 SpMM, automatic tiling. */
@@ -62,7 +63,9 @@ typedef struct sparsert_options {
     int32_t vec;             /* columns of C per lane; 0 = automatic, else 1,2,4 (,8 for f16) */
     int32_t split_threshold; /* rows with at least this many nonzeros are split over the
                                 waves of a workgroup; 0 = automatic */
-    int32_t reserved[6];     /* must be zero */
+    int32_t spec_rows;       /* SPARSERT_KERNEL_SPEC: rows of A per generated code block
+                                (accumulator registers per wave); 0 = automatic */
+    int32_t reserved[5];     /* must be zero */
 } sparsert_options;
 
 /*
@@ -142,8 +145,11 @@ typedef enum sparsert_field {
                                      (may be negative), each slot ordered by (r*3+s, c) */
     SPARSERT_FIELD_CONV_SEG = 10, /* conv only, int32[M][10]: stream positions where each
                                      (r,s) group of a slot starts; [9] = end of the slot */
-    SPARSERT_FIELD_SEGMENTS = 11  /* int32[n_split][Gy+1]: stream positions bounding the
+    SPARSERT_FIELD_SEGMENTS = 11, /* int32[n_split][Gy+1]: stream positions bounding the
                                      share of each wave of a split row */
+    SPARSERT_FIELD_SPEC_GROUPS = 12, /* SPEC plans, int32[M]: code block (row group) of each slot */
+    SPARSERT_FIELD_SPEC_COLUMNS = 13, /* SPEC plans, int32[groups]: B rows a block loads per tile */
+    SPARSERT_FIELD_SPEC_CODE = 14 /* SPEC plans, bytes: the generated gfx950 code object */
 } sparsert_field;
 
 enum {
@@ -158,6 +164,10 @@ enum {
     SPARSERT_INFO_N_SPLIT,        /* slots [0, N_SPLIT) are split rows */
     SPARSERT_INFO_N_WG_ROWS,      /* workgroups along M: N_SPLIT + ceil((M-N_SPLIT)/GY) */
     SPARSERT_INFO_N_BINS,
+    SPARSERT_INFO_SPEC_ROWS,      /* SPEC plans: rows per code block */
+    SPARSERT_INFO_SPEC_GROUPS,    /* SPEC plans: number of code blocks */
+    SPARSERT_INFO_SPEC_DEPTH,     /* SPEC plans: B rows in flight per wave */
+    SPARSERT_INFO_SPEC_CODE_BYTES,
     SPARSERT_INFO_COUNT = 24      /* remaining entries are zero */
 };
 

@@ -28,6 +28,13 @@ int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void 
     } catch (const std::bad_alloc &) {
         rc = SPARSERT_ENOMEM; err = "out of host memory";
     }
+    if (rc == SPARSERT_OK && plan->host.kernel == SPARSERT_KERNEL_SPEC) {
+        try {
+            rc = sparsert::build_spec_plan(plan->host, o, err);
+        } catch (const std::bad_alloc &) {
+            rc = SPARSERT_ENOMEM; err = "out of host memory";
+        }
+    }
     if (rc == SPARSERT_OK && !o.host_only) {
         rc = sparsert::upload_plan(plan->host, plan->dev, err);
         plan->on_device = (rc == SPARSERT_OK);
@@ -54,7 +61,9 @@ static int check_exec(const sparsert_plan *plan, const void *in, void *outp, boo
 int sparsert_spmm(const sparsert_plan *plan, const void *B_dev, void *C_dev, void *stream) {
     if (int rc = check_exec(plan, B_dev, C_dev, false)) return rc;
     std::string err;
-    int rc = sparsert::launch_rows(plan->host, plan->dev, B_dev, C_dev, stream, err);
+    int rc = plan->host.kernel == SPARSERT_KERNEL_SPEC
+                 ? sparsert::launch_spec(plan->host, plan->dev, B_dev, C_dev, stream, err)
+                 : sparsert::launch_rows(plan->host, plan->dev, B_dev, C_dev, stream, err);
     return rc == SPARSERT_OK ? rc : fail(rc, err);
 }
 
@@ -84,6 +93,10 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
         info[SPARSERT_INFO_SPLIT_THRESHOLD] = h.split_threshold;
         info[SPARSERT_INFO_N_SPLIT] = h.n_split; info[SPARSERT_INFO_N_WG_ROWS] = h.n_wg_rows;
         info[SPARSERT_INFO_N_BINS] = (int32_t)(h.bins.size() / 4);
+        info[SPARSERT_INFO_SPEC_ROWS] = h.spec.rows_per_group;
+        info[SPARSERT_INFO_SPEC_GROUPS] = h.spec.n_groups;
+        info[SPARSERT_INFO_SPEC_DEPTH] = h.spec.depth;
+        info[SPARSERT_INFO_SPEC_CODE_BYTES] = (int32_t)h.spec.code.size();
         src = info; bytes = sizeof(info);
         break;
     case SPARSERT_FIELD_ROW_NNZ: vec32(h.row_nnz); break;
@@ -97,6 +110,9 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
     case SPARSERT_FIELD_STREAM: src = h.stream.data(); bytes = h.stream.size() * 4; break;
     case SPARSERT_FIELD_CONV_SEG: vec32(h.conv_seg); break;
     case SPARSERT_FIELD_SEGMENTS: vec32(h.segments); break;
+    case SPARSERT_FIELD_SPEC_GROUPS: vec32(h.spec.group_of_slot); break;
+    case SPARSERT_FIELD_SPEC_COLUMNS: vec32(h.spec.group_columns); break;
+    case SPARSERT_FIELD_SPEC_CODE: src = h.spec.code.data(); bytes = h.spec.code.size(); break;
     default: return fail(SPARSERT_EINVAL, "unknown plan field");
     }
     if (need) *need = bytes;

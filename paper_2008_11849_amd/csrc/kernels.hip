@@ -204,6 +204,16 @@ int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err) {
     if (int rc = to_device(h.stream.data(), h.stream.size(), &d.stream, err)) return rc;
     if (int rc = to_device(h.segments.data(), h.segments.size(), &d.segments, err)) return rc;
     if (int rc = to_device(h.conv_seg.data(), h.conv_seg.size(), &d.conv_seg, err)) return rc;
+    if (h.kernel == SPARSERT_KERNEL_SPEC) {
+        hipModule_t mod = nullptr;
+        hipFunction_t fn = nullptr;
+        hipError_t e1 = hipModuleLoadData(&mod, h.spec.code.data());
+        if (e1 != hipSuccess) { err = std::string("loading the generated kernel: ") + hipGetErrorString(e1); return SPARSERT_ECOMPILE; }
+        d.spec_module = mod;
+        hipError_t e2 = hipModuleGetFunction(&fn, mod, "sparsert_spec");
+        if (e2 != hipSuccess) { err = std::string("generated kernel symbol: ") + hipGetErrorString(e2); return SPARSERT_ECOMPILE; }
+        d.spec_function = fn;
+    }
     return SPARSERT_OK;
 }
 
@@ -213,6 +223,7 @@ void free_device_plan(DevicePlan &d) {
     if (d.stream) (void)hipFree(d.stream);
     if (d.segments) (void)hipFree(d.segments);
     if (d.conv_seg) (void)hipFree(d.conv_seg);
+    if (d.spec_module) (void)hipModuleUnload(static_cast<hipModule_t>(d.spec_module));
     d = DevicePlan();
 }
 
@@ -262,6 +273,23 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
         [[fallthrough]];
     default: err = "unsupported vec for this dtype"; return SPARSERT_EINVAL;
     }
+}
+
+int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
+                void *stream, std::string &err) {
+    const SpecPlan &sp = h.spec;
+    if (!d.spec_function || sp.n_groups < 1 || sp.n_tiles < 1 || h.conv || h.dtype != SPARSERT_F32) {
+        err = "plan has no generated kernel";
+        return SPARSERT_EINVAL;
+    }
+    struct { const void *B; void *C; } args = {B, C};
+    size_t size = sizeof(args);
+    void *config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, &args, HIP_LAUNCH_PARAM_BUFFER_SIZE, &size,
+                      HIP_LAUNCH_PARAM_END};
+    const unsigned gx = (unsigned)((sp.n_tiles + kGy - 1) / kGy), gy = (unsigned)sp.n_groups;
+    HIP_TRY(hipModuleLaunchKernel(static_cast<hipFunction_t>(d.spec_function), gx, gy, 1, kGy * kWave, 1, 1,
+                                  0, static_cast<hipStream_t>(stream), nullptr, config));
+    return SPARSERT_OK;
 }
 
 }  // namespace sparsert

@@ -14,6 +14,15 @@ constexpr int kGy = 4;          // waves per workgroup (one per SIMD of a CU)
 constexpr int kBins = 33;       // bin(0)=0, bin(x)=1+floor(log2 x), x < 2^31
 constexpr int kFullTasks = 2048;  // wave tasks wanted before widening per-lane vectors
 
+// Per-matrix generated kernel (kernel == SPARSERT_KERNEL_SPEC).
+struct SpecPlan {
+    int32_t rows_per_group = 0, n_groups = 0, depth = 0, n_tiles = 0, lanes_per_tile = 0;
+    int64_t asm_bytes = 0;
+    std::vector<int32_t> group_of_slot;   // [M]
+    std::vector<int32_t> group_columns;   // [n_groups] B rows each group loads per column tile
+    std::vector<char> code;               // gfx950 code object
+};
+
 struct HostPlan {
     int32_t M = 0, K = 0, N = 0, nnz = 0;
     int32_t dtype = 0, conv = 0, Cin = 0, H = 0, W = 0, kernel = 0;
@@ -26,6 +35,7 @@ struct HostPlan {
     std::vector<uint32_t> stream;      // [nnz][2]
     std::vector<int32_t> conv_seg;     // [M][10], conv only
     std::vector<int32_t> segments;     // [n_split][gy+1]
+    SpecPlan spec;
 
     int elem_size() const { return dtype == SPARSERT_F16 ? 2 : 4; }
 };
@@ -37,6 +47,8 @@ struct DevicePlan {
     uint32_t *stream = nullptr;
     int32_t *conv_seg = nullptr;
     int32_t *segments = nullptr;
+    void *spec_module = nullptr;    // hipModule_t
+    void *spec_function = nullptr;  // hipFunction_t
 };
 
 // Host analysis.  Returns SPARSERT_OK or an error code with `err` filled in.
@@ -44,10 +56,15 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
                     int32_t M, int32_t K, int32_t N, const sparsert_options &opt,
                     HostPlan &out, std::string &err);
 
+// Generated-kernel path (specialize.cpp): fills h.spec, including the assembled code object.
+int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err);
+
 // Device side (kernels.hip).
 int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err);
 void free_device_plan(DevicePlan &d);
 int launch_rows(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
+                void *stream, std::string &err);
+int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
                 void *stream, std::string &err);
 
 }  // namespace sparsert
