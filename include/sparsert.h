@@ -65,7 +65,10 @@ typedef struct sparsert_options {
                                 waves of a workgroup; 0 = automatic */
     int32_t spec_rows;       /* SPARSERT_KERNEL_SPEC: rows of A per generated code block
                                 (accumulator registers per wave); 0 = automatic */
-    int32_t reserved[5];     /* must be zero */
+    int32_t spec_depth;      /* SPARSERT_KERNEL_SPEC: B rows a wave keeps in flight; 0 = automatic */
+    int32_t spec_tiles;      /* SPARSERT_KERNEL_SPEC: column tiles (waves) per workgroup that run
+                                the same code block: 1,2,4,8,16; 0 = automatic */
+    int32_t reserved[3];     /* must be zero */
 } sparsert_options;
 
 /*
@@ -168,6 +171,7 @@ enum {
     SPARSERT_INFO_SPEC_GROUPS,    /* SPEC plans: number of code blocks */
     SPARSERT_INFO_SPEC_DEPTH,     /* SPEC plans: B rows in flight per wave */
     SPARSERT_INFO_SPEC_CODE_BYTES,
+    SPARSERT_INFO_SPEC_TILES,     /* SPEC plans: column tiles (waves) per workgroup */
     SPARSERT_INFO_COUNT = 24      /* remaining entries are zero */
 };
 

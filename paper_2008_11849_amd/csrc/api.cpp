@@ -97,6 +97,7 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
         info[SPARSERT_INFO_SPEC_GROUPS] = h.spec.n_groups;
         info[SPARSERT_INFO_SPEC_DEPTH] = h.spec.depth;
         info[SPARSERT_INFO_SPEC_CODE_BYTES] = (int32_t)h.spec.code.size();
+        info[SPARSERT_INFO_SPEC_TILES] = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.tiles_per_wg : 0;
         src = info; bytes = sizeof(info);
         break;
     case SPARSERT_FIELD_ROW_NNZ: vec32(h.row_nnz); break;

@@ -286,8 +286,11 @@ int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
     size_t size = sizeof(args);
     void *config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, &args, HIP_LAUNCH_PARAM_BUFFER_SIZE, &size,
                       HIP_LAUNCH_PARAM_END};
-    const unsigned gx = (unsigned)((sp.n_tiles + kGy - 1) / kGy), gy = (unsigned)sp.n_groups;
-    HIP_TRY(hipModuleLaunchKernel(static_cast<hipFunction_t>(d.spec_function), gx, gy, 1, kGy * kWave, 1, 1,
+    const int tpw = sp.tiles_per_wg;
+    if (tpw < 1 || tpw > 16 || (tpw & (tpw - 1))) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
+    const unsigned gx = sp.share_rows ? (unsigned)sp.n_tiles : (unsigned)((sp.n_tiles + tpw - 1) / tpw);
+    const unsigned gy = sp.share_rows ? (unsigned)((sp.n_groups + tpw - 1) / tpw) : (unsigned)sp.n_groups;
+    HIP_TRY(hipModuleLaunchKernel(static_cast<hipFunction_t>(d.spec_function), gx, gy, 1, tpw * kWave, 1, 1,
                                   0, static_cast<hipStream_t>(stream), nullptr, config));
     return SPARSERT_OK;
 }

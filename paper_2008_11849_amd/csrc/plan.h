@@ -17,6 +17,8 @@ constexpr int kFullTasks = 2048;  // wave tasks wanted before widening per-lane 
 // Per-matrix generated kernel (kernel == SPARSERT_KERNEL_SPEC).
 struct SpecPlan {
     int32_t rows_per_group = 0, n_groups = 0, depth = 0, n_tiles = 0, lanes_per_tile = 0;
+    int32_t tiles_per_wg = 4;   // waves per workgroup
+    int32_t share_rows = 0;     // 0: waves = adjacent tiles, same block; 1: adjacent blocks, same tile
     int64_t asm_bytes = 0;
     std::vector<int32_t> group_of_slot;   // [M]
     std::vector<int32_t> group_columns;   // [n_groups] B rows each group loads per column tile

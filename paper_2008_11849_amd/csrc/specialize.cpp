@@ -200,7 +200,11 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     R = std::min(R, M);
     sp.rows_per_group = R;
     sp.n_groups = (M + R - 1) / R;
-    sp.depth = 16;
+    sp.depth = opt.spec_depth ? opt.spec_depth : 16;
+    sp.tiles_per_wg = opt.spec_tiles ? opt.spec_tiles : 4;
+    sp.share_rows = getenv("SPARSERT_SPEC_SHARE") ? atoi(getenv("SPARSERT_SPEC_SHARE")) : 0;
+    int tpw_shift = 0;
+    while ((1 << tpw_shift) < sp.tiles_per_wg) ++tpw_shift;
     // Block-level balance (Section 3.4, strategy b): slots are in descending-nnz order; deal
     // them to the groups in serpentine order so every group gets nearly the same nonzero count.
     const int G = sp.n_groups;
@@ -237,9 +241,20 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\ts_nop 1");
     e.line("\tv_readfirstlane_b32 s%d, v%d", kSgprTile, kVgprT1);
     e.line("\ts_nop 4");
-    e.line("\ts_lshl_b32 s%d, s2, 2", kSgprTmp);
-    e.line("\ts_add_u32 s%d, s%d, s%d", kSgprTile, kSgprTmp, kSgprTile);  // tile = 4*wg + wave
-    e.line("\ts_mov_b32 s%d, s3", kSgprBlock);
+    if (!sp.share_rows) {
+        // the waves of a workgroup run the same code block on adjacent column tiles
+        e.line("\ts_lshl_b32 s%d, s2, %d", kSgprTmp, tpw_shift);
+        e.line("\ts_add_u32 s%d, s%d, s%d", kSgprTile, kSgprTmp, kSgprTile);  // tile = tiles_per_wg*wg + wave
+        e.line("\ts_mov_b32 s%d, s3", kSgprBlock);
+    } else {
+        // the waves of a workgroup run adjacent code blocks on the same column tile, so the B
+        // rows one wave pulls into the L1 are hits for the others
+        e.line("\ts_lshl_b32 s%d, s3, %d", kSgprTmp, tpw_shift);
+        e.line("\ts_add_u32 s%d, s%d, s%d", kSgprBlock, kSgprTmp, kSgprTile);  // block = waves*wg + wave
+        e.line("\ts_mov_b32 s%d, s2", kSgprTile);
+        e.line("\ts_cmp_ge_u32 s%d, %d", kSgprBlock, G);
+        e.line("\ts_cbranch_scc1 .Lend");
+    }
     e.line("\ts_cmp_ge_u32 s%d, %d", kSgprTile, sp.n_tiles);
     e.line("\ts_cbranch_scc1 .Lend");
     e.line("\ts_mul_i32 s%d, s%d, %d", kSgprTmp, kSgprTile, sp.lanes_per_tile);  // first column of the tile
@@ -299,7 +314,9 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         e.line("\t.p2align 2");
         e.line(".Lg%d:", g);
         for (size_t i = 0; i < rows.size(); ++i) e.line("\tv_mov_b32_e32 v%d, 0", kVgprAcc0 + (int)i);
+        const int xp = getenv("SPARSERT_SPEC_XP") ? atoi(getenv("SPARSERT_SPEC_XP")) : 0;  // timing experiments only
         auto issue_load = [&](int j) {
+            if ((xp & 2) && j >= D) return;
             const int sreg = kSgprOffRing + (j % kOffRing);
             e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)order[j] * N * 4));
             e.line("\tbuffer_load_dword v%d, v%d, s[%d:%d], s%d offen", vgpr_b0 + (j % D), kVgprOff,
@@ -308,9 +325,12 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         for (int j = 0; j < std::min(D, nc); ++j) issue_load(j);
         for (int j = 0; j < nc; ++j) {
             // loads issued so far: columns [0, min(nc, j + D)); those after column j may stay in flight
-            e.line("\ts_waitcnt vmcnt(%d)", std::min(nc, j + D) - 1 - j);
-            for (const Term &t : cols[order[j]])
-                e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vgpr_b0 + (j % D));
+            if (!(xp & 2)) e.line("\ts_waitcnt vmcnt(%d)", std::min(nc, j + D) - 1 - j);
+            else if (j == 0) e.line("\ts_waitcnt vmcnt(0)");
+            for (const Term &t : cols[order[j]]) {
+                if (xp & 1) e.line("\tv_fmac_f32_e32 v%d, v%d, v%d", kVgprAcc0 + t.acc, vgpr_b0 + (j % D), vgpr_b0 + (j % D));
+                else e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vgpr_b0 + (j % D));
+            }
             if (j + D < nc) issue_load(j + D);
         }
         e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
@@ -377,7 +397,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("    .group_segment_fixed_size: 0");
     e.line("    .kernarg_segment_align: 8");
     e.line("    .kernarg_segment_size: 16");
-    e.line("    .max_flat_workgroup_size: 256");
+    e.line("    .max_flat_workgroup_size: %d", sp.tiles_per_wg * kWave);
     e.line("    .name:           sparsert_spec");
     e.line("    .private_segment_fixed_size: 0");
     e.line("    .sgpr_count:     %d", kNextFreeSgpr + 6);

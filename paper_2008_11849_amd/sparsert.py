@@ -22,7 +22,8 @@ KERNEL_AUTO, KERNEL_ROWS, KERNEL_SPEC = 0, 1, 2
  FIELD_SEGMENTS, FIELD_SPEC_GROUPS, FIELD_SPEC_COLUMNS, FIELD_SPEC_CODE) = range(15)
 INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", "vec",
               "lanes_per_tile", "n_tiles", "gy", "split_threshold", "n_split", "n_wg_rows",
-              "n_bins", "spec_rows", "spec_groups", "spec_depth", "spec_code_bytes"]
+              "n_bins", "spec_rows", "spec_groups", "spec_depth", "spec_code_bytes",
+              "spec_tiles"]
 INFO_COUNT = 24
 
 EXPORTED = ["sparsert_inspect", "sparsert_spmm", "sparsert_conv3x3", "sparsert_plan_export",
@@ -34,7 +35,8 @@ class Options(ctypes.Structure):
                 ("Cin", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
                 ("batch", ctypes.c_int32), ("host_only", ctypes.c_int32),
                 ("vec", ctypes.c_int32), ("split_threshold", ctypes.c_int32),
-                ("spec_rows", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
+                ("spec_rows", ctypes.c_int32), ("spec_depth", ctypes.c_int32),
+                ("spec_tiles", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
 class SparseRTError(RuntimeError):
@@ -127,7 +129,7 @@ class Plan:
 def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[int] = None,
             conv: Optional[Tuple[int, int, int]] = None, batch: int = 0, host_only: bool = False,
             vec: int = 0, split_threshold: int = 0, kernel: int = KERNEL_AUTO,
-            spec_rows: int = 0) -> Plan:
+            spec_rows: int = 0, spec_depth: int = 0, spec_tiles: int = 0) -> Plan:
     """sparsert_inspect.  `vals` must already be float32 or float16; it is not converted."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -142,7 +144,7 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
     opt = Options()
     opt.dtype, opt.kernel, opt.host_only = dtype, kernel, int(host_only)
     opt.vec, opt.split_threshold, opt.batch = vec, split_threshold, batch
-    opt.spec_rows = spec_rows
+    opt.spec_rows, opt.spec_depth, opt.spec_tiles = spec_rows, spec_depth, spec_tiles
     if conv is not None:
         opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
     handle = _vp()
