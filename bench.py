@@ -37,23 +37,21 @@ def parse_args():
     ap.add_argument("--dtype", default="f32", choices=["f32", "f16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cases", action="store_true", help="skip the side table of the other configs")
-    ap.add_argument("--kernel", default="auto", choices=["auto", "rows", "spec"])
+    ap.add_argument("--kernel", default="tune", choices=["tune", "rows", "spec"],
+                    help="tune: sparsert_tune picks the executor per layer (default); rows/spec: fixed family")
     return ap.parse_args()
 
 
 class Layer:
     """One sparse layer resident on the GPU: plan, input, output and its dense twin."""
 
-    def __init__(self, case, torch, sp, kernel=0):
+    def __init__(self, case, torch, sp, kernel="tune"):
         import numpy as np
         self.case, self.torch, self.sp = case, torch, sp
         csr = case.csr
         dev = torch.device("cuda:0")
         self.is_conv = case.conv is not None
         self.M, self.K, self.N, self.nnz = csr.M, csr.K, case.N, csr.nnz
-        self.plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N,
-                               conv=case.conv, kernel=kernel)
-        self.info = self.plan.info()
         tdt = torch.float16 if csr.vals.dtype == np.float16 else torch.float32
         self.esize = 2 if tdt == torch.float16 else 4
         if self.is_conv:
@@ -66,6 +64,16 @@ class Layer:
             self.out = torch.empty((csr.M, case.N), dtype=tdt, device=dev)
             self.Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
             self.fn = sp.raw.sparsert_spmm
+        self.tuned = None
+        if kernel == "tune":
+            # offline, once per matrix (Section 3.7); not part of the timed region
+            self.plan, self.tuned = sp.tune(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N,
+                                            self.inp.data_ptr(), self.out.data_ptr(),
+                                            torch.cuda.current_stream().cuda_stream, conv=case.conv)
+        else:
+            self.plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N, conv=case.conv,
+                                   kernel={"rows": sp.KERNEL_ROWS, "spec": sp.KERNEL_SPEC}[kernel])
+        self.info = self.plan.info()
         self.args = (ctypes.c_void_p(self.plan.handle), ctypes.c_void_p(self.inp.data_ptr()),
                      ctypes.c_void_p(self.out.data_ptr()))
 
@@ -153,7 +161,7 @@ def main():
     torch.backends.cuda.matmul.allow_tf32 = False
     torch.backends.cudnn.allow_tf32 = False
     dt = np.float16 if args.dtype == "f16" else np.float32
-    kernel = {"auto": 0, "rows": 1, "spec": 2}[args.kernel]
+    kernel = args.kernel
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
     names = {"c1": ["c1"], "c2": ["c2"], "c3": ["c3", "c3t"], "c4": ["c4"]}[args.workload]
@@ -185,13 +193,15 @@ def main():
         per_layer.append({"layer": L.case.name, "M": L.M, "K": L.K, "N": L.N, "nnz": L.nnz,
                           "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
                           "dense_us": ms_dense * 1e3, "speedup_vs_dense": ms_dense / ms,
-                          "vec": L.info["vec"], "n_split": L.info["n_split"]})
+                          "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
+                                                          "spec_tiles", "spec_code_bytes")},
+                          "tuned_candidates": len(L.tuned) if L.tuned else 0})
     kernel_ms = sum(p["us"] for p in per_layer) / 1e3 / len(layers)       # average launch
     alg_bytes = sum(L.algorithmic_bytes for L in layers) / len(layers)    # average launch
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
     dense_ms = sum(p["dense_us"] for p in per_layer) / 1e3
     sparse_ms = sum(p["us"] for p in per_layer) / 1e3
-    tag = f"rows_kernel_{args.workload}_{args.dtype}"
+    tag = f"spmm_{args.workload}_{args.dtype}"
     out = {
         "metric": "effective GFLOP/s (2*nnz*N)",
         "value": flops_step / (ms_per_step * 1e-3) / 1e9,
@@ -212,7 +222,8 @@ def main():
         "layers": per_layer,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(tag),
-                     "kernel": "sparsert::rows_kernel", "avg_launch_us": kernel_ms * 1e3,
+                     "kernel": "sparsert_spec / sparsert::rows_kernel (per layer, see layers[].plan.kernel: 2 / 1)",
+                     "avg_launch_us": kernel_ms * 1e3,
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "alu_frac_of_fp32_vector_peak":
                          flops_step / len(layers) / (kernel_ms * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TF},
@@ -227,7 +238,9 @@ def main():
             ms = time_loop(torch, lambda L=L: L.launch(stream), 500, 50)
             msd = time_loop(torch, L.dense, 100, 10)
             side.append({"layer": n, "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
-                         "dense_us": msd * 1e3, "speedup_vs_dense": msd / ms})
+                         "dense_us": msd * 1e3, "speedup_vs_dense": msd / ms,
+                         "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
+                                                         "spec_tiles")}})
             L.plan.destroy()
         out["other_configs"] = side
 

@@ -51,6 +51,15 @@ typedef enum sparsert_kernel {
                                   instruction constants (Section 3.5); fp32 SpMM only */
 } sparsert_kernel;
 
+/* Variants of the generated kernel (options.spec_mode). */
+typedef enum sparsert_spec_mode {
+    SPARSERT_SPEC_AUTO = 0,
+    SPARSERT_SPEC_DIRECT = 1, /* a workgroup's waves run one code block on adjacent column tiles;
+                                 B rows are read straight from L2/L1 */
+    SPARSERT_SPEC_LDS = 2     /* a workgroup's waves run adjacent code blocks on one column tile;
+                                 the tile's B rows are staged once through LDS */
+} sparsert_spec_mode;
+
 /* Zero-initialise, then set what you need.  All-zero = fp32 SpMM, automatic tiling. */
 typedef struct sparsert_options {
     int32_t dtype;           /* sparsert_dtype */
@@ -66,9 +75,11 @@ typedef struct sparsert_options {
     int32_t spec_rows;       /* SPARSERT_KERNEL_SPEC: rows of A per generated code block
                                 (accumulator registers per wave); 0 = automatic */
     int32_t spec_depth;      /* SPARSERT_KERNEL_SPEC: B rows a wave keeps in flight; 0 = automatic */
-    int32_t spec_tiles;      /* SPARSERT_KERNEL_SPEC: column tiles (waves) per workgroup that run
-                                the same code block: 1,2,4,8,16; 0 = automatic */
-    int32_t reserved[3];     /* must be zero */
+    int32_t spec_tiles;      /* SPARSERT_KERNEL_SPEC: waves per workgroup (adjacent column tiles in
+                                DIRECT mode, adjacent code blocks in LDS mode): 1,2,4,8,16;
+                                0 = automatic */
+    int32_t spec_mode;       /* sparsert_spec_mode; 0 = automatic */
+    int32_t reserved[2];     /* must be zero */
 } sparsert_options;
 
 /*
@@ -130,6 +141,38 @@ int sparsert_spmm(const sparsert_plan *plan, const void *B_dev, void *C_dev, voi
  */
 int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, void *stream);
 
+/*
+ * Autotuner (Section 3.7: exhaustive search over a short hand-picked list of executor
+ * configurations, done once per problem, off the inference path).  Builds a plan for each
+ * candidate configuration - executor family, columns per lane, split threshold, rows per
+ * generated code block, waves per workgroup, staging variant - times it on the GPU with the
+ * given operands, and returns the fastest plan.  `base` fixes dtype and the convolution
+ * geometry; its tuning fields are ignored.
+ *
+ *   in_dev / out_dev  DEVICE buffers of the shapes sparsert_spmm / sparsert_conv3x3 take;
+ *                     out_dev is overwritten many times
+ *   stream            launches and timing events go to this stream; the call synchronises it
+ *   out               receives the best plan
+ *   report            may be NULL; receives one entry per timed candidate
+ *
+ * Errors: as sparsert_inspect; EHIP if timing fails.  Allocates (plans, events): not for the
+ * inference path.
+ */
+#define SPARSERT_TUNE_MAX 64
+typedef struct sparsert_tune_entry {
+    int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles;
+    float microseconds; /* per launch; negative if the candidate failed */
+} sparsert_tune_entry;
+typedef struct sparsert_tune_report {
+    int32_t count;
+    float best_microseconds;
+    sparsert_tune_entry entries[SPARSERT_TUNE_MAX];
+} sparsert_tune_report;
+int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
+                  int32_t M, int32_t K, int32_t N, const sparsert_options *base,
+                  const void *in_dev, void *out_dev, void *stream,
+                  sparsert_plan **out, sparsert_tune_report *report);
+
 /* Arrays of the plan that sparsert_plan_export can copy out (HOST side). */
 typedef enum sparsert_field {
     SPARSERT_FIELD_INFO = 0,      /* int32[SPARSERT_INFO_COUNT], see below */
@@ -171,8 +214,10 @@ enum {
     SPARSERT_INFO_SPEC_GROUPS,    /* SPEC plans: number of code blocks */
     SPARSERT_INFO_SPEC_DEPTH,     /* SPEC plans: B rows in flight per wave */
     SPARSERT_INFO_SPEC_CODE_BYTES,
-    SPARSERT_INFO_SPEC_TILES,     /* SPEC plans: column tiles (waves) per workgroup */
-    SPARSERT_INFO_COUNT = 24      /* remaining entries are zero */
+    SPARSERT_INFO_SPEC_TILES,     /* SPEC plans: waves per workgroup */
+    SPARSERT_INFO_SPEC_MODE,      /* SPEC plans: sparsert_spec_mode in use */
+    SPARSERT_INFO_SPEC_LDS_BYTES, /* SPEC plans: LDS per workgroup */
+    SPARSERT_INFO_COUNT = 32      /* remaining entries are zero */
 };
 
 /*

@@ -10,6 +10,10 @@ thread_local std::string g_err;
 int fail(int code, const std::string &msg) { g_err = msg; return code; }
 }  // namespace
 
+namespace sparsert {
+int set_error(int code, const std::string &msg) { return fail(code, msg); }
+}  // namespace sparsert
+
 extern "C" {
 
 int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
@@ -98,6 +102,8 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
         info[SPARSERT_INFO_SPEC_DEPTH] = h.spec.depth;
         info[SPARSERT_INFO_SPEC_CODE_BYTES] = (int32_t)h.spec.code.size();
         info[SPARSERT_INFO_SPEC_TILES] = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.tiles_per_wg : 0;
+        info[SPARSERT_INFO_SPEC_MODE] = h.spec.mode;
+        info[SPARSERT_INFO_SPEC_LDS_BYTES] = h.spec.lds_bytes;
         src = info; bytes = sizeof(info);
         break;
     case SPARSERT_FIELD_ROW_NNZ: vec32(h.row_nnz); break;

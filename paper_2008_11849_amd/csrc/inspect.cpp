@@ -38,7 +38,7 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (M <= 0 || K <= 0 || N <= 0) { err = "M, K and N must be positive"; return SPARSERT_EINVAL; }
     if (opt.dtype != SPARSERT_F32 && opt.dtype != SPARSERT_F16) { err = "unknown dtype"; return SPARSERT_EINVAL; }
     if (opt.kernel < SPARSERT_KERNEL_AUTO || opt.kernel > SPARSERT_KERNEL_SPEC) { err = "unknown kernel family"; return SPARSERT_EINVAL; }
-    for (int i = 0; i < 3; ++i)
+    for (int i = 0; i < 2; ++i)
         if (opt.reserved[i] != 0) { err = "reserved option fields must be zero"; return SPARSERT_EINVAL; }
     if (row_ptr[0] != 0) { err = "row_ptr[0] must be 0"; return SPARSERT_EINVAL; }
     for (int32_t m = 0; m < M; ++m)
@@ -65,6 +65,7 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (opt.spec_depth < 0 || opt.spec_depth > 48) { err = "spec_depth must be in 0..48"; return SPARSERT_EINVAL; }
     if (opt.spec_tiles != 0 && opt.spec_tiles != 1 && opt.spec_tiles != 2 && opt.spec_tiles != 4 &&
         opt.spec_tiles != 8 && opt.spec_tiles != 16) { err = "spec_tiles must be 0,1,2,4,8,16"; return SPARSERT_EINVAL; }
+    if (opt.spec_mode < SPARSERT_SPEC_AUTO || opt.spec_mode > SPARSERT_SPEC_LDS) { err = "unknown spec_mode"; return SPARSERT_EINVAL; }
     if (opt.spec_rows < 0) { err = "spec_rows must be >= 0"; return SPARSERT_EINVAL; }
     if (opt.split_threshold < 0) { err = "split_threshold must be >= 0"; return SPARSERT_EINVAL; }
     const int64_t esz = opt.dtype == SPARSERT_F16 ? 2 : 4;

@@ -288,8 +288,10 @@ int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
                       HIP_LAUNCH_PARAM_END};
     const int tpw = sp.tiles_per_wg;
     if (tpw < 1 || tpw > 16 || (tpw & (tpw - 1))) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
-    const unsigned gx = sp.share_rows ? (unsigned)sp.n_tiles : (unsigned)((sp.n_tiles + tpw - 1) / tpw);
-    const unsigned gy = sp.share_rows ? (unsigned)((sp.n_groups + tpw - 1) / tpw) : (unsigned)sp.n_groups;
+    const bool lds = sp.mode == SPARSERT_SPEC_LDS;
+    if (lds && (sp.n_blocks % tpw || sp.lds_bytes < 1 || sp.lds_bytes > 65536)) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
+    const unsigned gx = lds ? (unsigned)sp.n_tiles : (unsigned)((sp.n_tiles + tpw - 1) / tpw);
+    const unsigned gy = lds ? (unsigned)(sp.n_blocks / tpw) : (unsigned)sp.n_groups;
     HIP_TRY(hipModuleLaunchKernel(static_cast<hipFunction_t>(d.spec_function), gx, gy, 1, tpw * kWave, 1, 1,
                                   0, static_cast<hipStream_t>(stream), nullptr, config));
     return SPARSERT_OK;

@@ -18,7 +18,9 @@ constexpr int kFullTasks = 2048;  // wave tasks wanted before widening per-lane 
 struct SpecPlan {
     int32_t rows_per_group = 0, n_groups = 0, depth = 0, n_tiles = 0, lanes_per_tile = 0;
     int32_t tiles_per_wg = 4;   // waves per workgroup
-    int32_t share_rows = 0;     // 0: waves = adjacent tiles, same block; 1: adjacent blocks, same tile
+    int32_t mode = 0;           // sparsert_spec_mode
+    int32_t n_blocks = 0;       // code blocks (n_groups, padded to a multiple of the waves in LDS mode)
+    int32_t lds_bytes = 0;
     int64_t asm_bytes = 0;
     std::vector<int32_t> group_of_slot;   // [M]
     std::vector<int32_t> group_columns;   // [n_groups] B rows each group loads per column tile
@@ -60,6 +62,9 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
 
 // Generated-kernel path (specialize.cpp): fills h.spec, including the assembled code object.
 int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err);
+
+// Records the thread-local error message behind sparsert_last_error (api.cpp); returns `code`.
+int set_error(int code, const std::string &msg);
 
 // Device side (kernels.hip).
 int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err);

@@ -10,15 +10,22 @@
 // load behind its use.
 //
 // Shape of the generated kernel `sparsert_spec`
-//   grid  = (ceil(n_tiles/4), G);  workgroup = 4 waves = 4 adjacent column tiles
-//   wave  = one row group g (<= R rows, chosen by the inspector for nonzero balance,
+//   wave  = one row group g (<= R rows, dealt by the inspector for nonzero balance,
 //           Section 3.4) x one column tile (lanes own one column of C each)
-//   code  = per group, for each column k that has a nonzero in the group, ascending:
-//             buffer_load  b <- B[k, tile columns]        (issued D columns ahead)
-//             v_fmac_f32   acc[row] += literal(A[row,k]) * b     for every nonzero (row,k)
-//           then one store per row.  No loops, no index loads, no barriers.
-// All addresses are "descriptor base + row offset literal + lane column offset" with the
-// column offset clamped to the tile, so every access is in bounds by construction.
+//   code  = one straight-line block per group: for each column k that has a nonzero in
+//           the group, ascending: fetch b <- B[k, tile columns] (several columns ahead),
+//           then  v_fmac_f32 acc[row] += literal(A[row,k]) * b  for every nonzero (row,k);
+//           finally one store per row.  No loops, no index loads.
+//   DIRECT: workgroup = T waves running the same block on T adjacent tiles; b comes
+//           straight from L2/L1 with buffer loads.
+//   LDS   : workgroup = W waves running W adjacent blocks on the same tile.  The tile's
+//           B rows are staged once per workgroup through LDS in chunks of up to 128 rows
+//           (double buffered, one barrier per chunk; each wave fetches a 1/W share) and
+//           every wave reads its b values from LDS with compile-time offsets.  Measured
+//           on MI355X the vector-memory path delivers ~37 B/clk per CU, the LDS path
+//           several times that, and each FMA needs 4 B of b: DIRECT is load bound.
+// All global addresses are "descriptor base + row offset literal + lane column offset"
+// with the column clamped to the tile, so every access is in bounds by construction.
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
@@ -174,8 +181,184 @@ constexpr int kSgprTile = 16, kSgprBlock = 17, kSgprPc = 18, kSgprTmp = 20, kSgp
 constexpr int kSgprOwns = 22;                  // s[22:23] lanes that own a column
 constexpr int kSgprOffRing = 24, kOffRing = 8; // s[24:31] row-offset literals in flight
 constexpr int kNextFreeSgpr = 32;
-constexpr int kVgprOff = 0, kVgprT1 = 1, kVgprT2 = 2, kVgprAcc0 = 4;
+constexpr int kVgprOff = 0;                    // byte offset of the lane's column inside a row
+constexpr int kVgprLds = 1;                    // LDS byte address of the lane's 16-byte slot
+constexpr int kVgprT1 = 2, kVgprT2 = 3, kVgprAcc0 = 4;
 constexpr uint32_t kRsrcWord3 = 0x00020000u;   // raw 32-bit buffer, gfx9 family
+constexpr int kMaxChunkRows = 128;             // B rows per LDS buffer (32 KiB), two buffers
+constexpr int kMaxLgkm = 15;                   // lgkmcnt is a 4-bit counter
+
+struct Term { int acc; uint32_t bits; };
+
+struct Gen {
+    Emitter e;
+    const HostPlan &h;
+    SpecPlan &sp;
+    int N, K, D;
+    int vgpr_stage0 = 0, vgpr_ring0 = 0, n_vgpr = 0, lds_bytes = 0;
+    int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
+    int xp = 0;  // timing experiments only (SPARSERT_SPEC_XP)
+    Gen(const HostPlan &hp, SpecPlan &s) : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth) {}
+
+    void zero_accs(size_t n) {
+        for (size_t i = 0; i < n; ++i) e.line("\tv_mov_b32_e32 v%d, 0", kVgprAcc0 + (int)i);
+    }
+    void fmas(const std::vector<Term> &terms, int vb) {
+        for (const Term &t : terms) {
+            if (xp & 1) e.line("\tv_fmac_f32_e32 v%d, v%d, v%d", kVgprAcc0 + t.acc, vb, vb);
+            else e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vb);
+        }
+    }
+    void load_b_row(int k, int vdst, int ring_pos) {
+        const int sreg = kSgprOffRing + (ring_pos % kOffRing);
+        e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)k * N * 4));
+        e.line("\tbuffer_load_dword v%d, v%d, s[%d:%d], s%d offen", vdst, kVgprOff, kRsrcB, kRsrcB + 3, sreg);
+    }
+    void stores(const std::vector<int32_t> &rows) {
+        if (rows.empty()) return;
+        e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
+        for (size_t i = 0; i < rows.size(); ++i) {
+            if ((xp & 4) && i > 0) break;
+            const int sreg = kSgprOffRing + ((int)i % kOffRing);
+            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i]] * N * 4));
+            e.line("\tbuffer_store_dword v%d, v%d, s[%d:%d], s%d offen", kVgprAcc0 + (int)i, kVgprOff,
+                   kRsrcC, kRsrcC + 3, sreg);
+        }
+    }
+
+    // column -> nonzeros of the group, ascending columns
+    std::map<int32_t, std::vector<Term>> columns_of(const std::vector<int32_t> &rows) const {
+        std::map<int32_t, std::vector<Term>> cols;
+        for (size_t i = 0; i < rows.size(); ++i) {
+            const int32_t slot = rows[i];
+            for (int32_t p = h.p_row_ptr[slot]; p < h.p_row_ptr[slot + 1]; ++p)
+                cols[h.p_col_idx[p]].push_back({(int)i, h.stream[2 * (size_t)p + 1]});
+        }
+        return cols;
+    }
+
+    // DIRECT: b values come straight from global memory, D columns in flight.
+    int block_direct(const std::vector<int32_t> &rows) {
+        auto cols = columns_of(rows);
+        std::vector<int32_t> order;
+        for (auto &kv : cols) order.push_back(kv.first);
+        const int nc = (int)order.size();
+        zero_accs(rows.size());
+        auto issue = [&](int j) {
+            if ((xp & 2) && j >= D) return;
+            load_b_row(order[j], vgpr_ring0 + (j % D), j);
+        };
+        for (int j = 0; j < std::min(D, nc); ++j) issue(j);
+        for (int j = 0; j < nc; ++j) {
+            // loads issued so far: columns [0, min(nc, j + D)); those after column j may stay in flight
+            if (!(xp & 2)) e.line("\ts_waitcnt vmcnt(%d)", std::min(nc, j + D) - 1 - j);
+            else if (j == 0) e.line("\ts_waitcnt vmcnt(0)");
+            fmas(cols[order[j]], vgpr_ring0 + (j % D));
+            if (j + D < nc) issue(j + D);
+        }
+        stores(rows);
+        e.line("\ts_endpgm");
+        return nc;
+    }
+
+    // LDS: wave `w` of W stages quads q == w (mod W) of every chunk; all waves read what
+    // they need.  LDS layout per buffer: [quad of 4 consecutive B rows][lane][4 floats].
+    int block_lds(const std::vector<int32_t> &rows, int w, int W) {
+        auto cols = columns_of(rows);
+        const int kChunkRows = chunk_rows;
+        const int n_chunks = (K + kChunkRows - 1) / kChunkRows;
+        const int quads_per_chunk = kChunkRows / 4;
+        const int buf_bytes = kChunkRows * 256;
+        int ring_pos = 0;
+        zero_accs(rows.size());
+        // Staging runs two chunks ahead of the compute: chunk c travels through register set
+        // c % 2, so a fetch has two compute phases to arrive before it is copied into LDS.
+        const int quads_per_wave = (quads_per_chunk + W - 1) / W;
+        std::vector<int> n_loads(n_chunks + 3, 0);
+        auto stage_loads = [&](int c) {
+            if (c >= n_chunks || (xp & 16)) return;
+            int t = 0, n = 0;
+            for (int q = w; q < quads_per_chunk; q += W, ++t)
+                for (int j = 0; j < 4; ++j) {
+                    const int k = c * kChunkRows + 4 * q + j;
+                    if (k < K) { load_b_row(k, vgpr_stage0 + (c & 1) * 4 * quads_per_wave + 4 * t + j, ring_pos++); ++n; }
+                }
+            n_loads[c] = n;
+        };
+        auto stage_write = [&](int c) {
+            // fetches return in order: chunk c has arrived once only chunk c+1's are outstanding
+            if (xp & 16) return;
+            e.line("\ts_waitcnt vmcnt(%d)", c + 1 < n_chunks ? n_loads[c + 1] : 0);
+            int t = 0;
+            for (int q = w; q < quads_per_chunk; q += W, ++t) {
+                if (c * kChunkRows + 4 * q >= K) break;
+                const int v = vgpr_stage0 + (c & 1) * 4 * quads_per_wave + 4 * t;
+                e.line("\tds_write_b128 v%d, v[%d:%d] offset:%d", kVgprLds, v, v + 3, (c & 1) * buf_bytes + q * 1024);
+            }
+        };
+        stage_loads(0);
+        stage_loads(1);
+        stage_write(0);
+        e.line("\ts_waitcnt lgkmcnt(0)");
+        stage_loads(2);
+        e.line("\ts_barrier");
+        int total_cols = 0;
+        for (int c = 0; c < n_chunks; ++c) {
+            // quads of this chunk that hold a nonzero column of the group
+            struct Quad { int q; std::vector<Term> terms[4]; bool need[4]; };
+            std::vector<Quad> quads;
+            for (auto it = cols.lower_bound(c * kChunkRows); it != cols.end() && it->first < (c + 1) * kChunkRows; ++it) {
+                const int kl = it->first - c * kChunkRows, q = kl / 4, j = kl % 4;
+                if (quads.empty() || quads.back().q != q) { quads.push_back(Quad()); quads.back().q = q; for (bool &b : quads.back().need) b = false; }
+                quads.back().need[j] = true;
+                quads.back().terms[j] = it->second;
+                ++total_cols;
+            }
+            const int nq = (int)quads.size();
+            std::vector<int> last_seq(nq, -1);
+            int issued = 0;
+            auto issue_reads = [&](int i) {
+                const Quad &Q = quads[i];
+                const int v0 = vgpr_ring0 + 4 * (i % D), off = (c & 1) * buf_bytes + Q.q * 1024;
+                const int cnt = Q.need[0] + Q.need[1] + Q.need[2] + Q.need[3];
+                if (cnt >= 3) {
+                    e.line("\tds_read_b128 v[%d:%d], v%d offset:%d", v0, v0 + 3, kVgprLds, off);
+                    ++issued;
+                } else {
+                    for (int j = 0; j < 4; j += 2) {
+                        if (Q.need[j] && Q.need[j + 1]) {
+                            e.line("\tds_read_b64 v[%d:%d], v%d offset:%d", v0 + j, v0 + j + 1, kVgprLds, off + 4 * j);
+                            ++issued;
+                        } else if (Q.need[j] || Q.need[j + 1]) {
+                            const int jj = Q.need[j] ? j : j + 1;
+                            e.line("\tds_read_b32 v%d, v%d offset:%d", v0 + jj, kVgprLds, off + 4 * jj);
+                            ++issued;
+                        }
+                    }
+                }
+                last_seq[i] = issued - 1;
+            };
+            for (int i = 0; i < std::min(D, nq); ++i) issue_reads(i);
+            for (int i = 0; i < nq; ++i) {
+                // LDS reads return in order: quad i is complete once at most
+                // (issued - 1 - last_seq[i]) later reads are outstanding
+                if (!(xp & 8)) e.line("\ts_waitcnt lgkmcnt(%d)", std::min(kMaxLgkm, issued - 1 - last_seq[i]));
+                for (int j = 0; j < 4; ++j)
+                    if (quads[i].need[j]) fmas(quads[i].terms[j], vgpr_ring0 + 4 * (i % D) + j);
+                if (i + D < nq) issue_reads(i + D);
+            }
+            if (c + 1 < n_chunks) {
+                stage_write(c + 1);
+                e.line("\ts_waitcnt lgkmcnt(0)");
+                stage_loads(c + 3);
+                if (!(xp & 32)) e.line("\ts_barrier");
+            }
+        }
+        stores(rows);
+        e.line("\ts_endpgm");
+        return total_cols;
+    }
+};
 
 }  // namespace
 
@@ -184,10 +367,16 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     if (h.conv) { err = "the specialised executor does not cover convolution plans yet"; return SPARSERT_EUNSUPPORTED; }
     if (h.dtype != SPARSERT_F32) { err = "the specialised executor is fp32 only"; return SPARSERT_EUNSUPPORTED; }
     const int32_t M = h.M, N = h.N;
+    sp.mode = opt.spec_mode ? opt.spec_mode : SPARSERT_SPEC_DIRECT;
+    const bool lds = sp.mode == SPARSERT_SPEC_LDS;
     // Column tiling with one column per lane, balanced tails (same rule as the row-walk plan at V = 1).
     sp.n_tiles = (N + kWave - 1) / kWave;
     sp.lanes_per_tile = (N + sp.n_tiles - 1) / sp.n_tiles;
-    // Rows per group: enough rows that a loaded B row is reused, few enough that the chip is
+    sp.tiles_per_wg = opt.spec_tiles ? opt.spec_tiles : 4;
+    const int W = sp.tiles_per_wg;
+    int wshift = 0;
+    while ((1 << wshift) < W) ++wshift;
+    // Rows per group: enough rows that a fetched B row is reused, few enough that the chip is
     // filled: R1 fills 1024 SIMDs with one wave each, R2 gives a wave about 400 multiply-adds.
     int R = opt.spec_rows;
     if (R == 0) {
@@ -200,16 +389,17 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     R = std::min(R, M);
     sp.rows_per_group = R;
     sp.n_groups = (M + R - 1) / R;
-    sp.depth = opt.spec_depth ? opt.spec_depth : 16;
-    sp.tiles_per_wg = opt.spec_tiles ? opt.spec_tiles : 4;
-    sp.share_rows = getenv("SPARSERT_SPEC_SHARE") ? atoi(getenv("SPARSERT_SPEC_SHARE")) : 0;
-    int tpw_shift = 0;
-    while ((1 << tpw_shift) < sp.tiles_per_wg) ++tpw_shift;
+    sp.depth = opt.spec_depth ? opt.spec_depth : (lds ? 6 : 16);
+    if (lds && sp.depth > 12) sp.depth = 12;
     // Block-level balance (Section 3.4, strategy b): slots are in descending-nnz order; deal
     // them to the groups in serpentine order so every group gets nearly the same nonzero count.
     const int G = sp.n_groups;
+    // LDS mode: a workgroup runs W consecutive blocks and every one of them takes part in the
+    // staging and the barriers, so the block list is padded with empty blocks.
+    const int n_blocks = lds ? (G + W - 1) / W * W : G;
+    sp.n_blocks = n_blocks;
     sp.group_of_slot.resize(M);
-    std::vector<std::vector<int32_t>> members(G);
+    std::vector<std::vector<int32_t>> members(n_blocks);
     for (int32_t i = 0; i < M; ++i) {
         const int32_t round = i / G, pos = i % G;
         const int32_t g = (round & 1) ? G - 1 - pos : pos;
@@ -217,14 +407,29 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         members[g].push_back(i);
     }
 
-    Emitter e;
+    Gen gen(h, sp);
+    gen.xp = getenv("SPARSERT_SPEC_XP") ? atoi(getenv("SPARSERT_SPEC_XP")) : 0;
+    Emitter &e = gen.e;
     const int64_t b_bytes = (int64_t)h.K * N * 4, c_bytes = (int64_t)M * N * 4;
     int max_rows = 0;
     for (auto &m : members) max_rows = std::max<int>(max_rows, (int)m.size());
     const int D = sp.depth;
-    const int vgpr_b0 = kVgprAcc0 + max_rows;
-    const int n_vgpr = vgpr_b0 + D;
+    if (lds) {
+        gen.chunk_rows = std::min(kMaxChunkRows, 32 * W);
+        const int kChunkRows = gen.chunk_rows;
+        const int quads_per_wave = (kChunkRows / 4 + W - 1) / W;
+        gen.vgpr_stage0 = (kVgprAcc0 + max_rows + 3) / 4 * 4;
+        gen.vgpr_ring0 = gen.vgpr_stage0 + 2 * 4 * quads_per_wave;
+        gen.n_vgpr = gen.vgpr_ring0 + 4 * D;
+        const int n_chunks = (h.K + kChunkRows - 1) / kChunkRows;
+        gen.lds_bytes = (n_chunks > 1 ? 2 : 1) * kChunkRows * 256;
+    } else {
+        gen.vgpr_ring0 = kVgprAcc0 + max_rows;
+        gen.n_vgpr = gen.vgpr_ring0 + D;
+    }
+    const int n_vgpr = gen.n_vgpr;
     if (n_vgpr > 256) { err = "spec_rows too large for the register file"; return SPARSERT_EINVAL; }
+    sp.lds_bytes = gen.lds_bytes;
 
     e.line("\t.amdgcn_target \"amdgcn-amd-amdhsa--gfx950\"");
     e.line("\t.amdhsa_code_object_version 6");
@@ -234,29 +439,28 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\t.p2align\t8");
     e.line("\t.type\tsparsert_spec,@function");
     e.line("sparsert_spec:");
-    // s[0:1] kernarg, s2 = workgroup id x (column tile quad), s3 = workgroup id y (row group), v0 = thread id
+    // s[0:1] kernarg, s2 = workgroup id x, s3 = workgroup id y, v0 = thread id
     e.line("\ts_load_dwordx4 s[%d:%d], s[0:1], 0x0", kSgprB, kSgprC + 1);
     e.line("\tv_lshrrev_b32_e32 v%d, 6, v0", kVgprT1);
     e.line("\tv_and_b32_e32 v%d, 63, v0", kVgprOff);
     e.line("\ts_nop 1");
-    e.line("\tv_readfirstlane_b32 s%d, v%d", kSgprTile, kVgprT1);
+    e.line("\tv_readfirstlane_b32 s%d, v%d", kSgprTile, kVgprT1);  // wave index inside the workgroup
     e.line("\ts_nop 4");
-    if (!sp.share_rows) {
-        // the waves of a workgroup run the same code block on adjacent column tiles
-        e.line("\ts_lshl_b32 s%d, s2, %d", kSgprTmp, tpw_shift);
-        e.line("\ts_add_u32 s%d, s%d, s%d", kSgprTile, kSgprTmp, kSgprTile);  // tile = tiles_per_wg*wg + wave
+    if (!lds) {
+        // grid (ceil(tiles/W), groups): the waves of a workgroup run one block on adjacent tiles
+        e.line("\ts_lshl_b32 s%d, s2, %d", kSgprTmp, wshift);
+        e.line("\ts_add_u32 s%d, s%d, s%d", kSgprTile, kSgprTmp, kSgprTile);
         e.line("\ts_mov_b32 s%d, s3", kSgprBlock);
-    } else {
-        // the waves of a workgroup run adjacent code blocks on the same column tile, so the B
-        // rows one wave pulls into the L1 are hits for the others
-        e.line("\ts_lshl_b32 s%d, s3, %d", kSgprTmp, tpw_shift);
-        e.line("\ts_add_u32 s%d, s%d, s%d", kSgprBlock, kSgprTmp, kSgprTile);  // block = waves*wg + wave
-        e.line("\ts_mov_b32 s%d, s2", kSgprTile);
-        e.line("\ts_cmp_ge_u32 s%d, %d", kSgprBlock, G);
+        e.line("\ts_cmp_ge_u32 s%d, %d", kSgprTile, sp.n_tiles);
         e.line("\ts_cbranch_scc1 .Lend");
+    } else {
+        // grid (tiles, blocks/W): the waves of a workgroup run adjacent blocks on one tile;
+        // the block list is padded, so every wave of every workgroup has a block
+        e.line("\ts_lshl_b32 s%d, s3, %d", kSgprTmp, wshift);
+        e.line("\ts_add_u32 s%d, s%d, s%d", kSgprBlock, kSgprTmp, kSgprTile);
+        e.line("\ts_mov_b32 s%d, s2", kSgprTile);
+        e.line("\tv_lshlrev_b32_e32 v%d, 4, v%d", kVgprLds, kVgprOff);  // lane * 16
     }
-    e.line("\ts_cmp_ge_u32 s%d, %d", kSgprTile, sp.n_tiles);
-    e.line("\ts_cbranch_scc1 .Lend");
     e.line("\ts_mul_i32 s%d, s%d, %d", kSgprTmp, kSgprTile, sp.lanes_per_tile);  // first column of the tile
     e.line("\tv_add_u32_e32 v%d, s%d, v%d", kVgprT1, kSgprTmp, kVgprOff);        // this lane's column
     e.line("\ts_mov_b32 s%d, %d", kSgprTmp2, N);
@@ -278,7 +482,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\ts_and_b32 s%d, s%d, 0xffff", kRsrcC + 1, kSgprC + 1);
     e.line("\ts_mov_b32 s%d, 0x%llx", kRsrcC + 2, (unsigned long long)c_bytes);
     e.line("\ts_mov_b32 s%d, 0x%x", kRsrcC + 3, kRsrcWord3);
-    // jump to the code of this row group through a table of offsets kept in the text section
+    // jump to the code of this block through a table of offsets kept in the text section
     e.line("\ts_getpc_b64 s[%d:%d]", kSgprPc, kSgprPc + 1);
     e.line(".Lpc:");
     e.line("\ts_add_u32 s%d, s%d, .Ltable-.Lpc", kSgprPc, kSgprPc);
@@ -293,61 +497,20 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\ts_endpgm");
     e.line("\t.p2align 2");
     e.line(".Ltable:");
-    for (int g = 0; g < G; ++g) e.line("\t.long .Lg%d-.Ltable", g);
+    for (int g = 0; g < n_blocks; ++g) e.line("\t.long .Lg%d-.Ltable", g);
 
-    // One straight-line block per row group.
-    struct Term { int acc; uint32_t bits; };
-    sp.group_columns.assign(G, 0);
-    for (int g = 0; g < G; ++g) {
-        const std::vector<int32_t> &rows = members[g];
-        std::map<int32_t, std::vector<Term>> cols;  // column -> nonzeros of this group
-        for (size_t i = 0; i < rows.size(); ++i) {
-            const int32_t slot = rows[i];
-            for (int32_t p = h.p_row_ptr[slot]; p < h.p_row_ptr[slot + 1]; ++p)
-                cols[h.p_col_idx[p]].push_back({(int)i, h.stream[2 * (size_t)p + 1]});
-        }
-        std::vector<int32_t> order;
-        order.reserve(cols.size());
-        for (auto &kv : cols) order.push_back(kv.first);
-        const int nc = (int)order.size();
-        sp.group_columns[g] = nc;
+    sp.group_columns.assign(n_blocks, 0);
+    for (int g = 0; g < n_blocks; ++g) {
         e.line("\t.p2align 2");
         e.line(".Lg%d:", g);
-        for (size_t i = 0; i < rows.size(); ++i) e.line("\tv_mov_b32_e32 v%d, 0", kVgprAcc0 + (int)i);
-        const int xp = getenv("SPARSERT_SPEC_XP") ? atoi(getenv("SPARSERT_SPEC_XP")) : 0;  // timing experiments only
-        auto issue_load = [&](int j) {
-            if ((xp & 2) && j >= D) return;
-            const int sreg = kSgprOffRing + (j % kOffRing);
-            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)order[j] * N * 4));
-            e.line("\tbuffer_load_dword v%d, v%d, s[%d:%d], s%d offen", vgpr_b0 + (j % D), kVgprOff,
-                   kRsrcB, kRsrcB + 3, sreg);
-        };
-        for (int j = 0; j < std::min(D, nc); ++j) issue_load(j);
-        for (int j = 0; j < nc; ++j) {
-            // loads issued so far: columns [0, min(nc, j + D)); those after column j may stay in flight
-            if (!(xp & 2)) e.line("\ts_waitcnt vmcnt(%d)", std::min(nc, j + D) - 1 - j);
-            else if (j == 0) e.line("\ts_waitcnt vmcnt(0)");
-            for (const Term &t : cols[order[j]]) {
-                if (xp & 1) e.line("\tv_fmac_f32_e32 v%d, v%d, v%d", kVgprAcc0 + t.acc, vgpr_b0 + (j % D), vgpr_b0 + (j % D));
-                else e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vgpr_b0 + (j % D));
-            }
-            if (j + D < nc) issue_load(j + D);
-        }
-        e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
-        for (size_t i = 0; i < rows.size(); ++i) {
-            const int sreg = kSgprOffRing + ((int)i % kOffRing);
-            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i]] * N * 4));
-            e.line("\tbuffer_store_dword v%d, v%d, s[%d:%d], s%d offen", kVgprAcc0 + (int)i, kVgprOff,
-                   kRsrcC, kRsrcC + 3, sreg);
-        }
-        e.line("\ts_endpgm");
+        sp.group_columns[g] = lds ? gen.block_lds(members[g], g % W, W) : gen.block_direct(members[g]);
     }
     e.line(".Lfunc_end:");
     e.line("\t.size\tsparsert_spec, .Lfunc_end-sparsert_spec");
     e.line("\t.section\t.rodata,\"a\",@progbits");
     e.line("\t.p2align\t6, 0x0");
     e.line("\t.amdhsa_kernel sparsert_spec");
-    e.line("\t\t.amdhsa_group_segment_fixed_size 0");
+    e.line("\t\t.amdhsa_group_segment_fixed_size %d", gen.lds_bytes);
     e.line("\t\t.amdhsa_private_segment_fixed_size 0");
     e.line("\t\t.amdhsa_kernarg_size 16");
     e.line("\t\t.amdhsa_user_sgpr_count 2");
@@ -394,10 +557,10 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("        .offset:         8");
     e.line("        .size:           8");
     e.line("        .value_kind:     global_buffer");
-    e.line("    .group_segment_fixed_size: 0");
+    e.line("    .group_segment_fixed_size: %d", gen.lds_bytes);
     e.line("    .kernarg_segment_align: 8");
     e.line("    .kernarg_segment_size: 16");
-    e.line("    .max_flat_workgroup_size: %d", sp.tiles_per_wg * kWave);
+    e.line("    .max_flat_workgroup_size: %d", W * kWave);
     e.line("    .name:           sparsert_spec");
     e.line("    .private_segment_fixed_size: 0");
     e.line("    .sgpr_count:     %d", kNextFreeSgpr + 6);

@@ -1,0 +1,145 @@
+// Autotuner (Section 3.7 of the paper): exhaustive search over a short, hand-picked list
+// of executor configurations for one problem, each built by the inspector and timed on
+// the GPU; the fastest plan is kept.  The paper tunes (M_blocks, N_blocks, Gy); the knobs
+// here are the executor family, columns per lane, rows per generated code block, waves
+// per workgroup and the staging variant.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "plan.h"
+
+namespace {
+
+struct Candidate { sparsert_options opt; };
+
+float time_plan(sparsert_plan *p, bool conv, const void *in, void *out, hipStream_t s,
+                hipEvent_t e0, hipEvent_t e1, int launches, int repeats) {
+    auto run = [&]() { return conv ? sparsert_conv3x3(p, in, out, s) : sparsert_spmm(p, in, out, s); };
+    for (int i = 0; i < 5; ++i)
+        if (run() != SPARSERT_OK) return -1.0f;
+    float best = -1.0f;
+    for (int r = 0; r < repeats; ++r) {
+        if (hipEventRecord(e0, s) != hipSuccess) return -1.0f;
+        for (int i = 0; i < launches; ++i)
+            if (run() != SPARSERT_OK) return -1.0f;
+        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1.0f;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.0f;
+        const float us = ms * 1000.0f / launches;
+        if (best < 0.0f || us < best) best = us;
+    }
+    return best;
+}
+
+}  // namespace
+
+extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
+                             int32_t M, int32_t K, int32_t N, const sparsert_options *base,
+                             const void *in_dev, void *out_dev, void *stream,
+                             sparsert_plan **out, sparsert_tune_report *report) {
+    if (out) *out = nullptr;
+    if (report) std::memset(report, 0, sizeof(*report));
+    sparsert_options b;
+    if (base) b = *base; else std::memset(&b, 0, sizeof(b));
+    b.host_only = 0;
+    // First candidate: the inspector's own choice.  It also validates every argument.
+    sparsert_plan *best = nullptr;
+    {
+        sparsert_options o = b;
+        o.kernel = SPARSERT_KERNEL_ROWS;
+        if (int rc = sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &best)) return rc;
+    }
+    if (!out || !in_dev || !out_dev || (((uintptr_t)in_dev | (uintptr_t)out_dev) & 15u)) {
+        sparsert_plan_destroy(best);
+        return sparsert::set_error(SPARSERT_EINVAL, "out is NULL, or a device pointer is NULL or not 16-byte aligned");
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        sparsert_plan_destroy(best);
+        return sparsert::set_error(SPARSERT_EHIP, "hipEventCreate failed");
+    }
+    const bool conv = b.conv != 0, f16 = b.dtype == SPARSERT_F16;
+    const int64_t nnz = row_ptr[M];
+    const int launches = 30, repeats = 3;
+
+    std::vector<sparsert_options> cands;
+    if (!conv) {
+        for (int v = 1; v <= (f16 ? 8 : 4); v *= 2) {
+            if (N % v) continue;
+            sparsert_options o = b;
+            o.kernel = SPARSERT_KERNEL_ROWS; o.vec = v;
+            cands.push_back(o);
+            o.split_threshold = 64;
+            cands.push_back(o);
+        }
+    } else {
+        for (int thr : {32, 64, 1 << 30}) {
+            sparsert_options o = b;
+            o.kernel = SPARSERT_KERNEL_ROWS; o.split_threshold = thr;
+            cands.push_back(o);
+        }
+    }
+    if (!conv && !f16 && nnz <= (4 << 20)) {
+        const int64_t tiles = (N + 63) / 64;
+        for (int r : {1, 2, 4, 8, 16, 24, 48}) {
+            if (r > M) continue;
+            const int64_t groups = (M + r - 1) / r;
+            if (r > 1 && groups * tiles < 256) continue;   // too few waves to be worth assembling
+            if (groups > 8192) continue;
+            for (int t : {2, 4}) {
+                sparsert_options o = b;
+                o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
+                o.spec_rows = r; o.spec_tiles = t;
+                cands.push_back(o);
+            }
+        }
+        if (K >= 256 && (int64_t)M * tiles >= 1024) {
+            for (int r : {12, 24, 48})
+                for (int w : {4, 8}) {
+                    if (((int64_t)M + r - 1) / r < w) continue;
+                    sparsert_options o = b;
+                    o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_LDS;
+                    o.spec_rows = r; o.spec_tiles = w;
+                    cands.push_back(o);
+                }
+        }
+    }
+
+    float best_us = time_plan(best, conv, in_dev, out_dev, s, e0, e1, launches, repeats);
+    auto log = [&](const sparsert_plan *p, float us) {
+        if (!report || report->count >= SPARSERT_TUNE_MAX) return;
+        sparsert_tune_entry &t = report->entries[report->count++];
+        const sparsert::HostPlan &h = p->host;
+        t.kernel = h.kernel; t.vec = h.vec; t.split_threshold = h.split_threshold;
+        t.spec_mode = h.spec.mode; t.spec_rows = h.spec.rows_per_group; t.spec_tiles = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.tiles_per_wg : 0;
+        t.microseconds = us;
+    };
+    log(best, best_us);
+    for (const sparsert_options &o : cands) {
+        sparsert_plan *p = nullptr;
+        if (sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &p) != SPARSERT_OK) continue;
+        const float us = time_plan(p, conv, in_dev, out_dev, s, e0, e1, launches, repeats);
+        log(p, us);
+        if (us > 0.0f && (best_us <= 0.0f || us < best_us)) {
+            sparsert_plan_destroy(best);
+            best = p; best_us = us;
+        } else {
+            sparsert_plan_destroy(p);
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (report) report->best_microseconds = best_us;
+    if (best_us <= 0.0f) {
+        sparsert_plan_destroy(best);
+        return sparsert::set_error(SPARSERT_EHIP, "no candidate configuration could be launched and timed");
+    }
+    *out = best;
+    return SPARSERT_OK;
+}

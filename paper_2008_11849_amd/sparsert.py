@@ -17,16 +17,17 @@ LIB_PATH = os.path.join(_HERE, "libsparsert.so")
 OK, EINVAL, ENOMEM, EHIP, EUNSUPPORTED, ECOMPILE = 0, -1, -2, -3, -4, -5
 F32, F16 = 0, 1
 KERNEL_AUTO, KERNEL_ROWS, KERNEL_SPEC = 0, 1, 2
+SPEC_AUTO, SPEC_DIRECT, SPEC_LDS = 0, 1, 2
 (FIELD_INFO, FIELD_ROW_NNZ, FIELD_HIST, FIELD_PERM, FIELD_INV_PERM, FIELD_P_ROW_PTR,
  FIELD_P_COL_IDX, FIELD_P_VALS, FIELD_BINS, FIELD_STREAM, FIELD_CONV_SEG,
  FIELD_SEGMENTS, FIELD_SPEC_GROUPS, FIELD_SPEC_COLUMNS, FIELD_SPEC_CODE) = range(15)
 INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", "vec",
               "lanes_per_tile", "n_tiles", "gy", "split_threshold", "n_split", "n_wg_rows",
               "n_bins", "spec_rows", "spec_groups", "spec_depth", "spec_code_bytes",
-              "spec_tiles"]
-INFO_COUNT = 24
+              "spec_tiles", "spec_mode", "spec_lds_bytes"]
+INFO_COUNT = 32
 
-EXPORTED = ["sparsert_inspect", "sparsert_spmm", "sparsert_conv3x3", "sparsert_plan_export",
+EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_plan_export",
             "sparsert_plan_destroy", "sparsert_last_error", "sparsert_version"]
 
 
@@ -36,7 +37,22 @@ class Options(ctypes.Structure):
                 ("batch", ctypes.c_int32), ("host_only", ctypes.c_int32),
                 ("vec", ctypes.c_int32), ("split_threshold", ctypes.c_int32),
                 ("spec_rows", ctypes.c_int32), ("spec_depth", ctypes.c_int32),
-                ("spec_tiles", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("spec_tiles", ctypes.c_int32), ("spec_mode", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
+
+
+TUNE_MAX = 64
+
+
+class TuneEntry(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("vec", ctypes.c_int32), ("split_threshold", ctypes.c_int32),
+                ("spec_mode", ctypes.c_int32), ("spec_rows", ctypes.c_int32),
+                ("spec_tiles", ctypes.c_int32), ("microseconds", ctypes.c_float)]
+
+
+class TuneReport(ctypes.Structure):
+    _fields_ = [("count", ctypes.c_int32), ("best_microseconds", ctypes.c_float),
+                ("entries", TuneEntry * TUNE_MAX)]
 
 
 class SparseRTError(RuntimeError):
@@ -62,6 +78,9 @@ _vp, _i32 = ctypes.c_void_p, ctypes.c_int32
 _lib.sparsert_inspect.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, ctypes.POINTER(Options),
                                   ctypes.POINTER(_vp)]
 _lib.sparsert_inspect.restype = ctypes.c_int
+_lib.sparsert_tune.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, ctypes.POINTER(Options), _vp, _vp, _vp,
+                               ctypes.POINTER(_vp), ctypes.POINTER(TuneReport)]
+_lib.sparsert_tune.restype = ctypes.c_int
 _lib.sparsert_spmm.argtypes = [_vp, _vp, _vp, _vp]
 _lib.sparsert_spmm.restype = ctypes.c_int
 _lib.sparsert_conv3x3.argtypes = [_vp, _vp, _vp, _vp]
@@ -129,7 +148,8 @@ class Plan:
 def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[int] = None,
             conv: Optional[Tuple[int, int, int]] = None, batch: int = 0, host_only: bool = False,
             vec: int = 0, split_threshold: int = 0, kernel: int = KERNEL_AUTO,
-            spec_rows: int = 0, spec_depth: int = 0, spec_tiles: int = 0) -> Plan:
+            spec_rows: int = 0, spec_depth: int = 0, spec_tiles: int = 0,
+            spec_mode: int = 0) -> Plan:
     """sparsert_inspect.  `vals` must already be float32 or float16; it is not converted."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -145,6 +165,7 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
     opt.dtype, opt.kernel, opt.host_only = dtype, kernel, int(host_only)
     opt.vec, opt.split_threshold, opt.batch = vec, split_threshold, batch
     opt.spec_rows, opt.spec_depth, opt.spec_tiles = spec_rows, spec_depth, spec_tiles
+    opt.spec_mode = spec_mode
     if conv is not None:
         opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
     handle = _vp()
@@ -152,6 +173,27 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
                                  vals.ctypes.data_as(_vp), M, K, N, ctypes.byref(opt),
                                  ctypes.byref(handle)))
     return Plan(handle.value, dtype)
+
+
+def tune(row_ptr, col_idx, vals, M: int, K: int, N: int, in_dev: int, out_dev: int, stream: int = 0, *,
+         conv: Optional[Tuple[int, int, int]] = None):
+    """sparsert_tune: returns (best plan, list of timed candidates as dicts)."""
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals)
+    if vals.dtype not in (np.float16, np.float32):
+        raise TypeError("vals must be float32 or float16")
+    opt = Options()
+    opt.dtype = F16 if vals.dtype == np.float16 else F32
+    if conv is not None:
+        opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
+    handle, rep = _vp(), TuneReport()
+    _check(_lib.sparsert_tune(row_ptr.ctypes.data_as(_vp), col_idx.ctypes.data_as(_vp),
+                              vals.ctypes.data_as(_vp), M, K, N, ctypes.byref(opt), in_dev, out_dev,
+                              stream, ctypes.byref(handle), ctypes.byref(rep)))
+    names = [f[0] for f in TuneEntry._fields_]
+    entries = [{n: getattr(rep.entries[i], n) for n in names} for i in range(rep.count)]
+    return Plan(handle.value, opt.dtype), entries
 
 
 def spmm(plan: Plan, B_dev: int, C_dev: int, stream: int = 0):

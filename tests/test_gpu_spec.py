@@ -20,45 +20,65 @@ def _oracle(csr, B):
     return ref.spmm(csr.M, csr.K, B.shape[1], csr.row_ptr, csr.col_idx, csr.vals, B)
 
 
+MODES = [sp.SPEC_DIRECT, sp.SPEC_LDS]
+
+
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("N", [1, 3, 49, 63, 64, 65, 196, 256, 300])
 @pytest.mark.parametrize("rows", [0, 1, 5, 64])
-def test_spec_small_integers_bit_exact(N, rows):
+def test_spec_small_integers_bit_exact(N, rows, mode):
     csr = synth.small_int_csr(77, 130, 0.85, N)
     B = synth.small_int_dense(130, N, N + 1)
     Cref, _ = _oracle(csr, B)
-    got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=rows)
-    assert info["kernel"] == sp.KERNEL_SPEC and info["spec_code_bytes"] > 0
+    got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_mode=mode)
+    assert info["kernel"] == sp.KERNEL_SPEC and info["spec_code_bytes"] > 0 and info["spec_mode"] == mode
     assert np.array_equal(got.astype(np.float64), Cref), (N, rows)
 
 
-def test_spec_empty_rows_dense_row_and_empty_matrix():
+@pytest.mark.parametrize("K", [1, 4, 127, 128, 129, 255, 257, 300, 515])
+@pytest.mark.parametrize("waves", [1, 2, 8, 16])
+def test_spec_lds_chunk_edges_and_wave_counts(K, waves):
+    # K around the 128-row staging chunk, with every workgroup width
+    csr = synth.small_int_csr(37, K, 0.5 if K < 16 else 0.9, K + waves)
+    B = synth.small_int_dense(K, 70, K)
+    Cref, _ = _oracle(csr, B)
+    got, _ = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_mode=sp.SPEC_LDS, spec_rows=3, spec_tiles=waves)
+    assert np.array_equal(got.astype(np.float64), Cref), (K, waves)
+    got, _ = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_mode=sp.SPEC_DIRECT, spec_rows=3, spec_tiles=waves)
+    assert np.array_equal(got.astype(np.float64), Cref), (K, waves)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_spec_empty_rows_dense_row_and_empty_matrix(mode):
     M, K, N = 40, 64, 130
     A = np.zeros((M, K), dtype=np.float32)
     A[5] = np.arange(1, K + 1)
     A[17, 3] = -2.0
     csr = synth.csr_from_mask(A, A != 0)
     B = synth.small_int_dense(K, N, 9)
-    got, _ = run_spmm(csr, B, kernel=sp.KERNEL_SPEC)
+    got, _ = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_mode=mode)
     Cref, _ = _oracle(csr, B)
     assert np.array_equal(got.astype(np.float64), Cref)
     assert not np.signbit(got[0]).any()
     empty = synth.csr_from_mask(np.zeros((M, K), np.float32), np.zeros((M, K), bool))
-    got, _ = run_spmm(empty, B, kernel=sp.KERNEL_SPEC)
+    got, _ = run_spmm(empty, B, kernel=sp.KERNEL_SPEC, spec_mode=mode)
     assert np.array_equal(got, np.zeros((M, N), np.float32)) and not np.signbit(got).any()
 
 
-def test_spec_identity_returns_B():
+@pytest.mark.parametrize("mode", MODES)
+def test_spec_identity_returns_B(mode):
     K, N = 300, 196
     B = synth.normal_dense(K, N, 3)
     eye = synth.csr_from_mask(np.eye(K, dtype=np.float32), np.eye(K, dtype=bool))
-    got, _ = run_spmm(eye, B, kernel=sp.KERNEL_SPEC)
+    got, _ = run_spmm(eye, B, kernel=sp.KERNEL_SPEC, spec_mode=mode)
     assert got.tobytes() == B.tobytes()
 
 
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c3t"])
-def test_spec_configs(name):
+def test_spec_configs(name, mode):
     case = synth.config(name)
-    got, info = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC)
+    got, info = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_mode=mode)
     Cref, S = _oracle(case.csr, case.B)
     m = check(got, Cref, S, np.float32, gate_relative=True)
     print(name, info, m)
@@ -66,9 +86,10 @@ def test_spec_configs(name):
 
 @pytest.mark.parametrize("M,K,N,s,kind", [(512, 1024, 784, 0.95, "skewed"), (1024, 512, 196, 0.9, "magnitude"),
                                          (256, 4096, 196, 0.8, "uniform"), (2048, 2048, 64, 0.98, "skewed")])
-def test_spec_sweep_subset(M, K, N, s, kind):
+@pytest.mark.parametrize("mode", MODES)
+def test_spec_sweep_subset(M, K, N, s, kind, mode):
     case = synth.sweep_case(M, K, N, s, kind, np.float32)
-    got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC)
+    got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_mode=mode)
     Cref, S = _oracle(case.csr, case.B)
     check(got, Cref, S, np.float32)
 
@@ -78,3 +99,40 @@ def test_spec_rejects_what_it_does_not_cover():
     with pytest.raises(sp.SparseRTError) as e:
         sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 16, 18, 8, kernel=sp.KERNEL_SPEC, host_only=True)
     assert e.value.status == sp.EUNSUPPORTED
+
+
+def test_tune_returns_a_correct_plan_and_a_report():
+    case = synth.config("c2")
+    csr = case.csr
+    dev = torch.device("cuda:0")
+    Bd = torch.from_numpy(case.B).to(dev)
+    Cd = torch.full((csr.M, case.N), float("nan"), device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    plan, report = sp.tune(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N,
+                           Bd.data_ptr(), Cd.data_ptr(), stream)
+    assert len(report) >= 4 and all(r["microseconds"] > 0 for r in report)
+    assert {r["kernel"] for r in report} == {sp.KERNEL_ROWS, sp.KERNEL_SPEC}
+    Cd.fill_(float("nan"))
+    sp.spmm(plan, Bd.data_ptr(), Cd.data_ptr(), stream)
+    torch.cuda.synchronize()
+    Cref, S = _oracle(csr, case.B)
+    check(Cd.cpu().numpy(), Cref, S, np.float32, gate_relative=True)
+    print(plan.info(), sorted(report, key=lambda r: r["microseconds"])[:3])
+    plan.destroy()
+
+
+def test_tune_covers_half_and_conv():
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    csr, Wd = synth.conv_weights_csr(24, 16, 0.9, 3, dtype=np.float16)
+    X = synth.normal_dense(16, 14 * 14, 4, dtype=np.float16).reshape(1, 16, 14, 14)
+    Xd = torch.from_numpy(X).to(dev)
+    Yd = torch.empty((1, 24, 14, 14), dtype=torch.float16, device=dev)
+    plan, report = sp.tune(csr.row_ptr, csr.col_idx, csr.vals, 24, 144, 196, Xd.data_ptr(), Yd.data_ptr(),
+                           stream, conv=(16, 14, 14))
+    assert len(report) >= 2
+    sp.conv3x3(plan, Xd.data_ptr(), Yd.data_ptr(), stream)
+    torch.cuda.synchronize()
+    Yref, S = ref.conv3x3(Wd, X)
+    check(Yd.cpu().numpy(), Yref, S, np.float16)
+    plan.destroy()
