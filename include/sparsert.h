@@ -102,7 +102,7 @@ typedef struct sparsert_options {
  * opt->host_only is set the plan's device arrays are allocated and uploaded
  * here (synchronously) on the current HIP device.
  * Errors: EINVAL for null pointers, non-positive sizes, malformed CSR, bad
- * options; EUNSUPPORTED for batch > 1 or for B, C or X of 2 GiB and more;
+ * options; EUNSUPPORTED for batch > 1, for B or C of 2 GiB and more, for X of 128 MiB and more;
  * ENOMEM / EHIP from allocation and upload.
  */
 int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
@@ -187,8 +187,9 @@ typedef enum sparsert_field {
     SPARSERT_FIELD_STREAM = 9,    /* uint32[nnz][2]: what the executor reads per nonzero:
                                      {operand byte offset as int32, value as binary32 bits}.
                                      SpMM: offset = col*N*sizeof(dtype), permuted-CSR order.
-                                     Conv: offset = (c*H*W + (r-1)*W + (s-1))*sizeof(dtype)
-                                     (may be negative), each slot ordered by (r*3+s, c) */
+                                     Conv: word = tap << 28 | (d & 0x0fffffff), tap = r*3+s,
+                                     d = (c*H*W + (r-1)*W + (s-1))*sizeof(dtype) (may be
+                                     negative); each slot ordered by (tap, c) */
     SPARSERT_FIELD_CONV_SEG = 10, /* conv only, int32[M][10]: stream positions where each
                                      (r,s) group of a slot starts; [9] = end of the slot */
     SPARSERT_FIELD_SEGMENTS = 11, /* int32[n_split][Gy+1]: stream positions bounding the

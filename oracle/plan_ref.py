@@ -21,9 +21,10 @@ Specification
                 s + min(g*share, n), g = 0..Gy  (all waves but the last get `share`)
   stream      = per nonzero {int32 byte offset, float32 bits of the value}
                 SpMM: offset = col*N*itemsize, permuted-CSR order
-                conv: k = c*9 + r*3 + s  ->  offset = (c*H*W + (r-1)*W + (s-1))*itemsize,
-                each slot stably reordered by tap t = r*3+s; conv_seg[slot] holds the ten
-                stream positions where the taps start/end
+                conv: k = c*9 + r*3 + s  ->  word = tap << 28 | (displacement & 0x0fffffff) with
+                tap = r*3+s and displacement = (c*H*W + (r-1)*W + (s-1))*itemsize; each slot
+                stably reordered by tap; conv_seg[slot] holds the ten stream positions where
+                the taps start/end
 """
 from __future__ import annotations
 
@@ -109,7 +110,7 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0):
         c, t = p_col // 9, p_col % 9
         r, s = t // 3, t % 3
         off = ((c * H * W + (r - 1) * W + (s - 1)) * item).astype(np.int64)
-        off32 = (off & 0xFFFFFFFF).astype(np.uint32)
+        off32 = ((off & 0x0FFFFFFF) | (t << 28)).astype(np.uint32)
         conv_seg = np.zeros((M, 10), dtype=np.int64)
         for slot in range(M):
             a, b = int(p_row_ptr[slot]), int(p_row_ptr[slot + 1])

@@ -76,8 +76,8 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
         if ((int64_t)N != (int64_t)opt.H * opt.W) { err = "conv needs N == H*W"; return SPARSERT_EINVAL; }
         if (opt.batch > 1) { err = "conv batch > 1 is not implemented"; return SPARSERT_EUNSUPPORTED; }
         if (opt.batch < 0) { err = "batch must be >= 0"; return SPARSERT_EINVAL; }
-        if (((int64_t)opt.Cin * opt.H * opt.W + opt.W + 1) * esz >= (1ll << 31)) {
-            err = "conv input too large for 32-bit operand offsets"; return SPARSERT_EUNSUPPORTED;
+        if (((int64_t)opt.Cin * opt.H * opt.W + opt.W + 1) * esz >= (1ll << 27)) {
+            err = "conv input too large for 28-bit operand displacements"; return SPARSERT_EUNSUPPORTED;
         }
     } else if ((int64_t)K * N * esz >= (1ll << 31) || (int64_t)M * N * esz >= (1ll << 31)) {
         err = "B or C reaches 2 GiB: operand offsets are 32-bit"; return SPARSERT_EUNSUPPORTED;
@@ -196,7 +196,8 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
     } else {
         // Section 3.6: each reference to B[k, oh*W+ow], k = c*9 + r*3 + s, is the input
         // element X[c, oh+r-1, ow+s-1].  Relative to pixel (oh,ow) of channel 0 that is the
-        // fixed (possibly negative) displacement c*H*W + (r-1)*W + (s-1).
+        // fixed (possibly negative) displacement c*H*W + (r-1)*W + (s-1).  The stream word holds
+        // the tap r*3+s in its top 4 bits and the byte displacement in the low 28 (two's complement).
         // Inside a slot the nonzeros are grouped by tap (r,s) so that the padding test is
         // made once per group instead of once per multiply-add.
         h.conv_seg.resize((size_t)M * 10);
@@ -213,7 +214,7 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
                 const int32_t k = h.p_col_idx[p], c = k / 9, rs = k % 9, r = rs / 3, s = rs % 3;
                 const int32_t q = pos[rs]++;
                 const int64_t off = (int64_t)c * HW + (r - 1) * h.W + (s - 1);
-                h.stream[2 * (size_t)q] = (uint32_t)(int32_t)(off * esz);
+                h.stream[2 * (size_t)q] = ((uint32_t)(int32_t)(off * esz) & 0x0fffffffu) | ((uint32_t)rs << 28);
                 h.stream[2 * (size_t)q + 1] = value_bits(p);
             }
         }

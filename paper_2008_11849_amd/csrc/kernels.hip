@@ -50,32 +50,57 @@ __device__ __forceinline__ void store_cols(T *dst, const float (&acc)[V]) {
     *reinterpret_cast<vec_t *>(dst) = v;
 }
 
-// acc[:] += sum over stream positions [p0, p1) of value * operand(in + offset + lane_off).
-// p0, p1, the stream and `in` are wave-uniform: the {offset, value} pairs arrive through
-// scalar loads, in + offset is a scalar address, lane_off the only per-lane part.
-template <typename T, int V>
+// One operand fetch.  SpMM: the stream word is the byte offset of B's row.  Convolution: the
+// top 4 bits name the filter tap (r*3+s), the low 28 bits are the signed byte displacement of
+// X[c, oh+r-1, ow+s-1] from X[0, oh, ow]; the caller only walks a tap's nonzeros with the lanes
+// whose tap lies inside the image, so no test is needed here.
+template <typename T, int V, bool CONV>
+__device__ __forceinline__ void fetch(gbytes in, uint32_t lane_off, uint32_t word, float (&b)[V]) {
+    const int32_t disp = CONV ? (int32_t)(word << 4) >> 4 : (int32_t)word;
+    load_cols<T, V>(in + disp + lane_off, b);
+}
+
+// acc[:] += sum over stream positions [p0, p1) of value * operand.  p0, p1, the stream and
+// `in` are wave-uniform: the {word, value} pairs arrive through scalar loads (the pairs of the
+// next chunk are requested before the current chunk's operands are waited for), lane_off is
+// the only per-lane part of an address.  The stream is padded by 2*U pairs, so pair loads
+// never need a guard.
+template <typename T, int V, bool CONV>
 __device__ __forceinline__ void walk(const uint2 *__restrict__ stream, int p0, int p1,
                                      gbytes in, uint32_t lane_off, float (&acc)[V]) {
     constexpr int U = 8;
     int p = p0;
+    uint2 e[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) e[i] = stream[p + i];
     for (; p + U <= p1; p += U) {
-        uint2 e[U];
+        uint2 en[U];
         float b[U][V];
 #pragma unroll
-        for (int i = 0; i < U; ++i) e[i] = stream[p + i];
+        for (int i = 0; i < U; ++i) en[i] = stream[p + U + i];
 #pragma unroll
-        for (int i = 0; i < U; ++i) load_cols<T, V>(in + (int32_t)e[i].x + lane_off, b[i]);
+        for (int i = 0; i < U; ++i) fetch<T, V, CONV>(in, lane_off, e[i].x, b[i]);
 #pragma unroll
         for (int i = 0; i < U; ++i)
 #pragma unroll
             for (int j = 0; j < V; ++j) acc[j] = __builtin_fmaf(__uint_as_float(e[i].y), b[i][j], acc[j]);
-    }
-    for (; p < p1; ++p) {
-        const uint2 e = stream[p];
-        float b[V];
-        load_cols<T, V>(in + (int32_t)e.x + lane_off, b);
 #pragma unroll
-        for (int j = 0; j < V; ++j) acc[j] = __builtin_fmaf(__uint_as_float(e.y), b[j], acc[j]);
+        for (int i = 0; i < U; ++i) e[i] = en[i];
+    }
+    // Tail of fewer than U nonzeros: same shape as a full chunk so the operand loads still go
+    // out together.  Loads past the tail are redirected to a row this wave reads anyway; only
+    // the multiply-adds are guarded (by a wave-uniform count).
+    const int rem = p1 - p;
+    if (rem > 0) {
+        float b[U - 1][V];
+#pragma unroll
+        for (int i = 0; i < U - 1; ++i) fetch<T, V, CONV>(in, lane_off, i < rem ? e[i].x : e[0].x, b[i]);
+#pragma unroll
+        for (int i = 0; i < U - 1; ++i)
+            if (i < rem) {
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[j] = __builtin_fmaf(__uint_as_float(e[i].y), b[i][j], acc[j]);
+            }
     }
 }
 
@@ -148,13 +173,15 @@ __global__ __launch_bounds__(kGy *kWave) void rows_kernel(const RowsArgs a) {
     }
 
     if constexpr (CONV) {
+        // The slot's nonzeros are grouped by tap (Section 3.6: the padding test is resolved
+        // ahead of time): one lane mask per group instead of a test per multiply-add.
         const int32_t *seg = a.conv_seg + slot * 10;
         for (int t = 0; t < 9; ++t) {
             const int q0 = max(p0, seg[t]), q1 = min(p1, seg[t + 1]);
-            if (q0 < q1 && ((tap_ok >> t) & 1u)) walk<T, 1>(a.stream, q0, q1, in, lane_off, acc);
+            if (q0 < q1 && ((tap_ok >> t) & 1u)) walk<T, 1, true>(a.stream, q0, q1, in, lane_off, acc);
         }
     } else {
-        walk<T, V>(a.stream, p0, p1, in, lane_off, acc);
+        walk<T, V, false>(a.stream, p0, p1, in, lane_off, acc);
     }
 
     if (split) {
@@ -201,7 +228,11 @@ int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err) {
     HIP_TRY(hipGetDevice(&d.device));
     if (int rc = to_device(h.p_row_ptr.data(), h.p_row_ptr.size(), &d.p_row_ptr, err)) return rc;
     if (int rc = to_device(h.perm.data(), h.perm.size(), &d.perm, err)) return rc;
-    if (int rc = to_device(h.stream.data(), h.stream.size(), &d.stream, err)) return rc;
+    {   // the executor may read up to 16 {word, value} pairs past the last nonzero
+        std::vector<uint32_t> padded(h.stream);
+        padded.resize(h.stream.size() + 32, 0u);
+        if (int rc = to_device(padded.data(), padded.size(), &d.stream, err)) return rc;
+    }
     if (int rc = to_device(h.segments.data(), h.segments.size(), &d.segments, err)) return rc;
     if (int rc = to_device(h.conv_seg.data(), h.conv_seg.size(), &d.conv_seg, err)) return rc;
     if (h.kernel == SPARSERT_KERNEL_SPEC) {
