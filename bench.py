@@ -39,13 +39,21 @@ def parse_args():
     ap.add_argument("--no-cases", action="store_true", help="skip the side table of the other configs")
     ap.add_argument("--kernel", default="tune", choices=["tune", "rows", "spec"],
                     help="tune: sparsert_tune picks the executor per layer (default); rows/spec: fixed family")
+    ap.add_argument("--plan-file", default=None,
+                    help="JSON of tuned per-layer options: read if it exists (no tuning in this process, so a "
+                         "profile sees only the chosen kernels), else written after tuning")
+    ap.add_argument("--pmc-mode", action="store_true",
+                    help="for rocprofv3 --pmc runs: a 256 MiB copy (counter calibration), then 20 launches "
+                         "of every layer of the workload, nothing else")
     return ap.parse_args()
 
 
 class Layer:
     """One sparse layer resident on the GPU: plan, input, output and its dense twin."""
 
-    def __init__(self, case, torch, sp, kernel="tune"):
+    PLAN_KEYS = ("kernel", "vec", "split_threshold", "spec_mode", "spec_rows", "spec_tiles")
+
+    def __init__(self, case, torch, sp, kernel="tune", fixed=None):
         import numpy as np
         self.case, self.torch, self.sp = case, torch, sp
         csr = case.csr
@@ -65,7 +73,9 @@ class Layer:
             self.Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
             self.fn = sp.raw.sparsert_spmm
         self.tuned = None
-        if kernel == "tune":
+        if fixed is not None:
+            self.plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N, conv=case.conv, **fixed)
+        elif kernel == "tune":
             # offline, once per matrix (Section 3.7); not part of the timed region
             self.plan, self.tuned = sp.tune(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N,
                                             self.inp.data_ptr(), self.out.data_ptr(),
@@ -166,7 +176,27 @@ def main():
 
     names = {"c1": ["c1"], "c2": ["c2"], "c3": ["c3", "c3t"], "c4": ["c4"]}[args.workload]
     cases = [synth.config(n, dt) for n in names]
-    layers = [Layer(c, torch, sp, kernel) for c in cases]
+    saved = {}
+    if args.plan_file and os.path.exists(args.plan_file):
+        saved = json.load(open(args.plan_file))
+    layers = [Layer(c, torch, sp, kernel, saved.get(f"{c.name}_{args.dtype}")) for c in cases]
+    if args.plan_file and not saved:
+        with open(args.plan_file, "w") as f:
+            json.dump({f"{L.case.name}_{args.dtype}": {k: L.info[k] for k in Layer.PLAN_KEYS} for L in layers}, f)
+
+    if args.pmc_mode:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        for L in layers:
+            for _ in range(20):
+                L.launch(stream)
+            torch.cuda.synchronize()
+        print(json.dumps({"pmc_mode": True, "copy_bytes": src.numel() * 4,
+                          "layers": [{"layer": L.case.name, "plan": L.info} for L in layers]}))
+        return
 
     def step():
         for L in layers:
