@@ -129,3 +129,13 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0):
                 p_vals=np.ascontiguousarray(p_vals), bins=i32(np.array(bins).reshape(-1)),
                 stream=stream.reshape(-1), conv_seg=i32(conv_seg.reshape(-1)),
                 segments=i32(segments.reshape(-1)))
+
+
+def spec_groups(M, rows_per_group):
+    """Code block of every slot in the generated kernel: serpentine dealing of the
+    nnz-descending slots over G = ceil(M/R) blocks (block-level balance, Section 3.4)."""
+    R = min(rows_per_group, M)
+    G = -(-M // R)
+    i = np.arange(M)
+    rnd, pos = i // G, i % G
+    return np.where(rnd % 2 == 1, G - 1 - pos, pos).astype(np.int32)

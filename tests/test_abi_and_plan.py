@@ -189,3 +189,45 @@ def test_null_pointers_and_host_only_execution_are_rejected():
     buf = (ctypes.c_int32 * 4)()
     assert lib.sparsert_plan_export(plan.handle, sp.FIELD_PERM, buf, 16, None) == sp.EINVAL
     lib.sparsert_plan_destroy(None)
+
+
+@pytest.mark.parametrize("mode", [sp.SPEC_DIRECT, sp.SPEC_LDS])
+@pytest.mark.parametrize("rows", [1, 7, 24])
+def test_generated_kernel_plan_assembles_on_the_host(rows, mode):
+    csr = synth.magnitude_csr(100, 300, 0.9, 3)
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 100, 300, 196, host_only=True,
+                      kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_mode=mode)
+    info = plan.info()
+    assert info["kernel"] == sp.KERNEL_SPEC and info["spec_rows"] == rows and info["spec_mode"] == mode
+    groups = plan.export(sp.FIELD_SPEC_GROUPS)
+    assert groups.tobytes() == plan_ref.spec_groups(100, rows).tobytes()
+    assert np.bincount(groups).max() <= rows
+    code = plan.export(sp.FIELD_SPEC_CODE)
+    assert code[:4].tobytes() == b"\x7fELF" and code.size == info["spec_code_bytes"]
+    # block balance: nonzeros per block within one row's worth of each other
+    nn = np.diff(plan.export(sp.FIELD_P_ROW_PTR))
+    per_block = np.bincount(groups, weights=nn)
+    assert per_block.max() - per_block.min() <= nn.max()
+    cols = plan.export(sp.FIELD_SPEC_COLUMNS)
+    assert cols[:info["spec_groups"]].sum() >= len(np.unique(csr.col_idx))
+    # the row-walk plan arrays are unaffected by the choice of executor
+    _assert_plan_equal(plan, {**plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, 100, 300, 196),
+                              "info": {"M": 100, "nnz": csr.nnz}})
+
+
+def test_generated_kernel_option_errors():
+    csr = synth.uniform_csr(16, 18, 0.5, 1)
+    args = (csr.row_ptr, csr.col_idx, csr.vals, 16, 18, 8)
+    for kw in ({"spec_tiles": 3}, {"spec_mode": 9}, {"spec_depth": 99}, {"spec_rows": 500}):
+        with pytest.raises(sp.SparseRTError) as e:
+            sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, **kw)
+        assert e.value.status == sp.EINVAL, kw
+    ccsr, _ = synth.conv_weights_csr(4, 2, 0.5, 1)
+    with pytest.raises(sp.SparseRTError) as e:
+        sp.inspect(ccsr.row_ptr, ccsr.col_idx, ccsr.vals, 4, 18, 16, conv=(2, 4, 4), host_only=True,
+                   kernel=sp.KERNEL_SPEC)
+    assert e.value.status == sp.EUNSUPPORTED
+    # tune validates before it touches the GPU
+    out, rep = ctypes.c_void_p(1), sp.TuneReport()
+    rc = sp.raw.sparsert_tune(None, None, None, 1, 1, 1, None, 16, 16, None, ctypes.byref(out), ctypes.byref(rep))
+    assert rc == sp.EINVAL and out.value is None
