@@ -197,7 +197,6 @@ struct Gen {
     int N, K, D;
     int vgpr_stage0 = 0, vgpr_ring0 = 0, n_vgpr = 0, lds_bytes = 0;
     int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
-    int xp = 0;  // timing experiments only (SPARSERT_SPEC_XP)
     Gen(const HostPlan &hp, SpecPlan &s) : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth) {}
 
     void zero_accs(size_t n) {
@@ -205,8 +204,7 @@ struct Gen {
     }
     void fmas(const std::vector<Term> &terms, int vb) {
         for (const Term &t : terms) {
-            if (xp & 1) e.line("\tv_fmac_f32_e32 v%d, v%d, v%d", kVgprAcc0 + t.acc, vb, vb);
-            else e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vb);
+            e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vb);
         }
     }
     void load_b_row(int k, int vdst, int ring_pos) {
@@ -218,7 +216,6 @@ struct Gen {
         if (rows.empty()) return;
         e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
         for (size_t i = 0; i < rows.size(); ++i) {
-            if ((xp & 4) && i > 0) break;
             const int sreg = kSgprOffRing + ((int)i % kOffRing);
             e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i]] * N * 4));
             e.line("\tbuffer_store_dword v%d, v%d, s[%d:%d], s%d offen", kVgprAcc0 + (int)i, kVgprOff,
@@ -244,15 +241,11 @@ struct Gen {
         for (auto &kv : cols) order.push_back(kv.first);
         const int nc = (int)order.size();
         zero_accs(rows.size());
-        auto issue = [&](int j) {
-            if ((xp & 2) && j >= D) return;
-            load_b_row(order[j], vgpr_ring0 + (j % D), j);
-        };
+        auto issue = [&](int j) { load_b_row(order[j], vgpr_ring0 + (j % D), j); };
         for (int j = 0; j < std::min(D, nc); ++j) issue(j);
         for (int j = 0; j < nc; ++j) {
             // loads issued so far: columns [0, min(nc, j + D)); those after column j may stay in flight
-            if (!(xp & 2)) e.line("\ts_waitcnt vmcnt(%d)", std::min(nc, j + D) - 1 - j);
-            else if (j == 0) e.line("\ts_waitcnt vmcnt(0)");
+            e.line("\ts_waitcnt vmcnt(%d)", std::min(nc, j + D) - 1 - j);
             fmas(cols[order[j]], vgpr_ring0 + (j % D));
             if (j + D < nc) issue(j + D);
         }
@@ -276,7 +269,7 @@ struct Gen {
         const int quads_per_wave = (quads_per_chunk + W - 1) / W;
         std::vector<int> n_loads(n_chunks + 3, 0);
         auto stage_loads = [&](int c) {
-            if (c >= n_chunks || (xp & 16)) return;
+            if (c >= n_chunks) return;
             int t = 0, n = 0;
             for (int q = w; q < quads_per_chunk; q += W, ++t)
                 for (int j = 0; j < 4; ++j) {
@@ -287,7 +280,6 @@ struct Gen {
         };
         auto stage_write = [&](int c) {
             // fetches return in order: chunk c has arrived once only chunk c+1's are outstanding
-            if (xp & 16) return;
             e.line("\ts_waitcnt vmcnt(%d)", c + 1 < n_chunks ? n_loads[c + 1] : 0);
             int t = 0;
             for (int q = w; q < quads_per_chunk; q += W, ++t) {
@@ -342,7 +334,7 @@ struct Gen {
             for (int i = 0; i < nq; ++i) {
                 // LDS reads return in order: quad i is complete once at most
                 // (issued - 1 - last_seq[i]) later reads are outstanding
-                if (!(xp & 8)) e.line("\ts_waitcnt lgkmcnt(%d)", std::min(kMaxLgkm, issued - 1 - last_seq[i]));
+                e.line("\ts_waitcnt lgkmcnt(%d)", std::min(kMaxLgkm, issued - 1 - last_seq[i]));
                 for (int j = 0; j < 4; ++j)
                     if (quads[i].need[j]) fmas(quads[i].terms[j], vgpr_ring0 + 4 * (i % D) + j);
                 if (i + D < nq) issue_reads(i + D);
@@ -351,7 +343,7 @@ struct Gen {
                 stage_write(c + 1);
                 e.line("\ts_waitcnt lgkmcnt(0)");
                 stage_loads(c + 3);
-                if (!(xp & 32)) e.line("\ts_barrier");
+                e.line("\ts_barrier");
             }
         }
         stores(rows);
@@ -408,7 +400,6 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     }
 
     Gen gen(h, sp);
-    gen.xp = getenv("SPARSERT_SPEC_XP") ? atoi(getenv("SPARSERT_SPEC_XP")) : 0;
     Emitter &e = gen.e;
     const int64_t b_bytes = (int64_t)h.K * N * 4, c_bytes = (int64_t)M * N * 4;
     int max_rows = 0;
