@@ -48,7 +48,7 @@ typedef enum sparsert_kernel {
     SPARSERT_KERNEL_AUTO = 0,
     SPARSERT_KERNEL_ROWS = 1,  /* one wave per row, B read straight from L2/HBM */
     SPARSERT_KERNEL_SPEC = 2   /* per-matrix generated gfx950 code with the nonzeros of A as
-                                  instruction constants (Section 3.5); fp32 SpMM only */
+                                  instruction constants (Section 3.5); fp32 only */
 } sparsert_kernel;
 
 /* Variants of the generated kernel (options.spec_mode). */

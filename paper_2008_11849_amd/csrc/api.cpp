@@ -74,7 +74,9 @@ int sparsert_spmm(const sparsert_plan *plan, const void *B_dev, void *C_dev, voi
 int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, void *stream) {
     if (int rc = check_exec(plan, X_dev, Y_dev, true)) return rc;
     std::string err;
-    int rc = sparsert::launch_rows(plan->host, plan->dev, X_dev, Y_dev, stream, err);
+    int rc = plan->host.kernel == SPARSERT_KERNEL_SPEC
+                 ? sparsert::launch_spec(plan->host, plan->dev, X_dev, Y_dev, stream, err)
+                 : sparsert::launch_rows(plan->host, plan->dev, X_dev, Y_dev, stream, err);
     return rc == SPARSERT_OK ? rc : fail(rc, err);
 }
 

@@ -180,7 +180,9 @@ constexpr int kRsrcB = 8, kRsrcC = 12;         // buffer descriptors (4 SGPRs ea
 constexpr int kSgprTile = 16, kSgprBlock = 17, kSgprPc = 18, kSgprTmp = 20, kSgprTmp2 = 21;
 constexpr int kSgprOwns = 22;                  // s[22:23] lanes that own a column
 constexpr int kSgprOffRing = 24, kOffRing = 8; // s[24:31] row-offset literals in flight
-constexpr int kNextFreeSgpr = 32;
+constexpr int kSgprTap0 = 32;                  // conv: s[32:49] = lane masks of the 9 filter taps
+constexpr int kSgprFull = 50;                  // conv: s[50:51] = all lanes
+constexpr int kNextFreeSgpr = 52;
 constexpr int kVgprOff = 0;                    // byte offset of the lane's column inside a row
 constexpr int kVgprLds = 1;                    // LDS byte address of the lane's 16-byte slot
 constexpr int kVgprT1 = 2, kVgprT2 = 3, kVgprAcc0 = 4;
@@ -228,24 +230,53 @@ struct Gen {
         std::map<int32_t, std::vector<Term>> cols;
         for (size_t i = 0; i < rows.size(); ++i) {
             const int32_t slot = rows[i];
-            for (int32_t p = h.p_row_ptr[slot]; p < h.p_row_ptr[slot + 1]; ++p)
-                cols[h.p_col_idx[p]].push_back({(int)i, h.stream[2 * (size_t)p + 1]});
+            for (int32_t p = h.p_row_ptr[slot]; p < h.p_row_ptr[slot + 1]; ++p) {
+                uint32_t bits;  // fp32 plans only: the value as stored (the conv stream is reordered, p_vals is not)
+                std::memcpy(&bits, &h.p_vals[(size_t)p * 4], 4);
+                cols[h.p_col_idx[p]].push_back({(int)i, bits});
+            }
         }
         return cols;
     }
 
-    // DIRECT: b values come straight from global memory, D columns in flight.
+    // Convolution (Section 3.6): operand row k = c*9 + tap is the input plane c displaced by the
+    // tap; relative to the descriptor base X - (W+1) elements that is c*H*W + r*W + s elements.
+    void load_x_row(int k, int vdst, int ring_pos) {
+        const int c = k / 9, tap = k % 9, r = tap / 3, t = tap % 3;
+        const int sreg = kSgprOffRing + (ring_pos % kOffRing);
+        e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)(((int64_t)c * h.H * h.W + r * h.W + t) * 4));
+        e.line("\tbuffer_load_dword v%d, v%d, s[%d:%d], s%d offen", vdst, kVgprOff, kRsrcB, kRsrcB + 3, sreg);
+    }
+    int cur_mask = -1;  // conv: tap whose lane mask is in exec; -1 = all lanes
+    void want_mask(int tap) {
+        if (tap == cur_mask) return;
+        if (tap < 0) e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprFull, kSgprFull + 1);
+        else e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprTap0 + 2 * tap, kSgprTap0 + 2 * tap + 1);
+        cur_mask = tap;
+    }
+
+    // DIRECT: b values come straight from global memory, D columns in flight.  For a
+    // convolution the columns are walked tap by tap and every load and multiply-add of a tap
+    // runs under that tap's lane mask: lanes whose tap falls into the padding neither read
+    // nor accumulate, which is the zero contribution of the padding.
     int block_direct(const std::vector<int32_t> &rows) {
         auto cols = columns_of(rows);
         std::vector<int32_t> order;
         for (auto &kv : cols) order.push_back(kv.first);
+        if (h.conv)
+            std::stable_sort(order.begin(), order.end(), [](int32_t a, int32_t b) { return a % 9 < b % 9; });
         const int nc = (int)order.size();
+        cur_mask = -1;
         zero_accs(rows.size());
-        auto issue = [&](int j) { load_b_row(order[j], vgpr_ring0 + (j % D), j); };
+        auto issue = [&](int j) {
+            if (h.conv) { want_mask(order[j] % 9); load_x_row(order[j], vgpr_ring0 + (j % D), j); }
+            else load_b_row(order[j], vgpr_ring0 + (j % D), j);
+        };
         for (int j = 0; j < std::min(D, nc); ++j) issue(j);
         for (int j = 0; j < nc; ++j) {
             // loads issued so far: columns [0, min(nc, j + D)); those after column j may stay in flight
             e.line("\ts_waitcnt vmcnt(%d)", std::min(nc, j + D) - 1 - j);
+            if (h.conv) want_mask(order[j] % 9);
             fmas(cols[order[j]], vgpr_ring0 + (j % D));
             if (j + D < nc) issue(j + D);
         }
@@ -356,7 +387,10 @@ struct Gen {
 
 int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) {
     SpecPlan &sp = h.spec;
-    if (h.conv) { err = "the specialised executor does not cover convolution plans yet"; return SPARSERT_EUNSUPPORTED; }
+    if (h.conv && opt.spec_mode == SPARSERT_SPEC_LDS) {
+        err = "convolution plans use the DIRECT variant of the generated kernel";
+        return SPARSERT_EUNSUPPORTED;
+    }
     if (h.dtype != SPARSERT_F32) { err = "the specialised executor is fp32 only"; return SPARSERT_EUNSUPPORTED; }
     const int32_t M = h.M, N = h.N;
     sp.mode = opt.spec_mode ? opt.spec_mode : SPARSERT_SPEC_DIRECT;
@@ -401,7 +435,18 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
 
     Gen gen(h, sp);
     Emitter &e = gen.e;
-    const int64_t b_bytes = (int64_t)h.K * N * 4, c_bytes = (int64_t)M * N * 4;
+    const int64_t b_bytes = h.conv ? ((int64_t)h.Cin * N + 2 * (h.W + 1)) * 4 : (int64_t)h.K * N * 4;
+    const int64_t c_bytes = (int64_t)M * N * 4;
+    // conv: pixel -> (oh, ow) by multiplication with ceil(2^32 / W); verified here for every pixel
+    uint32_t magic = 0;
+    if (h.conv && h.W > 1) {
+        magic = (uint32_t)(((1ull << 32) + h.W - 1) / h.W);
+        for (int64_t p = 0; p < N; ++p)
+            if ((int64_t)(((uint64_t)p * magic) >> 32) != p / h.W) {
+                err = "image too large for the generated kernel's pixel index arithmetic";
+                return SPARSERT_EUNSUPPORTED;
+            }
+    }
     int max_rows = 0;
     for (auto &m : members) max_rows = std::max<int>(max_rows, (int)m.size());
     const int D = sp.depth;
@@ -464,7 +509,45 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     // lanes without a column redo the tile's first column: loads stay in bounds, nothing is stored
     e.line("\tv_cndmask_b32_e64 v%d, v%d, v%d, s[%d:%d]", kVgprT1, kVgprT2, kVgprT1, kSgprOwns, kSgprOwns + 1);
     e.line("\tv_lshlrev_b32_e32 v%d, 2, v%d", kVgprOff, kVgprT1);  // byte offset of the column inside a row
+    if (h.conv) {
+        // oh = pixel / W, ow = pixel % W; then one lane mask per filter tap (r, s):
+        // 0 <= oh + r - 1 < H and 0 <= ow + s - 1 < W  (Section 3.6: the padding test, made once)
+        const int voh = kVgprAcc0, vow = kVgprAcc0 + 1;   // accumulators are not live yet
+        const int sa0 = kSgprOffRing, sa2 = kSgprOffRing + 2, sb0 = kSgprOffRing + 4, sb2 = kSgprOffRing + 6;
+        if (h.W > 1) {
+            e.line("\ts_mov_b32 s%d, 0x%x", kSgprTmp, magic);
+            e.line("\tv_mul_hi_u32 v%d, v%d, s%d", voh, kVgprT1, kSgprTmp);
+            e.line("\ts_mov_b32 s%d, %d", kSgprTmp, h.W);
+            e.line("\tv_mul_lo_u32 v%d, v%d, s%d", vow, voh, kSgprTmp);
+            e.line("\tv_sub_u32_e32 v%d, v%d, v%d", vow, kVgprT1, vow);
+        } else {  // one pixel per image row
+            e.line("\tv_mov_b32_e32 v%d, v%d", voh, kVgprT1);
+            e.line("\tv_mov_b32_e32 v%d, 0", vow);
+        }
+        e.line("\ts_nop 1");
+        e.line("\ts_mov_b32 s%d, %d", kSgprTmp, h.H - 2);
+        e.line("\ts_mov_b32 s%d, %d", kSgprTmp2, h.W - 2);
+        e.line("\tv_cmp_le_i32_e64 s[%d:%d], 1, v%d", sa0, sa0 + 1, voh);             // r = 0 needs oh >= 1
+        e.line("\tv_cmp_ge_i32_e64 s[%d:%d], s%d, v%d", sa2, sa2 + 1, kSgprTmp, voh);  // r = 2 needs oh <= H-2
+        e.line("\tv_cmp_le_i32_e64 s[%d:%d], 1, v%d", sb0, sb0 + 1, vow);             // s = 0 needs ow >= 1
+        e.line("\tv_cmp_ge_i32_e64 s[%d:%d], s%d, v%d", sb2, sb2 + 1, kSgprTmp2, vow); // s = 2 needs ow <= W-2
+        e.line("\ts_nop 4");
+        e.line("\ts_mov_b64 s[%d:%d], exec", kSgprFull, kSgprFull + 1);
+        for (int r = 0; r < 3; ++r)
+            for (int t = 0; t < 3; ++t) {
+                const int m = kSgprTap0 + 2 * (r * 3 + t);
+                e.line("\ts_mov_b64 s[%d:%d], exec", m, m + 1);
+                if (r != 1) e.line("\ts_and_b64 s[%d:%d], s[%d:%d], s[%d:%d]", m, m + 1, m, m + 1, r == 0 ? sa0 : sa2, (r == 0 ? sa0 : sa2) + 1);
+                if (t != 1) e.line("\ts_and_b64 s[%d:%d], s[%d:%d], s[%d:%d]", m, m + 1, m, m + 1, t == 0 ? sb0 : sb2, (t == 0 ? sb0 : sb2) + 1);
+            }
+    }
     e.line("\ts_waitcnt lgkmcnt(0)");
+    if (h.conv) {
+        // operand descriptor starts W+1 elements before X so that every tap displacement is
+        // non-negative; lanes that would read before X are always masked off for that tap
+        e.line("\ts_sub_u32 s%d, s%d, %d", kSgprB, kSgprB, (h.W + 1) * 4);
+        e.line("\ts_subb_u32 s%d, s%d, 0", kSgprB + 1, kSgprB + 1);
+    }
     e.line("\ts_mov_b32 s%d, s%d", kRsrcB, kSgprB);
     e.line("\ts_and_b32 s%d, s%d, 0xffff", kRsrcB + 1, kSgprB + 1);
     e.line("\ts_mov_b32 s%d, 0x%llx", kRsrcB + 2, (unsigned long long)b_bytes);

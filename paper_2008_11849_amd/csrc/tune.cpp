@@ -85,7 +85,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
             cands.push_back(o);
         }
     }
-    if (!conv && !f16 && nnz <= (4 << 20)) {
+    if (!f16 && nnz <= (4 << 20)) {
         const int64_t tiles = (N + 63) / 64;
         for (int r : {1, 2, 4, 8, 16, 24, 48}) {
             if (r > M) continue;
@@ -99,7 +99,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
                 cands.push_back(o);
             }
         }
-        if (K >= 256 && (int64_t)M * tiles >= 1024) {
+        if (!conv && K >= 256 && (int64_t)M * tiles >= 1024) {
             for (int r : {12, 24, 48})
                 for (int w : {4, 8}) {
                     if (((int64_t)M + r - 1) / r < w) continue;

@@ -225,8 +225,10 @@ def test_generated_kernel_option_errors():
     ccsr, _ = synth.conv_weights_csr(4, 2, 0.5, 1)
     with pytest.raises(sp.SparseRTError) as e:
         sp.inspect(ccsr.row_ptr, ccsr.col_idx, ccsr.vals, 4, 18, 16, conv=(2, 4, 4), host_only=True,
-                   kernel=sp.KERNEL_SPEC)
+                   kernel=sp.KERNEL_SPEC, spec_mode=sp.SPEC_LDS)
     assert e.value.status == sp.EUNSUPPORTED
+    sp.inspect(ccsr.row_ptr, ccsr.col_idx, ccsr.vals, 4, 18, 16, conv=(2, 4, 4), host_only=True,
+               kernel=sp.KERNEL_SPEC).destroy()
     # tune validates before it touches the GPU
     out, rep = ctypes.c_void_p(1), sp.TuneReport()
     rc = sp.raw.sparsert_tune(None, None, None, 1, 1, 1, None, 16, 16, None, ctypes.byref(out), ctypes.byref(rep))

@@ -94,6 +94,43 @@ def test_spec_sweep_subset(M, K, N, s, kind, mode):
     check(got, Cref, S, np.float32)
 
 
+CONV_SHAPES = [(3, 5, 1, 1), (4, 6, 2, 3), (2, 3, 1, 9), (2, 3, 9, 1), (8, 8, 7, 7), (16, 24, 14, 14),
+               (6, 10, 9, 13), (64, 64, 56, 56), (128, 128, 28, 28), (256, 256, 14, 14), (512, 512, 7, 7)]
+
+
+@pytest.mark.parametrize("Cin,Cout,H,W", CONV_SHAPES)
+def test_spec_conv_shapes(Cin, Cout, H, W):
+    from gpu_util import run_conv
+    csr, Wd = synth.conv_weights_csr(Cout, Cin, 0.9 if Cin > 4 else 0.5, Cin + H)
+    X = synth.normal_dense(Cin, H * W, Cout + W).reshape(1, Cin, H, W)
+    Yref, S = ref.conv3x3(Wd, X)
+    for rows in (0, 1, 5):
+        got, info = run_conv(csr, X, Cout, kernel=sp.KERNEL_SPEC, spec_rows=rows)
+        assert info["kernel"] == sp.KERNEL_SPEC and info["conv"] == 1
+        check(got, Yref, S, np.float32)
+
+
+def test_spec_conv_integer_taps_bit_exact():
+    from gpu_util import run_conv
+    Cin, Cout, H, W = 7, 9, 11, 6
+    rng = np.random.default_rng(4)
+    Wd = (rng.integers(-3, 4, size=(Cout, Cin, 3, 3)) * (rng.random((Cout, Cin, 3, 3)) < 0.3)).astype(np.float32)
+    X = rng.integers(-5, 6, size=(1, Cin, H, W)).astype(np.float32)
+    csr = synth.csr_from_mask(Wd.reshape(Cout, -1), Wd.reshape(Cout, -1) != 0)
+    Yref, _ = ref.conv3x3(Wd, X)
+    for rows, tiles in ((0, 0), (1, 1), (3, 2), (9, 16)):
+        got, _ = run_conv(csr, X, Cout, kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_tiles=tiles)
+        assert np.array_equal(got.astype(np.float64), Yref)
+    for t in range(9):  # one tap at a time: a zero-filled shift of the input, bit for bit
+        W1 = np.zeros((1, 1, 3, 3), dtype=np.float32)
+        W1[0, 0, t // 3, t % 3] = 1.0
+        X1 = synth.normal_dense(1, H * W, t).reshape(1, 1, H, W)
+        got, _ = run_conv(synth.csr_from_mask(W1.reshape(1, 9), W1.reshape(1, 9) != 0), X1, 1,
+                          kernel=sp.KERNEL_SPEC)
+        Yr, _ = ref.conv3x3(W1, X1)
+        assert np.array_equal(got.astype(np.float64), Yr)
+
+
 def test_spec_rejects_what_it_does_not_cover():
     csr = synth.uniform_csr(16, 18, 0.5, 1, dtype=np.float16)
     with pytest.raises(sp.SparseRTError) as e:
