@@ -51,7 +51,7 @@ def parse_args():
 class Layer:
     """One sparse layer resident on the GPU: plan, input, output and its dense twin."""
 
-    PLAN_KEYS = ("kernel", "vec", "split_threshold", "spec_mode", "spec_rows", "spec_tiles")
+    PLAN_KEYS = ("kernel", "vec", "split_threshold", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit")
 
     def __init__(self, case, torch, sp, kernel="tune", fixed=None):
         import numpy as np
@@ -229,7 +229,7 @@ def main():
                           "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
                           "dense_us": ms_dense * 1e3, "speedup_vs_dense": ms_dense / ms,
                           "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
-                                                          "spec_tiles", "spec_code_bytes")},
+                                                          "spec_tiles", "spec_ksplit", "spec_code_bytes")},
                           "tuned_candidates": len(L.tuned) if L.tuned else 0})
     kernel_ms = sum(p["us"] for p in per_layer) / 1e3 / len(layers)       # average launch
     alg_bytes = sum(L.algorithmic_bytes for L in layers) / len(layers)    # average launch
@@ -275,7 +275,7 @@ def main():
             side.append({"layer": n, "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
                          "dense_us": msd * 1e3, "speedup_vs_dense": msd / ms,
                          "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
-                                                         "spec_tiles")}})
+                                                         "spec_tiles", "spec_ksplit")}})
             L.plan.destroy()
         out["other_configs"] = side
 

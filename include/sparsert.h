@@ -79,7 +79,11 @@ typedef struct sparsert_options {
                                 DIRECT mode, adjacent code blocks in LDS mode): 1,2,4,8,16;
                                 0 = automatic */
     int32_t spec_mode;       /* sparsert_spec_mode; 0 = automatic */
-    int32_t reserved[2];     /* must be zero */
+    int32_t spec_ksplit;     /* SPARSERT_KERNEL_SPEC, DIRECT: 2, 4 or 8 waves of a workgroup share one
+                                code block's rows and column tile and split its columns (equal
+                                nonzero shares, partial sums meet in LDS); 0/1 = no split.  Sets
+                                the workgroup width, spec_tiles is then ignored */
+    int32_t reserved[1];     /* must be zero */
 } sparsert_options;
 
 /*
@@ -160,7 +164,7 @@ int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, 
  */
 #define SPARSERT_TUNE_MAX 64
 typedef struct sparsert_tune_entry {
-    int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles;
+    int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles, spec_ksplit;
     float microseconds; /* per launch; negative if the candidate failed */
 } sparsert_tune_entry;
 typedef struct sparsert_tune_report {
@@ -218,6 +222,7 @@ enum {
     SPARSERT_INFO_SPEC_TILES,     /* SPEC plans: waves per workgroup */
     SPARSERT_INFO_SPEC_MODE,      /* SPEC plans: sparsert_spec_mode in use */
     SPARSERT_INFO_SPEC_LDS_BYTES, /* SPEC plans: LDS per workgroup */
+    SPARSERT_INFO_SPEC_KSPLIT,    /* SPEC plans: K parts per workgroup (1 = none) */
     SPARSERT_INFO_COUNT = 32      /* remaining entries are zero */
 };
 

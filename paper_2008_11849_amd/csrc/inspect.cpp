@@ -38,7 +38,7 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (M <= 0 || K <= 0 || N <= 0) { err = "M, K and N must be positive"; return SPARSERT_EINVAL; }
     if (opt.dtype != SPARSERT_F32 && opt.dtype != SPARSERT_F16) { err = "unknown dtype"; return SPARSERT_EINVAL; }
     if (opt.kernel < SPARSERT_KERNEL_AUTO || opt.kernel > SPARSERT_KERNEL_SPEC) { err = "unknown kernel family"; return SPARSERT_EINVAL; }
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 1; ++i)
         if (opt.reserved[i] != 0) { err = "reserved option fields must be zero"; return SPARSERT_EINVAL; }
     if (row_ptr[0] != 0) { err = "row_ptr[0] must be 0"; return SPARSERT_EINVAL; }
     for (int32_t m = 0; m < M; ++m)

@@ -321,7 +321,8 @@ int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
     if (tpw < 1 || tpw > 16 || (tpw & (tpw - 1))) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     const bool lds = sp.mode == SPARSERT_SPEC_LDS;
     if (lds && (sp.n_blocks % tpw || sp.lds_bytes < 1 || sp.lds_bytes > 65536)) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
-    const unsigned gx = lds ? (unsigned)sp.n_tiles : (unsigned)((sp.n_tiles + tpw - 1) / tpw);
+    if (sp.ksplit > 1 && (lds || sp.ksplit != tpw || sp.n_blocks != sp.n_groups * sp.ksplit)) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
+    const unsigned gx = (lds || sp.ksplit > 1) ? (unsigned)sp.n_tiles : (unsigned)((sp.n_tiles + tpw - 1) / tpw);
     const unsigned gy = lds ? (unsigned)(sp.n_blocks / tpw) : (unsigned)sp.n_groups;
     HIP_TRY(hipModuleLaunchKernel(static_cast<hipFunction_t>(d.spec_function), gx, gy, 1, tpw * kWave, 1, 1,
                                   0, static_cast<hipStream_t>(stream), nullptr, config));

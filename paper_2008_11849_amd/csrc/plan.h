@@ -21,6 +21,7 @@ struct SpecPlan {
     int32_t mode = 0;           // sparsert_spec_mode
     int32_t n_blocks = 0;       // code blocks (n_groups, padded to a multiple of the waves in LDS mode)
     int32_t lds_bytes = 0;
+    int32_t ksplit = 1;         // DIRECT: waves of a workgroup that split the K range of one block
     int64_t asm_bytes = 0;
     std::vector<int32_t> group_of_slot;   // [M]
     std::vector<int32_t> group_columns;   // [n_groups] B rows each group loads per column tile

@@ -259,12 +259,28 @@ struct Gen {
     // convolution the columns are walked tap by tap and every load and multiply-add of a tap
     // runs under that tap's lane mask: lanes whose tap falls into the padding neither read
     // nor accumulate, which is the zero contribution of the padding.
-    int block_direct(const std::vector<int32_t> &rows) {
+    // With `parts` > 1 the waves of a workgroup share the block's rows and tile and split its
+    // columns (Section 3.4, thread-group balance: contiguous ranges with equal nonzero counts,
+    // the last one takes the remainder); partial accumulators meet in LDS (Section 3.3).
+    int block_direct(const std::vector<int32_t> &rows, int part = 0, int parts = 1, int max_rows = 0) {
         auto cols = columns_of(rows);
         std::vector<int32_t> order;
         for (auto &kv : cols) order.push_back(kv.first);
         if (h.conv)
             std::stable_sort(order.begin(), order.end(), [](int32_t a, int32_t b) { return a % 9 < b % 9; });
+        if (parts > 1) {
+            int64_t total = 0;
+            for (int32_t k : order) total += (int64_t)cols[k].size();
+            const int64_t share = (total + parts - 1) / parts;
+            std::vector<int32_t> mine;
+            int64_t seen = 0;
+            for (int32_t k : order) {   // a column belongs to the part its first nonzero falls into
+                const int p = share ? (int)std::min<int64_t>(parts - 1, seen / share) : 0;
+                if (p == part) mine.push_back(k);
+                seen += (int64_t)cols[k].size();
+            }
+            order.swap(mine);
+        }
         const int nc = (int)order.size();
         cur_mask = -1;
         zero_accs(rows.size());
@@ -279,6 +295,36 @@ struct Gen {
             if (h.conv) want_mask(order[j] % 9);
             fmas(cols[order[j]], vgpr_ring0 + (j % D));
             if (j + D < nc) issue(j + D);
+        }
+        if (parts > 1) {
+            if (h.conv) want_mask(-1);
+            // waves 1.. leave their partial rows in LDS; wave 0 adds them in wave order and stores
+            if (part > 0) {
+                for (size_t i = 0; i < rows.size(); ++i)
+                    e.line("\tds_write_b32 v%d, v%d offset:%d", kVgprLds, kVgprAcc0 + (int)i,
+                           ((part - 1) * max_rows + (int)i) * 256);
+                e.line("\ts_waitcnt lgkmcnt(0)");
+                e.line("\ts_barrier");
+                e.line("\ts_endpgm");
+                return nc;
+            }
+            e.line("\ts_barrier");
+            const int tmp0 = vgpr_ring0;  // the operand ring is free now
+            const int batch = std::min(D, 12);
+            std::vector<std::pair<int, int>> items;  // (row, part) in the order they are added
+            for (size_t i = 0; i < rows.size(); ++i)
+                for (int q = 1; q < parts; ++q) items.push_back({(int)i, q});
+            for (size_t b0 = 0; b0 < items.size(); b0 += batch) {
+                const size_t b1 = std::min(items.size(), b0 + batch);
+                for (size_t t = b0; t < b1; ++t)
+                    e.line("\tds_read_b32 v%d, v%d offset:%d", tmp0 + (int)(t - b0), kVgprLds,
+                           ((items[t].second - 1) * max_rows + items[t].first) * 256);
+                for (size_t t = b0; t < b1; ++t) {
+                    e.line("\ts_waitcnt lgkmcnt(%d)", (int)(b1 - 1 - t));
+                    e.line("\tv_add_f32_e32 v%d, v%d, v%d", kVgprAcc0 + items[t].first, kVgprAcc0 + items[t].first,
+                           tmp0 + (int)(t - b0));
+                }
+            }
         }
         stores(rows);
         e.line("\ts_endpgm");
@@ -399,6 +445,10 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     sp.n_tiles = (N + kWave - 1) / kWave;
     sp.lanes_per_tile = (N + sp.n_tiles - 1) / sp.n_tiles;
     sp.tiles_per_wg = opt.spec_tiles ? opt.spec_tiles : 4;
+    sp.ksplit = opt.spec_ksplit ? opt.spec_ksplit : 1;
+    if (sp.ksplit != 1 && sp.ksplit != 2 && sp.ksplit != 4 && sp.ksplit != 8) { err = "spec_ksplit must be 0,1,2,4,8"; return SPARSERT_EINVAL; }
+    if (sp.ksplit > 1 && lds) { err = "spec_ksplit applies to the DIRECT variant"; return SPARSERT_EINVAL; }
+    if (sp.ksplit > 1) sp.tiles_per_wg = sp.ksplit;   // the waves of a workgroup are the K parts
     const int W = sp.tiles_per_wg;
     int wshift = 0;
     while ((1 << wshift) < W) ++wshift;
@@ -422,7 +472,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     const int G = sp.n_groups;
     // LDS mode: a workgroup runs W consecutive blocks and every one of them takes part in the
     // staging and the barriers, so the block list is padded with empty blocks.
-    const int n_blocks = lds ? (G + W - 1) / W * W : G;
+    const int KS = sp.ksplit;
+    const int n_blocks = lds ? (G + W - 1) / W * W : G * KS;
     sp.n_blocks = n_blocks;
     sp.group_of_slot.resize(M);
     std::vector<std::vector<int32_t>> members(n_blocks);
@@ -462,6 +513,11 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     } else {
         gen.vgpr_ring0 = kVgprAcc0 + max_rows;
         gen.n_vgpr = gen.vgpr_ring0 + D;
+        if (KS > 1) {
+            gen.lds_bytes = (KS - 1) * max_rows * 256;
+            if (gen.lds_bytes > 65536) { err = "spec_rows x spec_ksplit needs more than 64 KiB of LDS"; return SPARSERT_EINVAL; }
+            if (gen.lds_bytes == 0) gen.lds_bytes = 256;
+        }
     }
     const int n_vgpr = gen.n_vgpr;
     if (n_vgpr > 256) { err = "spec_rows too large for the register file"; return SPARSERT_EINVAL; }
@@ -482,7 +538,13 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\ts_nop 1");
     e.line("\tv_readfirstlane_b32 s%d, v%d", kSgprTile, kVgprT1);  // wave index inside the workgroup
     e.line("\ts_nop 4");
-    if (!lds) {
+    if (!lds && KS > 1) {
+        // grid (tiles, groups): the waves of a workgroup run the K parts of one group on one tile
+        e.line("\ts_lshl_b32 s%d, s3, %d", kSgprTmp, wshift);
+        e.line("\ts_add_u32 s%d, s%d, s%d", kSgprBlock, kSgprTmp, kSgprTile);
+        e.line("\ts_mov_b32 s%d, s2", kSgprTile);
+        e.line("\tv_lshlrev_b32_e32 v%d, 2, v%d", kVgprLds, kVgprOff);  // lane * 4
+    } else if (!lds) {
         // grid (ceil(tiles/W), groups): the waves of a workgroup run one block on adjacent tiles
         e.line("\ts_lshl_b32 s%d, s2, %d", kSgprTmp, wshift);
         e.line("\ts_add_u32 s%d, s%d, s%d", kSgprTile, kSgprTmp, kSgprTile);
@@ -577,7 +639,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     for (int g = 0; g < n_blocks; ++g) {
         e.line("\t.p2align 2");
         e.line(".Lg%d:", g);
-        sp.group_columns[g] = lds ? gen.block_lds(members[g], g % W, W) : gen.block_direct(members[g]);
+        sp.group_columns[g] = lds ? gen.block_lds(members[g], g % W, W)
+                                  : gen.block_direct(members[g / KS], g % KS, KS, max_rows);
     }
     e.line(".Lfunc_end:");
     e.line("\t.size\tsparsert_spec, .Lfunc_end-sparsert_spec");

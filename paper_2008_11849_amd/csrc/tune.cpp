@@ -99,6 +99,16 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
                 cands.push_back(o);
             }
         }
+        if (K >= 512) {   // long reduction axis: split it over the waves of a workgroup
+            const int rk[][2] = {{16, 8}, {24, 8}, {32, 8}, {32, 4}, {48, 4}, {64, 4}, {64, 2}, {96, 2}};
+            for (auto &c : rk) {
+                if (c[0] > M) continue;
+                sparsert_options o = b;
+                o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
+                o.spec_rows = c[0]; o.spec_ksplit = c[1];
+                cands.push_back(o);
+            }
+        }
         if (!conv && K >= 256 && (int64_t)M * tiles >= 1024) {
             for (int r : {12, 24, 48})
                 for (int w : {4, 8}) {
@@ -118,6 +128,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
         const sparsert::HostPlan &h = p->host;
         t.kernel = h.kernel; t.vec = h.vec; t.split_threshold = h.split_threshold;
         t.spec_mode = h.spec.mode; t.spec_rows = h.spec.rows_per_group; t.spec_tiles = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.tiles_per_wg : 0;
+        t.spec_ksplit = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.ksplit : 0;
         t.microseconds = us;
     };
     log(best, best_us);

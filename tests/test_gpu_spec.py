@@ -94,6 +94,30 @@ def test_spec_sweep_subset(M, K, N, s, kind, mode):
     check(got, Cref, S, np.float32)
 
 
+@pytest.mark.parametrize("ks", [2, 4, 8])
+@pytest.mark.parametrize("N", [1, 65, 196, 300])
+def test_spec_ksplit_small_integers_bit_exact(N, ks):
+    csr = synth.small_int_csr(77, 130, 0.85, N)
+    B = synth.small_int_dense(130, N, N + 1)
+    Cref, _ = _oracle(csr, B)
+    for rows in (0, 1, 7, 36):   # (ks-1) * rows * 256 B of LDS must stay within 64 KiB
+        got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_ksplit=ks)
+        assert info["spec_ksplit"] == ks and info["spec_tiles"] == ks
+        assert np.array_equal(got.astype(np.float64), Cref), (N, rows, ks)
+
+
+def test_spec_ksplit_configs_and_skew():
+    for name in ("c2", "c3t"):
+        case = synth.config(name)
+        got, info = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_rows=48, spec_ksplit=4)
+        Cref, S = _oracle(case.csr, case.B)
+        check(got, Cref, S, np.float32, gate_relative=True)
+    case = synth.sweep_case(512, 1024, 784, 0.95, "skewed", np.float32)  # empty rows, empty K parts
+    got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_rows=16, spec_ksplit=8)
+    Cref, S = _oracle(case.csr, case.B)
+    check(got, Cref, S, np.float32)
+
+
 CONV_SHAPES = [(3, 5, 1, 1), (4, 6, 2, 3), (2, 3, 1, 9), (2, 3, 9, 1), (8, 8, 7, 7), (16, 24, 14, 14),
                (6, 10, 9, 13), (64, 64, 56, 56), (128, 128, 28, 28), (256, 256, 14, 14), (512, 512, 7, 7)]
 
@@ -120,6 +144,9 @@ def test_spec_conv_integer_taps_bit_exact():
     Yref, _ = ref.conv3x3(Wd, X)
     for rows, tiles in ((0, 0), (1, 1), (3, 2), (9, 16)):
         got, _ = run_conv(csr, X, Cout, kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_tiles=tiles)
+        assert np.array_equal(got.astype(np.float64), Yref)
+    for ks in (2, 4):
+        got, _ = run_conv(csr, X, Cout, kernel=sp.KERNEL_SPEC, spec_rows=3, spec_ksplit=ks)
         assert np.array_equal(got.astype(np.float64), Yref)
     for t in range(9):  # one tap at a time: a zero-filled shift of the input, bit for bit
         W1 = np.zeros((1, 1, 3, 3), dtype=np.float32)
