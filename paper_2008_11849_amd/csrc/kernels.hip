@@ -236,6 +236,13 @@ int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err) {
     if (int rc = to_device(h.segments.data(), h.segments.size(), &d.segments, err)) return rc;
     if (int rc = to_device(h.conv_seg.data(), h.conv_seg.size(), &d.conv_seg, err)) return rc;
     if (h.kernel == SPARSERT_KERNEL_SPEC) {
+        int dev = 0, lds_max = 0;
+        HIP_TRY(hipGetDevice(&dev));
+        HIP_TRY(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+        if (h.spec.lds_bytes > lds_max) {
+            err = "the generated kernel needs more LDS per workgroup than this device has";
+            return SPARSERT_EUNSUPPORTED;
+        }
         hipModule_t mod = nullptr;
         hipFunction_t fn = nullptr;
         hipError_t e1 = hipModuleLoadData(&mod, h.spec.code.data());
@@ -320,7 +327,7 @@ int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
     const int tpw = sp.tiles_per_wg;
     if (tpw < 1 || tpw > 16 || (tpw & (tpw - 1))) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     const bool lds = sp.mode == SPARSERT_SPEC_LDS;
-    if (lds && (sp.n_blocks % tpw || sp.lds_bytes < 1 || sp.lds_bytes > 65536)) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
+    if (lds && (sp.n_blocks % tpw || sp.lds_bytes < 1 || sp.lds_bytes > 160 * 1024)) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     if (sp.ksplit > 1 && (lds || sp.ksplit != tpw || sp.n_blocks != sp.n_groups * sp.ksplit)) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     const unsigned gx = (lds || sp.ksplit > 1) ? (unsigned)sp.n_tiles : (unsigned)((sp.n_tiles + tpw - 1) / tpw);
     const unsigned gy = lds ? (unsigned)(sp.n_blocks / tpw) : (unsigned)sp.n_groups;

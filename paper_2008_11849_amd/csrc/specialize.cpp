@@ -188,6 +188,7 @@ constexpr int kVgprLds = 1;                    // LDS byte address of the lane's
 constexpr int kVgprT1 = 2, kVgprT2 = 3, kVgprAcc0 = 4;
 constexpr uint32_t kRsrcWord3 = 0x00020000u;   // raw 32-bit buffer, gfx9 family
 constexpr int kMaxChunkRows = 128;             // B rows per LDS buffer (32 KiB), two buffers
+constexpr int kMaxLdsBytes = 160 * 1024;        // LDS of one gfx950 compute unit, all of it usable by one workgroup
 constexpr int kMaxLgkm = 15;                   // lgkmcnt is a 4-bit counter
 
 struct Term { int acc; uint32_t bits; };
@@ -198,6 +199,7 @@ struct Gen {
     SpecPlan &sp;
     int N, K, D;
     int vgpr_stage0 = 0, vgpr_ring0 = 0, n_vgpr = 0, lds_bytes = 0;
+    int ring_size = 0;               // DIRECT: registers of the operand ring (>= D)
     int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
     Gen(const HostPlan &hp, SpecPlan &s) : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth) {}
 
@@ -214,13 +216,14 @@ struct Gen {
         e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)k * N * 4));
         e.line("\tbuffer_load_dword v%d, v%d, s[%d:%d], s%d offen", vdst, kVgprOff, kRsrcB, kRsrcB + 3, sreg);
     }
-    void stores(const std::vector<int32_t> &rows) {
+    // (slot of the permuted CSR, accumulator register) pairs: one row of C each
+    void stores(const std::vector<std::pair<int32_t, int>> &rows) {
         if (rows.empty()) return;
         e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
         for (size_t i = 0; i < rows.size(); ++i) {
             const int sreg = kSgprOffRing + ((int)i % kOffRing);
-            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i]] * N * 4));
-            e.line("\tbuffer_store_dword v%d, v%d, s[%d:%d], s%d offen", kVgprAcc0 + (int)i, kVgprOff,
+            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i].first] * N * 4));
+            e.line("\tbuffer_store_dword v%d, v%d, s[%d:%d], s%d offen", rows[i].second, kVgprOff,
                    kRsrcC, kRsrcC + 3, sreg);
         }
     }
@@ -262,7 +265,7 @@ struct Gen {
     // With `parts` > 1 the waves of a workgroup share the block's rows and tile and split its
     // columns (Section 3.4, thread-group balance: contiguous ranges with equal nonzero counts,
     // the last one takes the remainder); partial accumulators meet in LDS (Section 3.3).
-    int block_direct(const std::vector<int32_t> &rows, int part = 0, int parts = 1, int max_rows = 0) {
+    int block_direct(const std::vector<int32_t> &rows, int part = 0, int parts = 1) {
         auto cols = columns_of(rows);
         std::vector<int32_t> order;
         for (auto &kv : cols) order.push_back(kv.first);
@@ -290,7 +293,8 @@ struct Gen {
         };
         for (int j = 0; j < std::min(D, nc); ++j) issue(j);
         for (int j = 0; j < nc; ++j) {
-            // loads issued so far: columns [0, min(nc, j + D)); those after column j may stay in flight
+            // loads issued so far: columns [0, min(nc, j + D)); those after column j may stay in
+            // flight.  (Waiting once per batch of columns was measured slower than once per column.)
             e.line("\ts_waitcnt vmcnt(%d)", std::min(nc, j + D) - 1 - j);
             if (h.conv) want_mask(order[j] % 9);
             fmas(cols[order[j]], vgpr_ring0 + (j % D));
@@ -298,35 +302,54 @@ struct Gen {
         }
         if (parts > 1) {
             if (h.conv) want_mask(-1);
-            // waves 1.. leave their partial rows in LDS; wave 0 adds them in wave order and stores
-            if (part > 0) {
-                for (size_t i = 0; i < rows.size(); ++i)
-                    e.line("\tds_write_b32 v%d, v%d offset:%d", kVgprLds, kVgprAcc0 + (int)i,
-                           ((part - 1) * max_rows + (int)i) * 256);
-                e.line("\ts_waitcnt lgkmcnt(0)");
-                e.line("\ts_barrier");
-                e.line("\ts_endpgm");
-                return nc;
-            }
+            // Row i of the block belongs to wave i % parts.  Every wave leaves its partial sums of
+            // the rows it does not own in LDS, and after one barrier adds the other waves'
+            // partials to its own rows in ascending wave order, then stores those rows.
+            const int nr = (int)rows.size();
+            auto slot = [&](int i, int q) {   // byte offset of wave q's partial of row i, q != i % parts
+                const int o = i % parts;
+                return (i * (parts - 1) + (q < o ? q : q - 1)) * 256;
+            };
+            // ds offsets are 16 bits wide: one address register per 64 KiB of the exchange area
+            const int n_base = ((parts - 1) * nr * 256 + 65535) / 65536;
+            const int base0 = vgpr_ring0;          // the operand ring is free now
+            for (int b = 1; b < n_base; ++b)
+                e.line("\tv_add_u32_e32 v%d, 0x%x, v%d", base0 + b, b * 65536, kVgprLds);
+            auto base_of = [&](int off) { return off < 65536 ? kVgprLds : base0 + off / 65536; };
+            for (int i = 0; i < nr; ++i)
+                if (i % parts != part)
+                    e.line("\tds_write_b32 v%d, v%d offset:%d", base_of(slot(i, part)), kVgprAcc0 + i,
+                           slot(i, part) & 65535);
+            e.line("\ts_waitcnt lgkmcnt(0)");
             e.line("\ts_barrier");
-            const int tmp0 = vgpr_ring0;  // the operand ring is free now
-            const int batch = std::min(D, 12);
-            std::vector<std::pair<int, int>> items;  // (row, part) in the order they are added
-            for (size_t i = 0; i < rows.size(); ++i)
-                for (int q = 1; q < parts; ++q) items.push_back({(int)i, q});
+            const int tmp0 = base0 + std::max(n_base, 1);
+            const int batch = std::max(1, std::min(12, ring_size - std::max(n_base, 1)));
+            std::vector<std::pair<int, int>> items;  // (row, source wave) in the order they are added
+            std::vector<std::pair<int32_t, int>> mine;
+            for (int i = part; i < nr; i += parts) {
+                mine.push_back({rows[i], kVgprAcc0 + i});
+                for (int q = 0; q < parts; ++q)
+                    if (q != part) items.push_back({i, q});
+            }
             for (size_t b0 = 0; b0 < items.size(); b0 += batch) {
                 const size_t b1 = std::min(items.size(), b0 + batch);
-                for (size_t t = b0; t < b1; ++t)
-                    e.line("\tds_read_b32 v%d, v%d offset:%d", tmp0 + (int)(t - b0), kVgprLds,
-                           ((items[t].second - 1) * max_rows + items[t].first) * 256);
+                for (size_t t = b0; t < b1; ++t) {
+                    const int off = slot(items[t].first, items[t].second);
+                    e.line("\tds_read_b32 v%d, v%d offset:%d", tmp0 + (int)(t - b0), base_of(off), off & 65535);
+                }
                 for (size_t t = b0; t < b1; ++t) {
                     e.line("\ts_waitcnt lgkmcnt(%d)", (int)(b1 - 1 - t));
                     e.line("\tv_add_f32_e32 v%d, v%d, v%d", kVgprAcc0 + items[t].first, kVgprAcc0 + items[t].first,
                            tmp0 + (int)(t - b0));
                 }
             }
+            stores(mine);
+            e.line("\ts_endpgm");
+            return nc;
         }
-        stores(rows);
+        std::vector<std::pair<int32_t, int>> all;
+        for (size_t i = 0; i < rows.size(); ++i) all.push_back({rows[i], kVgprAcc0 + (int)i});
+        stores(all);
         e.line("\ts_endpgm");
         return nc;
     }
@@ -423,7 +446,9 @@ struct Gen {
                 e.line("\ts_barrier");
             }
         }
-        stores(rows);
+        std::vector<std::pair<int32_t, int>> all;
+        for (size_t i = 0; i < rows.size(); ++i) all.push_back({rows[i], kVgprAcc0 + (int)i});
+        stores(all);
         e.line("\ts_endpgm");
         return total_cols;
     }
@@ -512,10 +537,11 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         gen.lds_bytes = (n_chunks > 1 ? 2 : 1) * kChunkRows * 256;
     } else {
         gen.vgpr_ring0 = kVgprAcc0 + max_rows;
-        gen.n_vgpr = gen.vgpr_ring0 + D;
+        gen.ring_size = KS > 1 ? std::max(D, 8) : D;   // the K-split exchange borrows the ring
+        gen.n_vgpr = gen.vgpr_ring0 + gen.ring_size;
         if (KS > 1) {
             gen.lds_bytes = (KS - 1) * max_rows * 256;
-            if (gen.lds_bytes > 65536) { err = "spec_rows x spec_ksplit needs more than 64 KiB of LDS"; return SPARSERT_EINVAL; }
+            if (gen.lds_bytes > kMaxLdsBytes) { err = "spec_rows x spec_ksplit needs more than 160 KiB of LDS"; return SPARSERT_EINVAL; }
             if (gen.lds_bytes == 0) gen.lds_bytes = 256;
         }
     }
@@ -640,7 +666,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         e.line("\t.p2align 2");
         e.line(".Lg%d:", g);
         sp.group_columns[g] = lds ? gen.block_lds(members[g], g % W, W)
-                                  : gen.block_direct(members[g / KS], g % KS, KS, max_rows);
+                                  : gen.block_direct(members[g / KS], g % KS, KS);
     }
     e.line(".Lfunc_end:");
     e.line("\t.size\tsparsert_spec, .Lfunc_end-sparsert_spec");

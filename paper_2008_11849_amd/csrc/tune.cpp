@@ -100,9 +100,11 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
             }
         }
         if (K >= 512) {   // long reduction axis: split it over the waves of a workgroup
-            const int rk[][2] = {{16, 8}, {24, 8}, {32, 8}, {32, 4}, {48, 4}, {64, 4}, {64, 2}, {96, 2}};
+            const int rk[][2] = {{16, 8}, {24, 8}, {32, 8}, {48, 8}, {64, 8}, {32, 4}, {48, 4}, {64, 4},
+                                 {96, 4}, {64, 2}, {96, 2}};
             for (auto &c : rk) {
-                if (c[0] > M) continue;
+                // needs at least two waves for every SIMD of the chip to be worth timing
+                if (c[0] > M || (int64_t)((M + c[0] - 1) / c[0]) * tiles * c[1] < 2048) continue;
                 sparsert_options o = b;
                 o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
                 o.spec_rows = c[0]; o.spec_ksplit = c[1];

@@ -100,10 +100,32 @@ def test_spec_ksplit_small_integers_bit_exact(N, ks):
     csr = synth.small_int_csr(77, 130, 0.85, N)
     B = synth.small_int_dense(130, N, N + 1)
     Cref, _ = _oracle(csr, B)
-    for rows in (0, 1, 7, 36):   # (ks-1) * rows * 256 B of LDS must stay within 64 KiB
+    for rows in (0, 1, 7, 36, 77):   # 77 rows x 8 waves: the exchange area spans three 64 KiB windows
         got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_ksplit=ks)
         assert info["spec_ksplit"] == ks and info["spec_tiles"] == ks
         assert np.array_equal(got.astype(np.float64), Cref), (N, rows, ks)
+
+
+@pytest.mark.parametrize("depth", [1, 2, 3, 5, 48])
+def test_spec_depth_small_integers_bit_exact(depth):
+    csr = synth.small_int_csr(40, 90, 0.8, depth)
+    B = synth.small_int_dense(90, 100, depth + 1)
+    Cref, _ = _oracle(csr, B)
+    for ks in (0, 2):
+        got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=9, spec_depth=depth, spec_ksplit=ks)
+        assert info["spec_depth"] == depth
+        assert np.array_equal(got.astype(np.float64), Cref), (depth, ks)
+
+
+def test_spec_ksplit_largest_block():
+    csr = synth.small_int_csr(200, 96, 0.9, 5)
+    B = synth.small_int_dense(96, 130, 6)
+    Cref, _ = _oracle(csr, B)
+    got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=200, spec_ksplit=4, spec_depth=24)
+    assert info["spec_lds_bytes"] == 3 * 200 * 256
+    assert np.array_equal(got.astype(np.float64), Cref)
+    with pytest.raises(sp.SparseRTError, match="LDS"):
+        run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=200, spec_ksplit=8)
 
 
 def test_spec_ksplit_configs_and_skew():
