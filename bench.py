@@ -257,7 +257,7 @@ def main():
         "layers": per_layer,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(tag),
-                     "kernel": "sparsert_spec / sparsert::rows_kernel (per layer, see layers[].plan.kernel: 2 / 1)",
+                     "kernel": "sparsert_spec_<M>x<K>x<N> (generated per layer) / sparsert::rows_kernel; see layers[].plan.kernel: 2 / 1",
                      "avg_launch_us": kernel_ms * 1e3,
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "alu_frac_of_fp32_vector_peak":

@@ -248,7 +248,7 @@ int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err) {
         hipError_t e1 = hipModuleLoadData(&mod, h.spec.code.data());
         if (e1 != hipSuccess) { err = std::string("loading the generated kernel: ") + hipGetErrorString(e1); return SPARSERT_ECOMPILE; }
         d.spec_module = mod;
-        hipError_t e2 = hipModuleGetFunction(&fn, mod, "sparsert_spec");
+        hipError_t e2 = hipModuleGetFunction(&fn, mod, h.spec.symbol.c_str());
         if (e2 != hipSuccess) { err = std::string("generated kernel symbol: ") + hipGetErrorString(e2); return SPARSERT_ECOMPILE; }
         d.spec_function = fn;
     }

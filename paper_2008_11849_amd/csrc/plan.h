@@ -18,6 +18,7 @@ constexpr int kFullTasks = 2048;  // wave tasks wanted before widening per-lane 
 struct SpecPlan {
     int32_t rows_per_group = 0, n_groups = 0, depth = 0, n_tiles = 0, lanes_per_tile = 0;
     int32_t tiles_per_wg = 4;   // waves per workgroup
+    std::string symbol;         // kernel symbol inside the code object
     int32_t mode = 0;           // sparsert_spec_mode
     int32_t n_blocks = 0;       // code blocks (n_groups, padded to a multiple of the waves in LDS mode)
     int32_t lds_bytes = 0;

@@ -552,11 +552,15 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\t.amdgcn_target \"amdgcn-amd-amdhsa--gfx950\"");
     e.line("\t.amdhsa_code_object_version 6");
     e.line("\t.text");
-    e.line("\t.protected\tsparsert_spec");
-    e.line("\t.globl\tsparsert_spec");
+    // The symbol carries the problem shape so that kernel traces tell the plans of a model apart.
+    char sym[96];
+    snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N);
+    sp.symbol = sym;
+    e.line("\t.protected\t%s", sym);
+    e.line("\t.globl\t%s", sym);
     e.line("\t.p2align\t8");
-    e.line("\t.type\tsparsert_spec,@function");
-    e.line("sparsert_spec:");
+    e.line("\t.type\t%s,@function", sym);
+    e.line("%s:", sym);
     // s[0:1] kernarg, s2 = workgroup id x, s3 = workgroup id y, v0 = thread id
     e.line("\ts_load_dwordx4 s[%d:%d], s[0:1], 0x0", kSgprB, kSgprC + 1);
     e.line("\tv_lshrrev_b32_e32 v%d, 6, v0", kVgprT1);
@@ -669,10 +673,10 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
                                   : gen.block_direct(members[g / KS], g % KS, KS);
     }
     e.line(".Lfunc_end:");
-    e.line("\t.size\tsparsert_spec, .Lfunc_end-sparsert_spec");
+    e.line("\t.size\t%s, .Lfunc_end-%s", sym, sym);
     e.line("\t.section\t.rodata,\"a\",@progbits");
     e.line("\t.p2align\t6, 0x0");
-    e.line("\t.amdhsa_kernel sparsert_spec");
+    e.line("\t.amdhsa_kernel %s", sym);
     e.line("\t\t.amdhsa_group_segment_fixed_size %d", gen.lds_bytes);
     e.line("\t\t.amdhsa_private_segment_fixed_size 0");
     e.line("\t\t.amdhsa_kernarg_size 16");
@@ -724,11 +728,11 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("    .kernarg_segment_align: 8");
     e.line("    .kernarg_segment_size: 16");
     e.line("    .max_flat_workgroup_size: %d", W * kWave);
-    e.line("    .name:           sparsert_spec");
+    e.line("    .name:           %s", sym);
     e.line("    .private_segment_fixed_size: 0");
     e.line("    .sgpr_count:     %d", kNextFreeSgpr + 6);
     e.line("    .sgpr_spill_count: 0");
-    e.line("    .symbol:         sparsert_spec.kd");
+    e.line("    .symbol:         %s.kd", sym);
     e.line("    .uniform_work_group_size: 1");
     e.line("    .uses_dynamic_stack: false");
     e.line("    .vgpr_count:     %d", n_vgpr);
