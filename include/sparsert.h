@@ -83,7 +83,14 @@ typedef struct sparsert_options {
                                 code block's rows and column tile and split its columns (equal
                                 nonzero shares, partial sums meet in LDS); 0/1 = no split.  Sets
                                 the workgroup width, spec_tiles is then ignored */
-    int32_t reserved[1];     /* must be zero */
+    int32_t natural_order;   /* 1: load-balance ablation (Section 4.3): rows keep their input order
+                                (identity permutation), no row is split over waves, and the
+                                generated kernel's blocks are contiguous row ranges; 0 = balanced */
+    int32_t spec_lanes;      /* SPARSERT_KERNEL_SPEC: widest column tile of a wave, 16, 32 or 64 lanes
+                                (0 = 64).  Narrow tiles leave lanes idle but let a compute unit
+                                cover more rows of fewer columns, which cuts the bytes of B it
+                                pulls in when M is small and K long */
+    int32_t reserved[3];     /* must be zero */
 } sparsert_options;
 
 /*
@@ -150,8 +157,9 @@ int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, 
  * configurations, done once per problem, off the inference path).  Builds a plan for each
  * candidate configuration - executor family, columns per lane, split threshold, rows per
  * generated code block, waves per workgroup, staging variant - times it on the GPU with the
- * given operands, and returns the fastest plan.  `base` fixes dtype and the convolution
- * geometry; its tuning fields are ignored.
+ * given operands, and returns the fastest plan.  `base` fixes dtype, the convolution
+ * geometry and natural_order; base->kernel other than AUTO restricts the search to that
+ * executor family (the specialisation ablation); its other tuning fields are ignored.
  *
  *   in_dev / out_dev  DEVICE buffers of the shapes sparsert_spmm / sparsert_conv3x3 take;
  *                     out_dev is overwritten many times
@@ -164,7 +172,7 @@ int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, 
  */
 #define SPARSERT_TUNE_MAX 64
 typedef struct sparsert_tune_entry {
-    int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles, spec_ksplit;
+    int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles, spec_ksplit, spec_lanes;
     float microseconds; /* per launch; negative if the candidate failed */
 } sparsert_tune_entry;
 typedef struct sparsert_tune_report {
@@ -223,6 +231,8 @@ enum {
     SPARSERT_INFO_SPEC_MODE,      /* SPEC plans: sparsert_spec_mode in use */
     SPARSERT_INFO_SPEC_LDS_BYTES, /* SPEC plans: LDS per workgroup */
     SPARSERT_INFO_SPEC_KSPLIT,    /* SPEC plans: K parts per workgroup (1 = none) */
+    SPARSERT_INFO_NATURAL_ORDER,  /* 1 if the plan was built with natural_order */
+    SPARSERT_INFO_SPEC_LANES,     /* SPEC plans: lanes per column tile in use (balanced, <= spec_lanes) */
     SPARSERT_INFO_COUNT = 32      /* remaining entries are zero */
 };
 

@@ -55,7 +55,7 @@ def choose_vec(M, N, vmax):
     return max(full) if full else min(kept)
 
 
-def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0):
+def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, natural_order=False):
     row_ptr = np.asarray(row_ptr, dtype=np.int64)
     col_idx = np.asarray(col_idx, dtype=np.int64)
     vals = np.asarray(vals)
@@ -65,7 +65,8 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0):
     row_nnz = np.diff(row_ptr)
     bins_of = _bin(row_nnz)
     hist = np.bincount(bins_of, minlength=33)
-    perm = np.argsort(-row_nnz, kind="stable")
+    # natural order (load-balance ablation): identity permutation and no split rows
+    perm = np.arange(M) if natural_order else np.argsort(-row_nnz, kind="stable")
     inv_perm = np.empty(M, dtype=np.int64)
     inv_perm[perm] = np.arange(M)
     p_nnz = row_nnz[perm]
@@ -91,6 +92,8 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0):
     n_tiles = -(-nvc // WAVE)
     lanes_per_tile = -(-nvc // n_tiles)
     thr = split_threshold if split_threshold else (64 if M * n_tiles < FULL_TASKS else 512)
+    if natural_order:
+        thr = 2**31 - 1
     n_split = int(np.sum(p_nnz >= thr))
     n_wg_rows = n_split + -(-(M - n_split) // GY)
     segments = np.zeros((n_split, GY + 1), dtype=np.int64)
@@ -131,11 +134,14 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0):
                 segments=i32(segments.reshape(-1)))
 
 
-def spec_groups(M, rows_per_group):
+def spec_groups(M, rows_per_group, natural_order=False):
     """Code block of every slot in the generated kernel: serpentine dealing of the
-    nnz-descending slots over G = ceil(M/R) blocks (block-level balance, Section 3.4)."""
+    nnz-descending slots over G = ceil(M/R) blocks (block-level balance, Section 3.4);
+    in natural order, contiguous ranges of R rows."""
     R = min(rows_per_group, M)
     G = -(-M // R)
     i = np.arange(M)
+    if natural_order:
+        return (i // R).astype(np.int32)
     rnd, pos = i // G, i % G
     return np.where(rnd % 2 == 1, G - 1 - pos, pos).astype(np.int32)

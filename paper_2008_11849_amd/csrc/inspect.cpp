@@ -1,6 +1,7 @@
 // Host-side inspector (Sections 2.3 and 3.4): integer analysis of the fixed
 // sparsity pattern.  Nothing here touches a value arithmetically.
 #include <algorithm>
+#include <climits>
 #include <cstring>
 #include <numeric>
 
@@ -38,7 +39,9 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (M <= 0 || K <= 0 || N <= 0) { err = "M, K and N must be positive"; return SPARSERT_EINVAL; }
     if (opt.dtype != SPARSERT_F32 && opt.dtype != SPARSERT_F16) { err = "unknown dtype"; return SPARSERT_EINVAL; }
     if (opt.kernel < SPARSERT_KERNEL_AUTO || opt.kernel > SPARSERT_KERNEL_SPEC) { err = "unknown kernel family"; return SPARSERT_EINVAL; }
-    for (int i = 0; i < 1; ++i)
+    if (opt.natural_order != 0 && opt.natural_order != 1) { err = "natural_order must be 0 or 1"; return SPARSERT_EINVAL; }
+    if (opt.spec_lanes != 0 && opt.spec_lanes != 16 && opt.spec_lanes != 32 && opt.spec_lanes != 64) { err = "spec_lanes must be 0,16,32,64"; return SPARSERT_EINVAL; }
+    for (int i = 0; i < 3; ++i)
         if (opt.reserved[i] != 0) { err = "reserved option fields must be zero"; return SPARSERT_EINVAL; }
     if (row_ptr[0] != 0) { err = "row_ptr[0] must be 0"; return SPARSERT_EINVAL; }
     for (int32_t m = 0; m < M; ++m)
@@ -126,8 +129,10 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
     }
     h.perm.resize(M);
     std::iota(h.perm.begin(), h.perm.end(), 0);
-    std::stable_sort(h.perm.begin(), h.perm.end(),
-                     [&](int32_t a, int32_t b) { return h.row_nnz[a] > h.row_nnz[b]; });
+    h.natural_order = opt.natural_order;
+    if (!h.natural_order)
+        std::stable_sort(h.perm.begin(), h.perm.end(),
+                         [&](int32_t a, int32_t b) { return h.row_nnz[a] > h.row_nnz[b]; });
     h.inv_perm.resize(M);
     for (int32_t i = 0; i < M; ++i) h.inv_perm[h.perm[i]] = i;
 
@@ -168,6 +173,7 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (opt.split_threshold) h.split_threshold = opt.split_threshold;
     else h.split_threshold = ((int64_t)M * h.n_tiles < kFullTasks) ? 64 : 512;
     h.n_split = 0;
+    if (h.natural_order) h.split_threshold = INT32_MAX;   // split rows are a prefix of the sorted order only
     while (h.n_split < M && h.row_nnz[h.perm[h.n_split]] >= h.split_threshold) ++h.n_split;
     h.n_wg_rows = h.n_split + (M - h.n_split + h.gy - 1) / h.gy;
     h.segments.resize((size_t)h.n_split * (h.gy + 1));

@@ -34,6 +34,7 @@ struct HostPlan {
     int32_t dtype = 0, conv = 0, Cin = 0, H = 0, W = 0, kernel = 0;
     int32_t vec = 1, lanes_per_tile = 0, n_tiles = 0, gy = kGy;
     int32_t split_threshold = 0, n_split = 0, n_wg_rows = 0;
+    int32_t natural_order = 0;         // rows kept in input order (load-balance ablation)
 
     std::vector<int32_t> row_nnz, hist, perm, inv_perm, p_row_ptr, p_col_idx;
     std::vector<uint8_t> p_vals;       // nnz * elem_size bytes, bit copies

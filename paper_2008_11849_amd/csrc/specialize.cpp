@@ -200,6 +200,7 @@ struct Gen {
     int N, K, D;
     int vgpr_stage0 = 0, vgpr_ring0 = 0, n_vgpr = 0, lds_bytes = 0;
     int ring_size = 0;               // DIRECT: registers of the operand ring (>= D)
+    int slot_bytes = 256;            // K split: bytes of one row's partial sums in the exchange area
     int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
     Gen(const HostPlan &hp, SpecPlan &s) : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth) {}
 
@@ -308,10 +309,10 @@ struct Gen {
             const int nr = (int)rows.size();
             auto slot = [&](int i, int q) {   // byte offset of wave q's partial of row i, q != i % parts
                 const int o = i % parts;
-                return (i * (parts - 1) + (q < o ? q : q - 1)) * 256;
+                return (i * (parts - 1) + (q < o ? q : q - 1)) * slot_bytes;
             };
             // ds offsets are 16 bits wide: one address register per 64 KiB of the exchange area
-            const int n_base = ((parts - 1) * nr * 256 + 65535) / 65536;
+            const int n_base = ((parts - 1) * nr * slot_bytes + 65535) / 65536;
             const int base0 = vgpr_ring0;          // the operand ring is free now
             for (int b = 1; b < n_base; ++b)
                 e.line("\tv_add_u32_e32 v%d, 0x%x, v%d", base0 + b, b * 65536, kVgprLds);
@@ -467,7 +468,9 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     sp.mode = opt.spec_mode ? opt.spec_mode : SPARSERT_SPEC_DIRECT;
     const bool lds = sp.mode == SPARSERT_SPEC_LDS;
     // Column tiling with one column per lane, balanced tails (same rule as the row-walk plan at V = 1).
-    sp.n_tiles = (N + kWave - 1) / kWave;
+    const int max_lanes = opt.spec_lanes ? opt.spec_lanes : kWave;
+    if (lds && max_lanes != kWave) { err = "spec_lanes applies to the DIRECT variant"; return SPARSERT_EINVAL; }
+    sp.n_tiles = (N + max_lanes - 1) / max_lanes;
     sp.lanes_per_tile = (N + sp.n_tiles - 1) / sp.n_tiles;
     sp.tiles_per_wg = opt.spec_tiles ? opt.spec_tiles : 4;
     sp.ksplit = opt.spec_ksplit ? opt.spec_ksplit : 1;
@@ -504,7 +507,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     std::vector<std::vector<int32_t>> members(n_blocks);
     for (int32_t i = 0; i < M; ++i) {
         const int32_t round = i / G, pos = i % G;
-        const int32_t g = (round & 1) ? G - 1 - pos : pos;
+        // natural order (ablation): block g is the contiguous row range [g*R, (g+1)*R)
+        const int32_t g = h.natural_order ? i / R : ((round & 1) ? G - 1 - pos : pos);
         sp.group_of_slot[i] = g;
         members[g].push_back(i);
     }
@@ -540,7 +544,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         gen.ring_size = KS > 1 ? std::max(D, 8) : D;   // the K-split exchange borrows the ring
         gen.n_vgpr = gen.vgpr_ring0 + gen.ring_size;
         if (KS > 1) {
-            gen.lds_bytes = (KS - 1) * max_rows * 256;
+            gen.slot_bytes = 4 * max_lanes;   // lane l of a wave keeps its partial at byte 4*l of the slot
+            gen.lds_bytes = (KS - 1) * max_rows * gen.slot_bytes;
             if (gen.lds_bytes > kMaxLdsBytes) { err = "spec_rows x spec_ksplit needs more than 160 KiB of LDS"; return SPARSERT_EINVAL; }
             if (gen.lds_bytes == 0) gen.lds_bytes = 256;
         }
@@ -601,6 +606,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     // lanes without a column redo the tile's first column: loads stay in bounds, nothing is stored
     e.line("\tv_cndmask_b32_e64 v%d, v%d, v%d, s[%d:%d]", kVgprT1, kVgprT2, kVgprT1, kSgprOwns, kSgprOwns + 1);
     e.line("\tv_lshlrev_b32_e32 v%d, 2, v%d", kVgprOff, kVgprT1);  // byte offset of the column inside a row
+    // from here on only lanes that own a column are active: idle lanes fetch nothing
+    e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
     if (h.conv) {
         // oh = pixel / W, ow = pixel % W; then one lane mask per filter tap (r, s):
         // 0 <= oh + r - 1 < H and 0 <= ow + s - 1 < W  (Section 3.6: the padding test, made once)

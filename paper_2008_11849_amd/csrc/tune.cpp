@@ -46,11 +46,12 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
     sparsert_options b;
     if (base) b = *base; else std::memset(&b, 0, sizeof(b));
     b.host_only = 0;
+    b.vec = b.split_threshold = b.spec_rows = b.spec_depth = b.spec_tiles = b.spec_mode = b.spec_ksplit = b.spec_lanes = 0;
     // First candidate: the inspector's own choice.  It also validates every argument.
     sparsert_plan *best = nullptr;
     {
         sparsert_options o = b;
-        o.kernel = SPARSERT_KERNEL_ROWS;
+        o.kernel = b.kernel == SPARSERT_KERNEL_SPEC ? SPARSERT_KERNEL_SPEC : SPARSERT_KERNEL_ROWS;
         if (int rc = sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &best)) return rc;
     }
     if (!out || !in_dev || !out_dev || (((uintptr_t)in_dev | (uintptr_t)out_dev) & 15u)) {
@@ -65,6 +66,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
         return sparsert::set_error(SPARSERT_EHIP, "hipEventCreate failed");
     }
     const bool conv = b.conv != 0, f16 = b.dtype == SPARSERT_F16;
+    const int family = b.kernel;   // AUTO: both executor families; else only that one
     const int64_t nnz = row_ptr[M];
     const int launches = 30, repeats = 3;
 
@@ -85,7 +87,8 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
             cands.push_back(o);
         }
     }
-    if (!f16 && nnz <= (4 << 20)) {
+    if (family == SPARSERT_KERNEL_SPEC) cands.clear();
+    if (!f16 && nnz <= (4 << 20) && family != SPARSERT_KERNEL_ROWS) {
         const int64_t tiles = (N + 63) / 64;
         for (int r : {1, 2, 4, 8, 16, 24, 48}) {
             if (r > M) continue;
@@ -100,11 +103,14 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
             }
         }
         if (K >= 512) {   // long reduction axis: split it over the waves of a workgroup
-            const int rk[][2] = {{16, 8}, {24, 8}, {32, 8}, {48, 8}, {64, 8}, {32, 4}, {48, 4}, {64, 4},
-                                 {96, 4}, {64, 2}, {96, 2}};
+            const int rk[][2] = {{1, 8}, {2, 8}, {4, 8}, {8, 8}, {16, 8}, {24, 8}, {32, 8}, {48, 8}, {64, 8},
+                                 {1, 4}, {2, 4}, {4, 4}, {8, 4}, {16, 4}, {32, 4}, {48, 4}, {64, 4}, {96, 4},
+                                 {64, 2}, {96, 2}};
             for (auto &c : rk) {
-                // needs at least two waves for every SIMD of the chip to be worth timing
-                if (c[0] > M || (int64_t)((M + c[0] - 1) / c[0]) * tiles * c[1] < 2048) continue;
+                // worth timing with at least two waves for every SIMD of the chip, but not with
+                // more than sixteen (the blocks are then too small to reuse a fetched row)
+                const int64_t waves = (int64_t)((M + c[0] - 1) / c[0]) * tiles * c[1];
+                if (c[0] > M || waves < 2048 || waves > 16384) continue;
                 sparsert_options o = b;
                 o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
                 o.spec_rows = c[0]; o.spec_ksplit = c[1];
@@ -131,6 +137,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
         t.kernel = h.kernel; t.vec = h.vec; t.split_threshold = h.split_threshold;
         t.spec_mode = h.spec.mode; t.spec_rows = h.spec.rows_per_group; t.spec_tiles = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.tiles_per_wg : 0;
         t.spec_ksplit = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.ksplit : 0;
+        t.spec_lanes = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.lanes_per_tile : 0;
         t.microseconds = us;
     };
     log(best, best_us);

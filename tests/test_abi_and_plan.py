@@ -31,8 +31,25 @@ def test_library_exports_every_declared_symbol():
     assert sp.version() >= 100
 
 
+def _header_struct_fields(name):
+    """(field, element count) of a header struct whose members are all int32_t / float."""
+    text = open(os.path.join(os.path.dirname(sp.LIB_PATH), "..", "include", "sparsert.h")).read()
+    body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (name, name), text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    out = []
+    for decl in re.findall(r"(?:int32_t|float)\s+([^;]+);", body):
+        for item in decl.split(","):
+            m = re.match(r"\s*(\w+)(?:\[(\d+)\])?\s*$", item)
+            out.append((m.group(1), int(m.group(2) or 1)))
+    return out
+
+
 def test_options_struct_matches_header_layout():
-    assert ctypes.sizeof(sp.Options) == 16 * 4
+    want = _header_struct_fields("sparsert_options")
+    got = [(n, getattr(t, "_length_", 1)) for n, t in sp.Options._fields_]
+    assert got == want
+    assert ctypes.sizeof(sp.Options) == 4 * sum(c for _, c in want) == 20 * 4
+    assert [n for n, _ in sp.TuneEntry._fields_] == [n for n, _ in _header_struct_fields("sparsert_tune_entry")]
 
 
 def _host_plan(csr, N, **kw):
@@ -77,6 +94,29 @@ def test_plan_overrides(vec, thr):
     plan = _host_plan(csr, 64, vec=vec, split_threshold=thr)
     _assert_plan_equal(plan, plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, 100, 200, 64,
                                            vec=vec, split_threshold=thr))
+
+
+def test_natural_order_plan_is_bit_exact():
+    """Load-balance ablation: identity permutation, no split rows, contiguous code blocks."""
+    csr = synth.skewed_csr(100, 200, 0.8, 3)
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 100, 200, 64, host_only=True, natural_order=True)
+    ref = plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, 100, 200, 64, natural_order=True)
+    _assert_plan_equal(plan, ref)
+    info = plan.info()
+    assert info["natural_order"] == 1 and info["n_split"] == 0
+    assert np.array_equal(plan.export(sp.FIELD_PERM), np.arange(100))
+    assert np.array_equal(plan.export(sp.FIELD_P_COL_IDX), csr.col_idx)
+    plan.destroy()
+    spec = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 100, 200, 64, host_only=True, natural_order=True,
+                      kernel=sp.KERNEL_SPEC, spec_rows=7)
+    assert spec.export(sp.FIELD_SPEC_GROUPS).tobytes() == plan_ref.spec_groups(100, 7, natural_order=True).tobytes()
+    spec.destroy()
+    with pytest.raises(sp.SparseRTError):
+        opt = sp.Options()
+        opt.natural_order = 2
+        h = ctypes.c_void_p()
+        sp._check(sp.raw.sparsert_inspect(csr.row_ptr.ctypes.data_as(ctypes.c_void_p), csr.col_idx.ctypes.data_as(ctypes.c_void_p),
+                                       csr.vals.ctypes.data_as(ctypes.c_void_p), 100, 200, 64, ctypes.byref(opt), ctypes.byref(h)))
 
 
 @pytest.mark.parametrize("Cin,Cout,H,W,dt", [(5, 7, 6, 9, np.float32), (16, 24, 14, 14, np.float16),
@@ -215,10 +255,23 @@ def test_generated_kernel_plan_assembles_on_the_host(rows, mode):
                               "info": {"M": 100, "nnz": csr.nnz}})
 
 
+def test_generated_kernel_ksplit_lds_budget():
+    """(KS-1) x rows x 4 x lanes bytes of exchange area must fit the 160 KiB of a compute unit."""
+    csr = synth.uniform_csr(200, 64, 0.9, 2)
+    args = (csr.row_ptr, csr.col_idx, csr.vals, 200, 64, 100)
+    with pytest.raises(sp.SparseRTError, match="LDS"):
+        sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, spec_rows=200, spec_ksplit=8)
+    plan = sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, spec_rows=200, spec_ksplit=8, spec_lanes=16)
+    info = plan.info()
+    assert info["spec_lds_bytes"] == 7 * 200 * 64 and info["spec_lanes"] == 15   # 100 columns in 7 balanced tiles
+    plan.destroy()
+
+
 def test_generated_kernel_option_errors():
     csr = synth.uniform_csr(16, 18, 0.5, 1)
     args = (csr.row_ptr, csr.col_idx, csr.vals, 16, 18, 8)
-    for kw in ({"spec_tiles": 3}, {"spec_mode": 9}, {"spec_depth": 99}, {"spec_rows": 500}):
+    for kw in ({"spec_tiles": 3}, {"spec_mode": 9}, {"spec_depth": 99}, {"spec_rows": 500}, {"spec_lanes": 48},
+               {"spec_ksplit": 3}, {"spec_ksplit": 2, "spec_mode": sp.SPEC_LDS}, {"spec_lanes": 32, "spec_mode": sp.SPEC_LDS}):
         with pytest.raises(sp.SparseRTError) as e:
             sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, **kw)
         assert e.value.status == sp.EINVAL, kw

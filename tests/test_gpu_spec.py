@@ -12,7 +12,7 @@ torch = pytest.importorskip("torch")
 if not torch.cuda.is_available():  # pragma: no cover
     pytest.skip("no GPU", allow_module_level=True)
 
-from gpu_util import check, run_spmm  # noqa: E402
+from gpu_util import check, run_conv, run_spmm  # noqa: E402
 from paper_2008_11849_amd import sparsert as sp  # noqa: E402
 
 
@@ -138,6 +138,60 @@ def test_spec_ksplit_configs_and_skew():
     got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_rows=16, spec_ksplit=8)
     Cref, S = _oracle(case.csr, case.B)
     check(got, Cref, S, np.float32)
+
+
+@pytest.mark.parametrize("lanes", [16, 32, 64])
+@pytest.mark.parametrize("N", [1, 17, 65, 196, 300])
+def test_spec_narrow_tiles_small_integers_bit_exact(N, lanes):
+    csr = synth.small_int_csr(77, 130, 0.85, N + lanes)
+    B = synth.small_int_dense(130, N, N + 1)
+    Cref, _ = _oracle(csr, B)
+    for opts in (dict(spec_rows=7), dict(spec_rows=20, spec_ksplit=4), dict(spec_rows=77, spec_ksplit=8)):
+        got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_lanes=lanes, **opts)
+        assert 1 <= info["spec_lanes"] <= lanes and info["n_tiles"] >= 1
+        assert np.array_equal(got.astype(np.float64), Cref), (N, lanes, opts)
+
+
+def test_spec_narrow_tiles_config_and_conv():
+    case = synth.config("c2")
+    Cref, S = _oracle(case.csr, case.B)
+    for lanes in (16, 32):
+        got, info = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_rows=16, spec_ksplit=2, spec_lanes=lanes)
+        check(got, Cref, S, np.float32, gate_relative=True)
+    csr, Wd = synth.conv_weights_csr(24, 16, 0.8, 5)
+    X = synth.normal_dense(16, 9 * 13, 6).reshape(1, 16, 9, 13)
+    Yref, S = ref.conv3x3(Wd, X)
+    for lanes in (16, 32):
+        got, info = run_conv(csr, X, 24, kernel=sp.KERNEL_SPEC, spec_rows=3, spec_lanes=lanes)
+        check(got, Yref, S, np.float32)
+
+
+NATURAL = [dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=9), dict(kernel=sp.KERNEL_SPEC, spec_rows=12, spec_mode=sp.SPEC_LDS),
+           dict(kernel=sp.KERNEL_SPEC, spec_rows=20, spec_ksplit=4)]
+
+
+@pytest.mark.parametrize("opts", NATURAL)
+def test_natural_order_ablation_is_still_exact(opts):
+    """Rows in input order, unsplit, contiguous code blocks: slower on skewed matrices, same result."""
+    case = synth.sweep_case(256, 512, 196, 0.95, "skewed", np.float32)   # long and empty rows side by side
+    got, info = run_spmm(case.csr, case.B, natural_order=True, **opts)
+    assert info["natural_order"] == 1 and info["n_split"] == 0
+    Cref, S = _oracle(case.csr, case.B)
+    check(got, Cref, S, np.float32)
+    csr = synth.small_int_csr(77, 130, 0.85, 9)
+    B = synth.small_int_dense(130, 65, 10)
+    got, _ = run_spmm(csr, B, natural_order=True, **opts)
+    assert np.array_equal(got.astype(np.float64), _oracle(csr, B)[0])
+
+
+def test_natural_order_conv():
+    csr, Wd = synth.conv_weights_csr(24, 16, 0.8, 5)
+    X = synth.normal_dense(16, 14 * 14, 6).reshape(1, 16, 14, 14)
+    Yref, S = ref.conv3x3(Wd, X)
+    for opts in (dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=3)):
+        got, info = run_conv(csr, X, 24, natural_order=True, **opts)
+        assert info["natural_order"] == 1
+        check(got, Yref, S, np.float32)
 
 
 CONV_SHAPES = [(3, 5, 1, 1), (4, 6, 2, 3), (2, 3, 1, 9), (2, 3, 9, 1), (8, 8, 7, 7), (16, 24, 14, 14),
