@@ -65,6 +65,9 @@ def geomean(xs):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--only", default="", help="comma list of problem tags to run, e.g. t1_p9_90,t3_p3_95")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time, per problem, the best row-walk (not specialised) plan and the best plan "
+                         "without load balancing (rows in input order): the paper's two ablations (Section 4.3)")
     args = ap.parse_args()
     import numpy as np
     import torch
@@ -79,20 +82,32 @@ def main():
 
     def run(tag, csr, N, inp, out, dense_fn, conv=None):
         cur = lambda: torch.cuda.current_stream().cuda_stream
-        plan, report = sp.tune(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N,
-                               inp.data_ptr(), out.data_ptr(), cur(), conv=conv)
         fn = sp.raw.sparsert_conv3x3 if conv else sp.raw.sparsert_spmm
-        h, a, b = ctypes.c_void_p(plan.handle), ctypes.c_void_p(inp.data_ptr()), ctypes.c_void_p(out.data_ptr())
+        a, b = ctypes.c_void_p(inp.data_ptr()), ctypes.c_void_p(out.data_ptr())
 
-        def sparse():
-            rc = fn(h, a, b, ctypes.c_void_p(cur()))
-            assert rc == 0, sp.last_error()
+        def tuned(**kw):
+            plan, _ = sp.tune(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N,
+                              inp.data_ptr(), out.data_ptr(), cur(), conv=conv, **kw)
+            h = ctypes.c_void_p(plan.handle)
 
-        sparse()
-        torch.cuda.synchronize()
-        eager = out.clone()
-        t_sparse = graph_us(torch, sparse)
-        assert torch.equal(out, eager), "graph replay changed the result"
+            def sparse():
+                rc = fn(h, a, b, ctypes.c_void_p(cur()))
+                assert rc == 0, sp.last_error()
+
+            sparse()
+            torch.cuda.synchronize()
+            eager = out.clone()
+            t = graph_us(torch, sparse)
+            assert torch.equal(out, eager), "graph replay changed the result"
+            return plan, t
+
+        extra = {}
+        if args.ablation:
+            for key, kw in (("rows_only_us", {"kernel": sp.KERNEL_ROWS}), ("natural_order_us", {"natural_order": True})):
+                p_abl, t_abl = tuned(**kw)
+                p_abl.destroy()
+                extra[key] = round(t_abl, 3)
+        plan, t_sparse = tuned()
         try:
             t_dense, dense_how = graph_us(torch, dense_fn), "graph"
         except Exception:  # a library call that cannot be captured: plain event loop instead
@@ -111,7 +126,8 @@ def main():
         return {"tag": tag, "sparse_us": round(t_sparse, 3), "dense_us": round(t_dense, 3),
                 "speedup": round(t_dense / t_sparse, 3), "dense_timing": dense_how,
                 "gflops": round(2.0 * csr.nnz * N / t_sparse / 1e3, 1),
-                "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit")}}
+                "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit")},
+                **extra}
 
     for sparsity in (0.90, 0.95):
         pct = int(round(sparsity * 100))
@@ -146,12 +162,18 @@ def main():
     def gm(prefix, s):
         return geomean([r["speedup"] for r in rows if r["tag"].startswith(prefix) and r["sparsity"] == s])
 
+    ablation = None
+    if args.ablation:
+        ablation = {"specialised_over_row_walk": geomean([r["rows_only_us"] / r["sparse_us"] for r in rows]),
+                    "balanced_over_natural_order": geomean([r["natural_order_us"] / r["sparse_us"] for r in rows]),
+                    "paper": "unrolled code > 10x over rolled loops; load balancing up to 2x (Section 4.3)"}
     print(json.dumps({
         "workload": "paper Table 1 (SpMM) and Table 3 (3x3 conv) shapes, synthetic magnitude-pruned weights, fp32",
         "timing": f"{INNER} launches per HIP graph, 20 replays, HIP events; same for sparse and dense",
         "geomean_speedup_vs_dense": {"table1_90": gm("t1", 0.90), "table1_95": gm("t1", 0.95),
                                      "table3_90": gm("t3", 0.90), "table3_95": gm("t3", 0.95)},
         "paper_geomean_t4": {"table1_90": 3.4, "table1_95": 5.4},
+        "ablation_geomean_speedup": ablation,
         "problems": rows}))
 
 

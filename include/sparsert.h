@@ -66,7 +66,7 @@ typedef struct sparsert_options {
     int32_t kernel;          /* sparsert_kernel; AUTO lets the inspector choose */
     int32_t conv;            /* 0: SpMM plan.  1: 3x3 / pad 1 / stride 1 convolution plan */
     int32_t Cin, H, W;       /* conv only: K must equal 9*Cin and N must equal H*W */
-    int32_t batch;           /* conv only: must be 1 (0 is read as 1) */
+    int32_t batch;           /* conv only: images per call, 1..65535 (0 is read as 1) */
     int32_t host_only;       /* 1: analyse only; no HIP call is made, the plan can be
                                 exported but not executed */
     int32_t vec;             /* columns of C per lane; 0 = automatic, else 1,2,4 (,8 for f16) */
@@ -90,7 +90,10 @@ typedef struct sparsert_options {
                                 (0 = 64).  Narrow tiles leave lanes idle but let a compute unit
                                 cover more rows of fewer columns, which cuts the bytes of B it
                                 pulls in when M is small and K long */
-    int32_t reserved[3];     /* must be zero */
+    int32_t spec_swizzle;    /* SPARSERT_KERNEL_SPEC: 1 = rows are dealt to code blocks by column-pattern
+                                similarity (the row swizzle the paper proposes as future work,
+                                Section 5), so a block touches fewer rows of B; 0 = serpentine deal */
+    int32_t reserved[2];     /* must be zero */
 } sparsert_options;
 
 /*
@@ -113,7 +116,7 @@ typedef struct sparsert_options {
  * opt->host_only is set the plan's device arrays are allocated and uploaded
  * here (synchronously) on the current HIP device.
  * Errors: EINVAL for null pointers, non-positive sizes, malformed CSR, bad
- * options; EUNSUPPORTED for batch > 1, for B or C of 2 GiB and more, for X of 128 MiB and more;
+ * options; EUNSUPPORTED for B or C of 2 GiB and more, for one image of X of 128 MiB and more;
  * ENOMEM / EHIP from allocation and upload.
  */
 int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
@@ -138,14 +141,16 @@ int sparsert_spmm(const sparsert_plan *plan, const void *B_dev, void *C_dev, voi
 
 /*
  * Executor, sparse 3x3 convolution (Section 3.6): padding 1, stride 1,
- * cross-correlation, batch 1.  The filter bank [Cout, Cin, 3, 3] is the plan's
- * A with M = Cout and column k = c*9 + r*3 + s; the im2col matrix is never
- * built - every reference to B[k, oh*W+ow] reads X[c, oh+r-1, ow+s-1] and the
- * padding test is resolved per (r,s) group by the inspector's ordering, not per
- * multiply.
+ * cross-correlation.  The filter bank [Cout, Cin, 3, 3] is the plan's A with
+ * M = Cout and column k = c*9 + r*3 + s; the im2col matrix is never built -
+ * every reference to B[k, oh*W+ow] reads X[c, oh+r-1, ow+s-1] and the padding
+ * test is resolved per (r,s) group by the inspector's ordering, not per
+ * multiply.  The paper evaluates batch 1 (Section 4.2); with opt->batch = b the
+ * b images of a call are independent convolutions with the same filters, run
+ * by one launch (the image is one more grid dimension).
  *
- *   X_dev  DEVICE, [1, Cin, H, W] contiguous, plan's dtype, 16-byte aligned
- *   Y_dev  DEVICE, [1, Cout, H, W] contiguous, plan's dtype, 16-byte aligned
+ *   X_dev  DEVICE, [batch, Cin, H, W] contiguous, plan's dtype, 16-byte aligned
+ *   Y_dev  DEVICE, [batch, Cout, H, W] contiguous, plan's dtype, 16-byte aligned
  *
  * Same asynchrony, ownership and error rules as sparsert_spmm; EINVAL if the
  * plan was not made with opt->conv = 1.
@@ -172,7 +177,7 @@ int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, 
  */
 #define SPARSERT_TUNE_MAX 64
 typedef struct sparsert_tune_entry {
-    int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles, spec_ksplit, spec_lanes;
+    int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles, spec_ksplit, spec_lanes, spec_swizzle;
     float microseconds; /* per launch; negative if the candidate failed */
 } sparsert_tune_entry;
 typedef struct sparsert_tune_report {
@@ -233,6 +238,8 @@ enum {
     SPARSERT_INFO_SPEC_KSPLIT,    /* SPEC plans: K parts per workgroup (1 = none) */
     SPARSERT_INFO_NATURAL_ORDER,  /* 1 if the plan was built with natural_order */
     SPARSERT_INFO_SPEC_LANES,     /* SPEC plans: lanes per column tile in use (balanced, <= spec_lanes) */
+    SPARSERT_INFO_SPEC_SWIZZLE,   /* SPEC plans: 1 if blocks were formed by similarity */
+    SPARSERT_INFO_BATCH,          /* conv plans: images per call; 0 for SpMM plans */
     SPARSERT_INFO_COUNT = 32      /* remaining entries are zero */
 };
 

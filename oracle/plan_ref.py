@@ -145,3 +145,33 @@ def spec_groups(M, rows_per_group, natural_order=False):
         return (i // R).astype(np.int32)
     rnd, pos = i // G, i % G
     return np.where(rnd % 2 == 1, G - 1 - pos, pos).astype(np.int32)
+
+
+def spec_groups_swizzled(p_row_ptr, p_col_idx, M, K, rows_per_group):
+    """Row swizzle (Section 5 names it as a preprocessing step that would help): the
+    nnz-descending slots are handed out in rounds of G = ceil(M/R); round 0 seeds block i
+    with slot i; in every later round the blocks, visited in serpentine direction, each take
+    the candidate of the round that shares the most columns with the union of the rows the
+    block already holds (ties: the lowest slot)."""
+    R = min(rows_per_group, M)
+    G = -(-M // R)
+    pat = np.zeros((M, K), dtype=bool)
+    for i in range(M):
+        pat[i, p_col_idx[p_row_ptr[i]:p_row_ptr[i + 1]]] = True
+    union = np.zeros((G, K), dtype=bool)
+    group = np.full(M, -1, dtype=np.int32)
+    rnd = 0
+    for first in range(0, M, G):
+        cand = list(range(first, min(M, first + G)))
+        for step in range(len(cand)):
+            g = G - 1 - step if rnd % 2 else step
+            free = [c for c in range(first, min(M, first + G)) if group[c] < 0]
+            if rnd == 0:
+                pick = free[0]
+            else:
+                shared = [(int(np.count_nonzero(pat[c] & union[g])), -c) for c in free]
+                pick = -max(shared)[1]
+            group[pick] = g
+            union[g] |= pat[pick]
+        rnd += 1
+    return group

@@ -41,7 +41,8 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (opt.kernel < SPARSERT_KERNEL_AUTO || opt.kernel > SPARSERT_KERNEL_SPEC) { err = "unknown kernel family"; return SPARSERT_EINVAL; }
     if (opt.natural_order != 0 && opt.natural_order != 1) { err = "natural_order must be 0 or 1"; return SPARSERT_EINVAL; }
     if (opt.spec_lanes != 0 && opt.spec_lanes != 16 && opt.spec_lanes != 32 && opt.spec_lanes != 64) { err = "spec_lanes must be 0,16,32,64"; return SPARSERT_EINVAL; }
-    for (int i = 0; i < 3; ++i)
+    if (opt.spec_swizzle != 0 && opt.spec_swizzle != 1) { err = "spec_swizzle must be 0 or 1"; return SPARSERT_EINVAL; }
+    for (int i = 0; i < 2; ++i)
         if (opt.reserved[i] != 0) { err = "reserved option fields must be zero"; return SPARSERT_EINVAL; }
     if (row_ptr[0] != 0) { err = "row_ptr[0] must be 0"; return SPARSERT_EINVAL; }
     for (int32_t m = 0; m < M; ++m)
@@ -77,8 +78,7 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
         if (opt.Cin <= 0 || opt.H <= 0 || opt.W <= 0) { err = "conv needs Cin, H, W > 0"; return SPARSERT_EINVAL; }
         if ((int64_t)K != 9ll * opt.Cin) { err = "conv needs K == 9*Cin"; return SPARSERT_EINVAL; }
         if ((int64_t)N != (int64_t)opt.H * opt.W) { err = "conv needs N == H*W"; return SPARSERT_EINVAL; }
-        if (opt.batch > 1) { err = "conv batch > 1 is not implemented"; return SPARSERT_EUNSUPPORTED; }
-        if (opt.batch < 0) { err = "batch must be >= 0"; return SPARSERT_EINVAL; }
+        if (opt.batch < 0 || opt.batch > 65535) { err = "batch must be in 0..65535"; return SPARSERT_EINVAL; }
         if (((int64_t)opt.Cin * opt.H * opt.W + opt.W + 1) * esz >= (1ll << 27)) {
             err = "conv input too large for 28-bit operand displacements"; return SPARSERT_EUNSUPPORTED;
         }
@@ -117,6 +117,7 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
     h.M = M; h.K = K; h.N = N; h.nnz = row_ptr[M];
     h.dtype = opt.dtype; h.conv = opt.conv ? 1 : 0;
     h.Cin = h.conv ? opt.Cin : 0; h.H = h.conv ? opt.H : 0; h.W = h.conv ? opt.W : 0;
+    h.batch = h.conv ? std::max(1, opt.batch) : 0;
     h.kernel = opt.kernel == SPARSERT_KERNEL_AUTO ? SPARSERT_KERNEL_ROWS : opt.kernel;
     const int esz = h.elem_size();
 

@@ -19,6 +19,7 @@ struct SpecPlan {
     int32_t rows_per_group = 0, n_groups = 0, depth = 0, n_tiles = 0, lanes_per_tile = 0;
     int32_t tiles_per_wg = 4;   // waves per workgroup
     std::string symbol;         // kernel symbol inside the code object
+    int32_t swizzle = 0;        // blocks formed by column-pattern similarity
     int32_t mode = 0;           // sparsert_spec_mode
     int32_t n_blocks = 0;       // code blocks (n_groups, padded to a multiple of the waves in LDS mode)
     int32_t lds_bytes = 0;
@@ -35,6 +36,7 @@ struct HostPlan {
     int32_t vec = 1, lanes_per_tile = 0, n_tiles = 0, gy = kGy;
     int32_t split_threshold = 0, n_split = 0, n_wg_rows = 0;
     int32_t natural_order = 0;         // rows kept in input order (load-balance ablation)
+    int32_t batch = 0;                 // conv: images per call (>= 1); SpMM: 0
 
     std::vector<int32_t> row_nnz, hist, perm, inv_perm, p_row_ptr, p_col_idx;
     std::vector<uint8_t> p_vals;       // nnz * elem_size bytes, bit copies

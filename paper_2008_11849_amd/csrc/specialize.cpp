@@ -182,7 +182,8 @@ constexpr int kSgprOwns = 22;                  // s[22:23] lanes that own a colu
 constexpr int kSgprOffRing = 24, kOffRing = 8; // s[24:31] row-offset literals in flight
 constexpr int kSgprTap0 = 32;                  // conv: s[32:49] = lane masks of the 9 filter taps
 constexpr int kSgprFull = 50;                  // conv: s[50:51] = all lanes
-constexpr int kNextFreeSgpr = 52;
+constexpr int kSgprImage = 52;                 // conv with batch > 1: workgroup id z = image
+constexpr int kNextFreeSgpr = 53;
 constexpr int kVgprOff = 0;                    // byte offset of the lane's column inside a row
 constexpr int kVgprLds = 1;                    // LDS byte address of the lane's 16-byte slot
 constexpr int kVgprT1 = 2, kVgprT2 = 3, kVgprAcc0 = 4;
@@ -504,13 +505,50 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     const int n_blocks = lds ? (G + W - 1) / W * W : G * KS;
     sp.n_blocks = n_blocks;
     sp.group_of_slot.resize(M);
+    sp.swizzle = opt.spec_swizzle && !h.natural_order;
     std::vector<std::vector<int32_t>> members(n_blocks);
-    for (int32_t i = 0; i < M; ++i) {
-        const int32_t round = i / G, pos = i % G;
-        // natural order (ablation): block g is the contiguous row range [g*R, (g+1)*R)
-        const int32_t g = h.natural_order ? i / R : ((round & 1) ? G - 1 - pos : pos);
-        sp.group_of_slot[i] = g;
-        members[g].push_back(i);
+    if (!sp.swizzle) {
+        for (int32_t i = 0; i < M; ++i) {
+            const int32_t round = i / G, pos = i % G;
+            // natural order (ablation): block g is the contiguous row range [g*R, (g+1)*R)
+            const int32_t g = h.natural_order ? i / R : ((round & 1) ? G - 1 - pos : pos);
+            sp.group_of_slot[i] = g;
+            members[g].push_back(i);
+        }
+    } else {
+        // Row swizzle (Section 5, named there as a preprocessing step that would help): rows that share columns go to the
+        // same block, so the block fetches fewer rows of B.  The nnz-descending slots are
+        // handed out in rounds of G, one row per block and round, which keeps the nonzero
+        // counts of the blocks within one row's worth of each other as the serpentine deal
+        // does; inside a round each block, in serpentine direction, takes the candidate that
+        // shares the most columns with what the block already fetches (ties: lowest slot).
+        const int words = (h.K + 63) / 64;
+        std::vector<uint64_t> pattern((size_t)M * words, 0), fetched((size_t)G * words, 0);
+        for (int32_t i = 0; i < M; ++i)
+            for (int32_t p = h.p_row_ptr[i]; p < h.p_row_ptr[i + 1]; ++p)
+                pattern[(size_t)i * words + h.p_col_idx[p] / 64] |= 1ull << (h.p_col_idx[p] % 64);
+        std::vector<char> taken(M, 0);
+        for (int32_t first = 0, round = 0; first < M; first += G, ++round) {
+            const int32_t last = std::min<int32_t>(M, first + G);
+            for (int32_t step = 0; step < last - first; ++step) {
+                const int32_t g = (round & 1) ? G - 1 - step : step;
+                int32_t best = -1;
+                int64_t best_shared = -1;
+                for (int32_t c = first; c < last; ++c) {
+                    if (taken[c]) continue;
+                    int64_t shared = 0;
+                    if (round > 0)
+                        for (int w = 0; w < words; ++w)
+                            shared += __builtin_popcountll(pattern[(size_t)c * words + w] & fetched[(size_t)g * words + w]);
+                    if (shared > best_shared) { best_shared = shared; best = c; }
+                    if (round == 0) break;   // seeding: slot first+step goes to block step
+                }
+                taken[best] = 1;
+                sp.group_of_slot[best] = g;
+                members[g].push_back(best);
+                for (int w = 0; w < words; ++w) fetched[(size_t)g * words + w] |= pattern[(size_t)best * words + w];
+            }
+        }
     }
 
     Gen gen(h, sp);
@@ -566,7 +604,9 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\t.p2align\t8");
     e.line("\t.type\t%s,@function", sym);
     e.line("%s:", sym);
-    // s[0:1] kernarg, s2 = workgroup id x, s3 = workgroup id y, v0 = thread id
+    // s[0:1] kernarg, s2 = workgroup id x, s3 = workgroup id y, (s4 = workgroup id z), v0 = thread id
+    const bool images = h.conv && h.batch > 1;
+    if (images) e.line("\ts_mov_b32 s%d, s4", kSgprImage);   // s4 is about to receive a kernel argument
     e.line("\ts_load_dwordx4 s[%d:%d], s[0:1], 0x0", kSgprB, kSgprC + 1);
     e.line("\tv_lshrrev_b32_e32 v%d, 6, v0", kVgprT1);
     e.line("\tv_and_b32_e32 v%d, 63, v0", kVgprOff);
@@ -647,6 +687,18 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         e.line("\ts_sub_u32 s%d, s%d, %d", kSgprB, kSgprB, (h.W + 1) * 4);
         e.line("\ts_subb_u32 s%d, s%d, 0", kSgprB + 1, kSgprB + 1);
     }
+    if (images) {
+        // image z of the batch: X and Y advance by one image each
+        const int64_t strides[2] = {(int64_t)h.Cin * N * 4, (int64_t)M * N * 4};
+        const int bases[2] = {kSgprB, kSgprC};
+        for (int i = 0; i < 2; ++i) {
+            e.line("\ts_mov_b32 s%d, 0x%llx", kSgprTmp2, (unsigned long long)strides[i]);
+            e.line("\ts_mul_hi_u32 s%d, s%d, s%d", kSgprTmp, kSgprImage, kSgprTmp2);
+            e.line("\ts_mul_i32 s%d, s%d, s%d", kSgprTmp2, kSgprImage, kSgprTmp2);
+            e.line("\ts_add_u32 s%d, s%d, s%d", bases[i], bases[i], kSgprTmp2);
+            e.line("\ts_addc_u32 s%d, s%d, s%d", bases[i] + 1, bases[i] + 1, kSgprTmp);
+        }
+    }
     e.line("\ts_mov_b32 s%d, s%d", kRsrcB, kSgprB);
     e.line("\ts_and_b32 s%d, s%d, 0xffff", kRsrcB + 1, kSgprB + 1);
     e.line("\ts_mov_b32 s%d, 0x%llx", kRsrcB + 2, (unsigned long long)b_bytes);
@@ -699,7 +751,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\t\t.amdhsa_enable_private_segment 0");
     e.line("\t\t.amdhsa_system_sgpr_workgroup_id_x 1");
     e.line("\t\t.amdhsa_system_sgpr_workgroup_id_y 1");
-    e.line("\t\t.amdhsa_system_sgpr_workgroup_id_z 0");
+    e.line("\t\t.amdhsa_system_sgpr_workgroup_id_z %d", images ? 1 : 0);
     e.line("\t\t.amdhsa_system_sgpr_workgroup_info 0");
     e.line("\t\t.amdhsa_system_vgpr_workitem_id 0");
     e.line("\t\t.amdhsa_next_free_vgpr %d", n_vgpr);

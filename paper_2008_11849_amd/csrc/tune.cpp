@@ -46,7 +46,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
     sparsert_options b;
     if (base) b = *base; else std::memset(&b, 0, sizeof(b));
     b.host_only = 0;
-    b.vec = b.split_threshold = b.spec_rows = b.spec_depth = b.spec_tiles = b.spec_mode = b.spec_ksplit = b.spec_lanes = 0;
+    b.vec = b.split_threshold = b.spec_rows = b.spec_depth = b.spec_tiles = b.spec_mode = b.spec_ksplit = b.spec_lanes = b.spec_swizzle = 0;
     // First candidate: the inspector's own choice.  It also validates every argument.
     sparsert_plan *best = nullptr;
     {
@@ -138,6 +138,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
         t.spec_mode = h.spec.mode; t.spec_rows = h.spec.rows_per_group; t.spec_tiles = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.tiles_per_wg : 0;
         t.spec_ksplit = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.ksplit : 0;
         t.spec_lanes = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.lanes_per_tile : 0;
+        t.spec_swizzle = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.swizzle : 0;
         t.microseconds = us;
     };
     log(best, best_us);
@@ -151,6 +152,25 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
             best = p; best_us = us;
         } else {
             sparsert_plan_destroy(p);
+        }
+    }
+    // Last candidate: the winner's configuration with its blocks formed by similarity (row swizzle).
+    if (best_us > 0.0f && best->host.kernel == SPARSERT_KERNEL_SPEC && best->host.spec.rows_per_group > 1 &&
+        !b.natural_order) {
+        const sparsert::SpecPlan &w = best->host.spec;
+        sparsert_options o = b;
+        o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = w.mode; o.spec_rows = w.rows_per_group;
+        o.spec_tiles = w.tiles_per_wg; o.spec_ksplit = w.ksplit; o.spec_swizzle = 1;
+        sparsert_plan *p = nullptr;
+        if (sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &p) == SPARSERT_OK) {
+            const float us = time_plan(p, conv, in_dev, out_dev, s, e0, e1, launches, repeats);
+            log(p, us);
+            if (us > 0.0f && us < best_us) {
+                sparsert_plan_destroy(best);
+                best = p; best_us = us;
+            } else {
+                sparsert_plan_destroy(p);
+            }
         }
     }
     (void)hipEventDestroy(e0);

@@ -24,7 +24,7 @@ SPEC_AUTO, SPEC_DIRECT, SPEC_LDS = 0, 1, 2
 INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", "vec",
               "lanes_per_tile", "n_tiles", "gy", "split_threshold", "n_split", "n_wg_rows",
               "n_bins", "spec_rows", "spec_groups", "spec_depth", "spec_code_bytes",
-              "spec_tiles", "spec_mode", "spec_lds_bytes", "spec_ksplit", "natural_order", "spec_lanes"]
+              "spec_tiles", "spec_mode", "spec_lds_bytes", "spec_ksplit", "natural_order", "spec_lanes", "spec_swizzle", "batch"]
 INFO_COUNT = 32
 
 EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_plan_export",
@@ -39,7 +39,8 @@ class Options(ctypes.Structure):
                 ("spec_rows", ctypes.c_int32), ("spec_depth", ctypes.c_int32),
                 ("spec_tiles", ctypes.c_int32), ("spec_mode", ctypes.c_int32),
                 ("spec_ksplit", ctypes.c_int32), ("natural_order", ctypes.c_int32),
-                ("spec_lanes", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("spec_lanes", ctypes.c_int32), ("spec_swizzle", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
 
 
 TUNE_MAX = 64
@@ -49,7 +50,8 @@ class TuneEntry(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int32), ("vec", ctypes.c_int32), ("split_threshold", ctypes.c_int32),
                 ("spec_mode", ctypes.c_int32), ("spec_rows", ctypes.c_int32),
                 ("spec_tiles", ctypes.c_int32), ("spec_ksplit", ctypes.c_int32),
-                ("spec_lanes", ctypes.c_int32), ("microseconds", ctypes.c_float)]
+                ("spec_lanes", ctypes.c_int32), ("spec_swizzle", ctypes.c_int32),
+                ("microseconds", ctypes.c_float)]
 
 
 class TuneReport(ctypes.Structure):
@@ -152,7 +154,7 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
             vec: int = 0, split_threshold: int = 0, kernel: int = KERNEL_AUTO,
             spec_rows: int = 0, spec_depth: int = 0, spec_tiles: int = 0,
             spec_mode: int = 0, spec_ksplit: int = 0, natural_order: bool = False,
-            spec_lanes: int = 0) -> Plan:
+            spec_lanes: int = 0, spec_swizzle: bool = False) -> Plan:
     """sparsert_inspect.  `vals` must already be float32 or float16; it is not converted."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -169,7 +171,7 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
     opt.vec, opt.split_threshold, opt.batch = vec, split_threshold, batch
     opt.spec_rows, opt.spec_depth, opt.spec_tiles = spec_rows, spec_depth, spec_tiles
     opt.spec_mode, opt.spec_ksplit, opt.natural_order = spec_mode, spec_ksplit, int(natural_order)
-    opt.spec_lanes = spec_lanes
+    opt.spec_lanes, opt.spec_swizzle = spec_lanes, int(spec_swizzle)
     if conv is not None:
         opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
     handle = _vp()
@@ -180,7 +182,8 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
 
 
 def tune(row_ptr, col_idx, vals, M: int, K: int, N: int, in_dev: int, out_dev: int, stream: int = 0, *,
-         conv: Optional[Tuple[int, int, int]] = None, kernel: int = KERNEL_AUTO, natural_order: bool = False):
+         conv: Optional[Tuple[int, int, int]] = None, batch: int = 0, kernel: int = KERNEL_AUTO,
+         natural_order: bool = False):
     """sparsert_tune: returns (best plan, list of timed candidates as dicts).  `kernel` other
     than KERNEL_AUTO restricts the search to that executor family."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
@@ -190,7 +193,7 @@ def tune(row_ptr, col_idx, vals, M: int, K: int, N: int, in_dev: int, out_dev: i
         raise TypeError("vals must be float32 or float16")
     opt = Options()
     opt.dtype = F16 if vals.dtype == np.float16 else F32
-    opt.kernel, opt.natural_order = kernel, int(natural_order)
+    opt.kernel, opt.natural_order, opt.batch = kernel, int(natural_order), batch
     if conv is not None:
         opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
     handle, rep = _vp(), TuneReport()

@@ -111,6 +111,27 @@ def skewed_csr(M, K, sparsity, seed, dtype=np.float32) -> CSR:
     return csr_from_mask(_as_dtype(W, dtype), magnitude_mask(W, sparsity))
 
 
+def clustered_csr(M, K, sparsity, seed, clusters=8, dtype=np.float32) -> CSR:
+    """Rows fall into `clusters` hidden groups, scattered over the matrix by a seeded
+    permutation; a row only uses the K/clusters columns of its group (a second seeded
+    permutation), uniformly at `clusters` times the overall density.  A stand-in for the
+    block structure pruned layers can show (heads, channel groups): rows of one group share
+    their columns, rows of different groups share none - the case a row swizzle is for.
+    """
+    rng = np.random.default_rng(seed)
+    group_of_row = rng.permutation(M) % clusters
+    col_group = rng.permutation(K) % clusters
+    W = rng.standard_normal((M, K))
+    allowed = group_of_row[:, None] == col_group[None, :]
+    nnz = int(round((1.0 - sparsity) * M * K))
+    assert nnz <= int(allowed.sum()), "density x clusters must stay below 1"
+    score = np.where(allowed, rng.random((M, K)), -1.0)
+    keep = np.argsort(-score.reshape(-1), kind="stable")[:nnz]
+    mask = np.zeros(M * K, dtype=bool)
+    mask[keep] = True
+    return csr_from_mask(_as_dtype(W, dtype), mask.reshape(M, K))
+
+
 def small_int_csr(M, K, sparsity, seed, dtype=np.float32, vmax=4) -> CSR:
     """Uniform mask with nonzeros in {-vmax..vmax} minus {0}.
 

@@ -28,11 +28,11 @@ def run_spmm(csr, B, **opts):
 
 def run_conv(csr, X, Cout, **opts):
     dev = torch.device("cuda:0")
-    _, Cin, H, W = X.shape
+    batch, Cin, H, W = X.shape
     plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, Cout, 9 * Cin, H * W,
-                      conv=(Cin, H, W), **opts)
+                      conv=(Cin, H, W), batch=batch, **opts)
     Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
-    Yd = torch.full((1, Cout, H, W), float("nan"), dtype=_tdtype(X.dtype), device=dev)
+    Yd = torch.full((batch, Cout, H, W), float("nan"), dtype=_tdtype(X.dtype), device=dev)
     sp.conv3x3(plan, Xd.data_ptr(), Yd.data_ptr(), torch.cuda.current_stream(dev).cuda_stream)
     torch.cuda.synchronize()
     out = Yd.cpu().numpy()

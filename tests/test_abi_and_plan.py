@@ -203,7 +203,9 @@ def test_validation_errors():
     assert _inspect_rc(rp, ci, v, 2, 3, 8, dtype=7) == sp.EINVAL
     assert _inspect_rc(rp, ci, v, 2, 3, 8, conv=(1, 2, 4)) == sp.EINVAL  # K != 9*Cin
     assert _inspect_rc(rp, ci, v, 2, 9, 8, conv=(1, 2, 4)) == 0
-    assert _inspect_rc(rp, ci, v, 2, 9, 8, conv=(1, 2, 4), batch=2) == sp.EUNSUPPORTED
+    assert _inspect_rc(rp, ci, v, 2, 9, 8, conv=(1, 2, 4), batch=2) == sp.OK
+    assert _inspect_rc(rp, ci, v, 2, 9, 8, conv=(1, 2, 4), batch=70000) == sp.EINVAL
+    assert _inspect_rc(rp, ci, v, 2, 9, 8, conv=(1, 2, 4), batch=-1) == sp.EINVAL
     assert _inspect_rc(rp, ci, v, 2, 9, 7, conv=(1, 2, 4)) == sp.EINVAL  # N != H*W
     assert _inspect_rc(rp, ci, v, 2, 70000, 70000) == sp.EUNSUPPORTED  # >= 2 GiB operands
 
@@ -253,6 +255,31 @@ def test_generated_kernel_plan_assembles_on_the_host(rows, mode):
     # the row-walk plan arrays are unaffected by the choice of executor
     _assert_plan_equal(plan, {**plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, 100, 300, 196),
                               "info": {"M": 100, "nnz": csr.nnz}})
+
+
+@pytest.mark.parametrize("rows", [2, 8, 16, 200])
+def test_row_swizzle_groups_are_bit_exact_and_balanced(rows):
+    M, K = 256, 512
+    csr = synth.clustered_csr(M, K, 0.9, 3, clusters=8)
+    args = (csr.row_ptr, csr.col_idx, csr.vals, M, K, 196)
+    plan = sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_swizzle=True, spec_depth=4)
+    info = plan.info()
+    assert info["spec_swizzle"] == 1
+    groups = plan.export(sp.FIELD_SPEC_GROUPS)
+    prp, pci = plan.export(sp.FIELD_P_ROW_PTR), plan.export(sp.FIELD_P_COL_IDX)
+    assert groups.tobytes() == plan_ref.spec_groups_swizzled(prp, pci, M, K, rows).tobytes()
+    assert np.bincount(groups).max() <= rows
+    nn = np.diff(prp)
+    per_block = np.bincount(groups, weights=nn)
+    assert per_block.max() - per_block.min() <= nn.max()          # same balance bound as the serpentine deal
+    plain = sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_depth=4)
+    fetched = lambda p: int(p.export(sp.FIELD_SPEC_COLUMNS)[:p.info()["spec_groups"]].sum())
+    if rows in (8, 16):   # eight hidden clusters: a swizzled block fetches far fewer rows of B
+        assert fetched(plan) < 0.65 * fetched(plain), (fetched(plan), fetched(plain))
+    else:
+        assert fetched(plan) <= fetched(plain)
+    plan.destroy()
+    plain.destroy()
 
 
 def test_generated_kernel_ksplit_lds_budget():

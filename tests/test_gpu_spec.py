@@ -166,6 +166,60 @@ def test_spec_narrow_tiles_config_and_conv():
         check(got, Yref, S, np.float32)
 
 
+@pytest.mark.parametrize("opts", [dict(spec_rows=8), dict(spec_rows=16, spec_ksplit=4),
+                                  dict(spec_rows=12, spec_tiles=4, spec_mode=sp.SPEC_LDS)])
+def test_row_swizzle_results(opts):
+    csr = synth.clustered_csr(256, 512, 0.9, 3, clusters=8)
+    B = synth.normal_dense(512, 196, 4)
+    got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_swizzle=True, **opts)
+    assert info["spec_swizzle"] == 1
+    Cref, S = _oracle(csr, B)
+    check(got, Cref, S, np.float32)
+    csr = synth.small_int_csr(77, 130, 0.85, 21)
+    B = synth.small_int_dense(130, 65, 22)
+    got, _ = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_swizzle=True, **opts)
+    assert np.array_equal(got.astype(np.float64), _oracle(csr, B)[0])
+
+
+def test_row_swizzle_conv():
+    csr, Wd = synth.conv_weights_csr(24, 16, 0.8, 5)
+    X = synth.normal_dense(16, 14 * 14, 6).reshape(1, 16, 14, 14)
+    Yref, S = ref.conv3x3(Wd, X)
+    got, info = run_conv(csr, X, 24, kernel=sp.KERNEL_SPEC, spec_rows=4, spec_swizzle=True)
+    assert info["spec_swizzle"] == 1
+    check(got, Yref, S, np.float32)
+
+
+@pytest.mark.parametrize("batch", [2, 3, 8])
+def test_conv_batch_generated_and_row_walk(batch):
+    """Images of a batch are independent convolutions with the same filters (grid z / grid y)."""
+    Cin, Cout, H, W = 16, 24, 9, 13
+    csr, Wd = synth.conv_weights_csr(Cout, Cin, 0.8, 5)
+    X = synth.normal_dense(batch * Cin, H * W, 6).reshape(batch, Cin, H, W)
+    Yref, S = ref.conv3x3(Wd, X)
+    for opts in (dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=3), dict(kernel=sp.KERNEL_SPEC, spec_rows=6, spec_ksplit=4)):
+        got, info = run_conv(csr, X, Cout, **opts)
+        assert info["batch"] == batch and got.shape == (batch, Cout, H, W)
+        check(got, Yref, S, np.float32)
+    # half storage, row-walk kernel
+    csr16, W16 = synth.conv_weights_csr(Cout, Cin, 0.8, 5, dtype=np.float16)
+    X16 = X.astype(np.float16)
+    Yref, S = ref.conv3x3(W16, X16)
+    got, _ = run_conv(csr16, X16, Cout)
+    check(got, Yref, S, np.float16)
+    # small integers: every image bit-exact, and image i equals the batch-1 result of image i
+    Wi = np.zeros((Cout, Cin, 3, 3), dtype=np.float32)
+    ci = synth.small_int_csr(Cout, 9 * Cin, 0.8, 11)
+    Wi.reshape(Cout, -1)[np.repeat(np.arange(Cout), np.diff(ci.row_ptr)), ci.col_idx] = ci.vals
+    Xi = synth.small_int_dense(batch * Cin, H * W, 12).reshape(batch, Cin, H, W)
+    Yi, _ = ref.conv3x3(Wi, Xi)
+    for opts in (dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=5)):
+        got, _ = run_conv(ci, Xi, Cout, **opts)
+        assert np.array_equal(got.astype(np.float64), Yi)
+        one, _ = run_conv(ci, Xi[batch - 1:batch], Cout, **opts)
+        assert np.array_equal(one[0], got[batch - 1])
+
+
 NATURAL = [dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=9), dict(kernel=sp.KERNEL_SPEC, spec_rows=12, spec_mode=sp.SPEC_LDS),
            dict(kernel=sp.KERNEL_SPEC, spec_rows=20, spec_ksplit=4)]
 
