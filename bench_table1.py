@@ -65,6 +65,7 @@ def geomean(xs):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--only", default="", help="comma list of problem tags to run, e.g. t1_p9_90,t3_p3_95")
+    ap.add_argument("--markdown", default="", help="also write the results as a markdown summary to this path")
     ap.add_argument("--ablation", action="store_true",
                     help="also time, per problem, the best row-walk (not specialised) plan and the best plan "
                          "without load balancing (rows in input order): the paper's two ablations (Section 4.3)")
@@ -159,22 +160,78 @@ def main():
             rows.append(r)
             print(json.dumps(r), file=sys.stderr, flush=True)
 
+    if args.ablation:
+        # the suite's weights are uniform; two skewed matrices (Zipf-like row lengths) show what the
+        # load balancing is for
+        for i, (M, K, N) in enumerate([(1024, 1024, 256), (3072, 768, 1024)]):
+            tag = f"skew_p{i + 1}_95"
+            if only and tag not in only:
+                continue
+            csr = synth.skewed_csr(M, K, 0.95, synth.BASE_SEED + 9000 + i)
+            B = torch.from_numpy(synth.normal_dense(K, N, synth.BASE_SEED + 9100 + i)).to(dev)
+            C = torch.empty((M, N), device=dev)
+            Ad = torch.from_numpy(csr.todense(np.float32)).to(dev)
+            r = run(tag, csr, N, B, C, lambda: torch.matmul(Ad, B))
+            r.update(M=M, K=K, N=N, sparsity=0.95, paper_speedup_t4="-", skewed=True)
+            rows.append(r)
+            print(json.dumps(r), file=sys.stderr, flush=True)
+
     def gm(prefix, s):
         return geomean([r["speedup"] for r in rows if r["tag"].startswith(prefix) and r["sparsity"] == s])
 
     ablation = None
     if args.ablation:
-        ablation = {"specialised_over_row_walk": geomean([r["rows_only_us"] / r["sparse_us"] for r in rows]),
-                    "balanced_over_natural_order": geomean([r["natural_order_us"] / r["sparse_us"] for r in rows]),
+        suite = [r for r in rows if not r.get("skewed")]
+        skew = [r for r in rows if r.get("skewed")]
+        ablation = {"specialised_over_row_walk": geomean([r["rows_only_us"] / r["sparse_us"] for r in suite]),
+                    "balanced_over_natural_order": geomean([r["natural_order_us"] / r["sparse_us"] for r in suite]),
+                    "balanced_over_natural_order_skewed": geomean([r["natural_order_us"] / r["sparse_us"] for r in skew]),
                     "paper": "unrolled code > 10x over rolled loops; load balancing up to 2x (Section 4.3)"}
-    print(json.dumps({
+    result = {
         "workload": "paper Table 1 (SpMM) and Table 3 (3x3 conv) shapes, synthetic magnitude-pruned weights, fp32",
         "timing": f"{INNER} launches per HIP graph, 20 replays, HIP events; same for sparse and dense",
         "geomean_speedup_vs_dense": {"table1_90": gm("t1", 0.90), "table1_95": gm("t1", 0.95),
                                      "table3_90": gm("t3", 0.90), "table3_95": gm("t3", 0.95)},
         "paper_geomean_t4": {"table1_90": 3.4, "table1_95": 5.4},
         "ablation_geomean_speedup": ablation,
-        "problems": rows}))
+        "problems": rows}
+    print(json.dumps(result))
+    if args.markdown:
+        write_markdown(args.markdown, result, " ".join(["python3", "bench_table1.py"] + sys.argv[1:]))
+
+
+def write_markdown(path, res, command):
+    g = res["geomean_speedup_vs_dense"]
+    fmt = lambda x: "-" if x is None else f"{x:.2f}x"
+    lines = ["# Paper's problem list (Table 1 SpMM, Table 3 3x3 conv) on MI355X, synthetic weights, fp32", "",
+             f"command: `{command}` (one MI355X; plans from sparsert_tune; sparse and dense both timed as",
+             f"{INNER} launches per HIP graph, 20 replays, HIP events).", "",
+             "Geometric-mean speedup over the dense fp32 baseline (torch.matmul / conv2d) on the same GPU:", "",
+             "| set | this build, MI355X | paper, Tesla T4 (context) |", "|---|---|---|",
+             f"| Table 1, 90 % (20 problems) | {fmt(g['table1_90'])} | 3.4x |",
+             f"| Table 1, 95 % (problems 1-11) | {fmt(g['table1_95'])} | 5.4x |",
+             f"| Table 3, 90 % (4 convs) | {fmt(g['table3_90'])} | 1.4-3.7x |",
+             f"| Table 3, 95 % (4 convs) | {fmt(g['table3_95'])} | 2.5-8.5x |", ""]
+    abl = res.get("ablation_geomean_speedup")
+    if abl:
+        lines += ["Ablations (Section 4.3), geometric mean over all problems of time(ablated) / time(tuned):",
+                  f"best row-walk plan (no per-matrix code) {abl['specialised_over_row_walk']:.2f}x slower;",
+                  f"best plan with rows in input order (no load balancing) {abl['balanced_over_natural_order']:.2f}x slower",
+                  "(the magnitude-pruned synthetic weights are uniform, as the paper says of its own);",
+                  f"on the two skewed matrices (skew_*) input order is {fmt(abl.get('balanced_over_natural_order_skewed'))} slower.", ""]
+    lines += ["Most SpMM problems finish in 2.5-3.3 us on the sparse path, about the floor of one kernel node in a",
+              "graph on this machine; the dense kernels take 4.2-9.5 us.  kernel: 1 = row-walk, 2 = generated;",
+              "R = rows per code block, KS = K split, W = waves per workgroup.", "",
+              "| problem | shape | sparse us | dense us | speedup | paper (T4) | kernel | R | KS | W | row-walk us | input-order us |",
+              "|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    for r in res["problems"]:
+        shape = (f"{r['M']}x{r['K']}x{r['N']}" if "M" in r else f"conv {r['Cin']}->{r['Cout']} @ {r['image']}x{r['image']}")
+        p = r["plan"]
+        lines.append(f"| {r['tag']} | {shape} | {r['sparse_us']:.2f} | {r['dense_us']:.2f} | {r['speedup']:.2f} | "
+                     f"{r['paper_speedup_t4']} | {p['kernel']} | {p['spec_rows']} | {p['spec_ksplit']} | {p['spec_tiles']} | "
+                     f"{r.get('rows_only_us', '-')} | {r.get('natural_order_us', '-')} |")
+    with open(path, "w") as f:
+        f.write("\n".join(lines) + "\n")
 
 
 if __name__ == "__main__":
