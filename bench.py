@@ -51,7 +51,8 @@ def parse_args():
 class Layer:
     """One sparse layer resident on the GPU: plan, input, output and its dense twin."""
 
-    PLAN_KEYS = ("kernel", "vec", "split_threshold", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit")
+    PLAN_KEYS = ("kernel", "vec", "split_threshold", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit",
+                 "spec_swizzle")
 
     def __init__(self, case, torch, sp, kernel="tune", fixed=None):
         import numpy as np
@@ -133,9 +134,11 @@ def load_traffic(kernel_tag):
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline(cases):
+def cpu_baseline(cases, gpu_outputs):
     """The CPU oracle as it stands, on the host cores, on the same workload: whole steps are
-    repeated for about 10 s of wall time and the mean pass is reported."""
+    repeated for about 10 s of wall time and the mean pass is reported.  The oracle's result
+    is also held against what the timed plans left in their output buffers (every element);
+    a mismatch beyond the storage type's tolerance ends the run with an error."""
     from oracle import ref
     threads = min(ref.max_threads(), len(os.sched_getaffinity(0)))
     flops = sum(2.0 * c.csr.nnz * c.N for c in cases)
@@ -155,7 +158,21 @@ def cpu_baseline(cases):
         one_pass()
         passes += 1
     per_pass = (time.perf_counter() - t0) / passes
+    worst = 0.0
+    for case, got in zip(cases, gpu_outputs):
+        csr = case.csr
+        if case.conv is not None:
+            want, scale = ref.conv3x3(case.Wdense, case.X, threads=threads)
+        else:
+            want, scale = ref.spmm(csr.M, csr.K, case.N, csr.row_ptr, csr.col_idx, csr.vals, case.B, threads=threads)
+        m = ref.error_metrics(got.reshape(want.shape), want, scale)
+        tol = 2e-2 if got.dtype.itemsize == 2 else 1e-4
+        if not (m["componentwise"] <= tol and m["normwise"] <= tol and m["exact_on_zero_scale"]):
+            print(f"bench.py: the timed plan of {case.name} disagrees with the oracle: {m}", file=sys.stderr)
+            sys.exit(1)
+        worst = max(worst, m["componentwise"])
     return {"value": flops / per_pass / 1e9, "unit": "GFLOP/s", "cores": threads, "kind": "oracle",
+            "parity_max_componentwise_error": worst,
             "sample": "every layer of the step, all rows, float64 oracle with OpenMP over rows; "
                       "%d passes in %.1f s, %.4f s per pass" % (passes, per_pass * passes, per_pass)}
 
@@ -229,7 +246,8 @@ def main():
                           "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
                           "dense_us": ms_dense * 1e3, "speedup_vs_dense": ms_dense / ms,
                           "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
-                                                          "spec_tiles", "spec_ksplit", "spec_code_bytes")},
+                                                          "spec_tiles", "spec_ksplit", "spec_swizzle",
+                                                          "spec_code_bytes")},
                           "tuned_candidates": len(L.tuned) if L.tuned else 0})
     kernel_ms = sum(p["us"] for p in per_layer) / 1e3 / len(layers)       # average launch
     alg_bytes = sum(L.algorithmic_bytes for L in layers) / len(layers)    # average launch
@@ -275,12 +293,12 @@ def main():
             side.append({"layer": n, "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
                          "dense_us": msd * 1e3, "speedup_vs_dense": msd / ms,
                          "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
-                                                         "spec_tiles", "spec_ksplit")}})
+                                                         "spec_tiles", "spec_ksplit", "spec_swizzle")}})
             L.plan.destroy()
         out["other_configs"] = side
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cases)
+        out["cpu_baseline"] = cpu_baseline(cases, [L.out.cpu().numpy() for L in layers])
     print(json.dumps(out))
 
 

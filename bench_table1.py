@@ -127,7 +127,7 @@ def main():
         return {"tag": tag, "sparse_us": round(t_sparse, 3), "dense_us": round(t_dense, 3),
                 "speedup": round(t_dense / t_sparse, 3), "dense_timing": dense_how,
                 "gflops": round(2.0 * csr.nnz * N / t_sparse / 1e3, 1),
-                "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit")},
+                "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit", "spec_swizzle")},
                 **extra}
 
     for sparsity in (0.90, 0.95):

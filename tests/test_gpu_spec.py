@@ -128,6 +128,19 @@ def test_spec_ksplit_largest_block():
         run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=200, spec_ksplit=8)
 
 
+@pytest.mark.parametrize("name,opts", [("c3", dict(spec_rows=96, spec_ksplit=4)),
+                                       ("c3", dict(spec_rows=96, spec_ksplit=4, spec_swizzle=True)),
+                                       ("c3t", dict(spec_rows=48, spec_ksplit=8)),
+                                       ("c3t", dict(spec_rows=48, spec_ksplit=8, spec_swizzle=True))])
+def test_headline_layers_in_the_plans_the_tuner_picks(name, opts):
+    """Full-size c3 / c3t in the launch configurations the benchmark ends up timing."""
+    case = synth.config(name)
+    got, info = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, **opts)
+    assert info["spec_ksplit"] == opts["spec_ksplit"] and info["spec_rows"] == opts["spec_rows"]
+    Cref, S = _oracle(case.csr, case.B)
+    check(got, Cref, S, np.float32, gate_relative=True)
+
+
 def test_spec_ksplit_configs_and_skew():
     for name in ("c2", "c3t"):
         case = synth.config(name)
