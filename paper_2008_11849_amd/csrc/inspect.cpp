@@ -15,23 +15,6 @@ static inline int bin_of(int32_t x) {
     return b;  // 0 for x == 0, else 1 + floor(log2 x)
 }
 
-// IEEE binary16 -> binary32, exact for every input (subnormals, inf, NaN payload kept).
-static inline uint32_t half_bits_to_float_bits(uint16_t h) {
-    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
-    uint32_t exp = (h >> 10) & 0x1fu;
-    uint32_t man = h & 0x3ffu;
-    if (exp == 0x1fu) return sign | 0x7f800000u | (man << 13);
-    if (exp == 0) {
-        if (man == 0) return sign;
-        int shift = 0;
-        while (!(man & 0x400u)) { man <<= 1; ++shift; }
-        man &= 0x3ffu;
-        exp = 1 - shift;
-        return sign | ((exp + 112u) << 23) | (man << 13);
-    }
-    return sign | ((exp + 112u) << 23) | (man << 13);
-}
-
 static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
                     int32_t M, int32_t K, int32_t N, const sparsert_options &opt,
                     std::string &err) {

@@ -322,7 +322,7 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
 int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
                 void *stream, std::string &err) {
     const SpecPlan &sp = h.spec;
-    if (!d.spec_function || sp.n_groups < 1 || sp.n_tiles < 1 || h.dtype != SPARSERT_F32) {
+    if (!d.spec_function || sp.n_groups < 1 || sp.n_tiles < 1) {
         err = "plan has no generated kernel";
         return SPARSERT_EINVAL;
     }

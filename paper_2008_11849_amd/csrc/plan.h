@@ -15,6 +15,23 @@ constexpr int kBins = 33;       // bin(0)=0, bin(x)=1+floor(log2 x), x < 2^31
 constexpr int kFullTasks = 2048;  // wave tasks wanted before widening per-lane vectors
 
 // Per-matrix generated kernel (kernel == SPARSERT_KERNEL_SPEC).
+// IEEE binary16 -> binary32, exact for every input (subnormals, inf, NaN payload kept).
+inline uint32_t half_bits_to_float_bits(uint16_t h) {
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t exp = (h >> 10) & 0x1fu;
+    uint32_t man = h & 0x3ffu;
+    if (exp == 0x1fu) return sign | 0x7f800000u | (man << 13);
+    if (exp == 0) {
+        if (man == 0) return sign;
+        int shift = 0;
+        while (!(man & 0x400u)) { man <<= 1; ++shift; }
+        man &= 0x3ffu;
+        exp = 1 - shift;
+        return sign | ((exp + 112u) << 23) | (man << 13);
+    }
+    return sign | ((exp + 112u) << 23) | (man << 13);
+}
+
 struct SpecPlan {
     int32_t rows_per_group = 0, n_groups = 0, depth = 0, n_tiles = 0, lanes_per_tile = 0;
     int32_t tiles_per_wg = 4;   // waves per workgroup

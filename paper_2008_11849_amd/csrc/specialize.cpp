@@ -183,7 +183,8 @@ constexpr int kSgprOffRing = 24, kOffRing = 8; // s[24:31] row-offset literals i
 constexpr int kSgprTap0 = 32;                  // conv: s[32:49] = lane masks of the 9 filter taps
 constexpr int kSgprFull = 50;                  // conv: s[50:51] = all lanes
 constexpr int kSgprImage = 52;                 // conv with batch > 1: workgroup id z = image
-constexpr int kNextFreeSgpr = 53;
+constexpr int kSgprValRing = 54, kValRing = 8; // half plans: s[54:61] values of A on their way into v_fma_mix_f32
+constexpr int kNextFreeSgpr = 62;
 constexpr int kVgprOff = 0;                    // byte offset of the lane's column inside a row
 constexpr int kVgprLds = 1;                    // LDS byte address of the lane's 16-byte slot
 constexpr int kVgprT1 = 2, kVgprT2 = 3, kVgprAcc0 = 4;
@@ -199,24 +200,39 @@ struct Gen {
     const HostPlan &h;
     SpecPlan &sp;
     int N, K, D;
+    bool half = false;   // B, C and the values of A are IEEE half; sums stay fp32
+    int esz = 4;
+    int val_pos = 0;     // half plans: next slot of the value ring
     int vgpr_stage0 = 0, vgpr_ring0 = 0, n_vgpr = 0, lds_bytes = 0;
     int ring_size = 0;               // DIRECT: registers of the operand ring (>= D)
     int slot_bytes = 256;            // K split: bytes of one row's partial sums in the exchange area
     int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
-    Gen(const HostPlan &hp, SpecPlan &s) : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth) {}
+    Gen(const HostPlan &hp, SpecPlan &s)
+        : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth), half(hp.dtype == SPARSERT_F16), esz(half ? 2 : 4) {}
 
     void zero_accs(size_t n) {
         for (size_t i = 0; i < n; ++i) e.line("\tv_mov_b32_e32 v%d, 0", kVgprAcc0 + (int)i);
     }
+    // fp32: the value of A is a literal of the multiply-add.  Half storage: the operand sits in
+    // the low half of vb and v_fma_mix_f32 widens it on the fly (exact), multiplies by the
+    // value - widened to fp32 at generation time, exact as well, and moved through a scalar
+    // register because this encoding takes no literal - and accumulates in fp32.
     void fmas(const std::vector<Term> &terms, int vb) {
         for (const Term &t : terms) {
-            e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vb);
+            if (!half) {
+                e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vb);
+            } else {
+                const int sv = kSgprValRing + (val_pos++ % kValRing);
+                e.line("\ts_mov_b32 s%d, 0x%08x", sv, t.bits);
+                e.line("\tv_fma_mix_f32 v%d, s%d, v%d, v%d op_sel_hi:[0,1,0]", kVgprAcc0 + t.acc, sv, vb, kVgprAcc0 + t.acc);
+            }
         }
     }
+    const char *load_op() const { return half ? "buffer_load_short_d16" : "buffer_load_dword"; }
     void load_b_row(int k, int vdst, int ring_pos) {
         const int sreg = kSgprOffRing + (ring_pos % kOffRing);
-        e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)k * N * 4));
-        e.line("\tbuffer_load_dword v%d, v%d, s[%d:%d], s%d offen", vdst, kVgprOff, kRsrcB, kRsrcB + 3, sreg);
+        e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)k * N * esz));
+        e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", load_op(), vdst, kVgprOff, kRsrcB, kRsrcB + 3, sreg);
     }
     // (slot of the permuted CSR, accumulator register) pairs: one row of C each
     void stores(const std::vector<std::pair<int32_t, int>> &rows) {
@@ -224,9 +240,11 @@ struct Gen {
         e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
         for (size_t i = 0; i < rows.size(); ++i) {
             const int sreg = kSgprOffRing + ((int)i % kOffRing);
-            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i].first] * N * 4));
-            e.line("\tbuffer_store_dword v%d, v%d, s[%d:%d], s%d offen", rows[i].second, kVgprOff,
-                   kRsrcC, kRsrcC + 3, sreg);
+            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i].first] * N * esz));
+            // half storage: one rounding to nearest even, at the store
+            if (half) e.line("\tv_cvt_f16_f32_e32 v%d, v%d", rows[i].second, rows[i].second);
+            e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", half ? "buffer_store_short" : "buffer_store_dword",
+                   rows[i].second, kVgprOff, kRsrcC, kRsrcC + 3, sreg);
         }
     }
 
@@ -236,8 +254,14 @@ struct Gen {
         for (size_t i = 0; i < rows.size(); ++i) {
             const int32_t slot = rows[i];
             for (int32_t p = h.p_row_ptr[slot]; p < h.p_row_ptr[slot + 1]; ++p) {
-                uint32_t bits;  // fp32 plans only: the value as stored (the conv stream is reordered, p_vals is not)
-                std::memcpy(&bits, &h.p_vals[(size_t)p * 4], 4);
+                uint32_t bits;  // the value as stored (the conv stream is reordered, p_vals is not), as fp32
+                if (half) {
+                    uint16_t hb;
+                    std::memcpy(&hb, &h.p_vals[(size_t)p * 2], 2);
+                    bits = half_bits_to_float_bits(hb);
+                } else {
+                    std::memcpy(&bits, &h.p_vals[(size_t)p * 4], 4);
+                }
                 cols[h.p_col_idx[p]].push_back({(int)i, bits});
             }
         }
@@ -249,8 +273,8 @@ struct Gen {
     void load_x_row(int k, int vdst, int ring_pos) {
         const int c = k / 9, tap = k % 9, r = tap / 3, t = tap % 3;
         const int sreg = kSgprOffRing + (ring_pos % kOffRing);
-        e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)(((int64_t)c * h.H * h.W + r * h.W + t) * 4));
-        e.line("\tbuffer_load_dword v%d, v%d, s[%d:%d], s%d offen", vdst, kVgprOff, kRsrcB, kRsrcB + 3, sreg);
+        e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)(((int64_t)c * h.H * h.W + r * h.W + t) * esz));
+        e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", load_op(), vdst, kVgprOff, kRsrcB, kRsrcB + 3, sreg);
     }
     int cur_mask = -1;  // conv: tap whose lane mask is in exec; -1 = all lanes
     void want_mask(int tap) {
@@ -464,7 +488,12 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         err = "convolution plans use the DIRECT variant of the generated kernel";
         return SPARSERT_EUNSUPPORTED;
     }
-    if (h.dtype != SPARSERT_F32) { err = "the specialised executor is fp32 only"; return SPARSERT_EUNSUPPORTED; }
+    const bool half = h.dtype == SPARSERT_F16;
+    const int esz = half ? 2 : 4;
+    if (half && opt.spec_mode == SPARSERT_SPEC_LDS) {
+        err = "half-precision plans use the DIRECT variant of the generated kernel";
+        return SPARSERT_EUNSUPPORTED;
+    }
     const int32_t M = h.M, N = h.N;
     sp.mode = opt.spec_mode ? opt.spec_mode : SPARSERT_SPEC_DIRECT;
     const bool lds = sp.mode == SPARSERT_SPEC_LDS;
@@ -553,8 +582,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
 
     Gen gen(h, sp);
     Emitter &e = gen.e;
-    const int64_t b_bytes = h.conv ? ((int64_t)h.Cin * N + 2 * (h.W + 1)) * 4 : (int64_t)h.K * N * 4;
-    const int64_t c_bytes = (int64_t)M * N * 4;
+    const int64_t b_bytes = h.conv ? ((int64_t)h.Cin * N + 2 * (h.W + 1)) * esz : (int64_t)h.K * N * esz;
+    const int64_t c_bytes = (int64_t)M * N * esz;
     // conv: pixel -> (oh, ow) by multiplication with ceil(2^32 / W); verified here for every pixel
     uint32_t magic = 0;
     if (h.conv && h.W > 1) {
@@ -597,7 +626,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\t.text");
     // The symbol carries the problem shape so that kernel traces tell the plans of a model apart.
     char sym[96];
-    snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N);
+    snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d%s", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N, half ? "_f16" : "");
     sp.symbol = sym;
     e.line("\t.protected\t%s", sym);
     e.line("\t.globl\t%s", sym);
@@ -645,7 +674,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\ts_nop 4");
     // lanes without a column redo the tile's first column: loads stay in bounds, nothing is stored
     e.line("\tv_cndmask_b32_e64 v%d, v%d, v%d, s[%d:%d]", kVgprT1, kVgprT2, kVgprT1, kSgprOwns, kSgprOwns + 1);
-    e.line("\tv_lshlrev_b32_e32 v%d, 2, v%d", kVgprOff, kVgprT1);  // byte offset of the column inside a row
+    e.line("\tv_lshlrev_b32_e32 v%d, %d, v%d", kVgprOff, half ? 1 : 2, kVgprT1);  // byte offset of the column inside a row
     // from here on only lanes that own a column are active: idle lanes fetch nothing
     e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
     if (h.conv) {
@@ -684,12 +713,12 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     if (h.conv) {
         // operand descriptor starts W+1 elements before X so that every tap displacement is
         // non-negative; lanes that would read before X are always masked off for that tap
-        e.line("\ts_sub_u32 s%d, s%d, %d", kSgprB, kSgprB, (h.W + 1) * 4);
+        e.line("\ts_sub_u32 s%d, s%d, %d", kSgprB, kSgprB, (h.W + 1) * esz);
         e.line("\ts_subb_u32 s%d, s%d, 0", kSgprB + 1, kSgprB + 1);
     }
     if (images) {
         // image z of the batch: X and Y advance by one image each
-        const int64_t strides[2] = {(int64_t)h.Cin * N * 4, (int64_t)M * N * 4};
+        const int64_t strides[2] = {(int64_t)h.Cin * N * esz, (int64_t)M * N * esz};
         const int bases[2] = {kSgprB, kSgprC};
         for (int i = 0; i < 2; ++i) {
             e.line("\ts_mov_b32 s%d, 0x%llx", kSgprTmp2, (unsigned long long)strides[i]);

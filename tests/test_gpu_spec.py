@@ -233,6 +233,68 @@ def test_conv_batch_generated_and_row_walk(batch):
         assert np.array_equal(one[0], got[batch - 1])
 
 
+HALF_OPTS = [dict(spec_rows=1), dict(spec_rows=7), dict(spec_rows=20, spec_ksplit=4), dict(spec_rows=9, spec_swizzle=True),
+             dict(spec_rows=50, spec_ksplit=8, spec_depth=3)]
+
+
+@pytest.mark.parametrize("N", [1, 8, 65, 200, 520])
+def test_spec_half_small_integers_bit_exact(N):
+    """Half storage in the generated kernel: sums in fp32, exact on small integers in any order."""
+    csr = synth.small_int_csr(50, 90, 0.9, N, dtype=np.float16, vmax=3)
+    B = synth.small_int_dense(90, N, N + 1, dtype=np.float16, bmax=4)
+    Cref, _ = _oracle(csr, B)
+    assert np.abs(Cref).max() <= 2048
+    for opts in HALF_OPTS:
+        got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, **opts)
+        assert info["kernel"] == sp.KERNEL_SPEC and info["dtype"] == sp.F16 and got.dtype == np.float16
+        assert np.array_equal(got.astype(np.float64), Cref), (N, opts)
+
+
+def test_spec_half_rounds_once_at_the_store():
+    """fp32 accumulation, one rounding to nearest even: identity returns B bit for bit; rows of
+    2049 and 2051 ones times a column of ones sum exactly in fp32 and round to the even
+    neighbours 2048 and 2052 (a half-precision running sum would stall at 2048)."""
+    K, N = 130, 70
+    B = synth.normal_dense(K, N, 3, dtype=np.float16)
+    eye = synth.csr_from_mask(np.eye(K, dtype=np.float16), np.eye(K, dtype=bool))
+    got, _ = run_spmm(eye, B, kernel=sp.KERNEL_SPEC, spec_rows=5)
+    assert got.tobytes() == B.tobytes()
+    mask = np.ones((2, 2051), dtype=bool)
+    mask[0, 2049:] = False
+    ones = synth.csr_from_mask(np.ones((2, 2051), dtype=np.float16), mask)
+    Bx = np.ones((2051, 66), dtype=np.float16)
+    Bx[:, 1] = 2.0 ** -14
+    want = _oracle(ones, Bx)[0].astype(np.float16)
+    assert want[0, 0] == 2048 and want[1, 0] == 2052
+    for opts in (dict(spec_rows=2), dict(spec_rows=2, spec_ksplit=8), dict(kernel=sp.KERNEL_ROWS)):
+        got, _ = run_spmm(ones, Bx, **{"kernel": sp.KERNEL_SPEC, **opts})
+        assert got.tobytes() == want.tobytes(), opts
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3t"])
+def test_spec_half_configs(name):
+    case = synth.config(name, np.float16)
+    opts = dict(spec_rows=48, spec_ksplit=8) if name == "c3t" else dict(spec_rows=4)
+    got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, **opts)
+    Cref, S = _oracle(case.csr, case.B)
+    check(got, Cref, S, np.float16, gate_relative=True)
+
+
+def test_spec_half_skewed_and_conv():
+    case = synth.sweep_case(256, 512, 196, 0.95, "skewed", np.float16)
+    got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_rows=16, spec_ksplit=4)
+    Cref, S = _oracle(case.csr, case.B)
+    check(got, Cref, S, np.float16)
+    for (Cin, Cout, H, W, batch) in ((16, 24, 14, 14, 1), (5, 7, 9, 13, 3), (3, 4, 1, 9, 2)):
+        csr, Wd = synth.conv_weights_csr(Cout, Cin, 0.8, 5, dtype=np.float16)
+        X = synth.normal_dense(batch * Cin, H * W, 6, dtype=np.float16).reshape(batch, Cin, H, W)
+        Yref, S = ref.conv3x3(Wd, X)
+        for opts in (dict(spec_rows=3), dict(spec_rows=4, spec_ksplit=2)):
+            got, info = run_conv(csr, X, Cout, kernel=sp.KERNEL_SPEC, **opts)
+            assert info["dtype"] == sp.F16
+            check(got, Yref, S, np.float16)
+
+
 NATURAL = [dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=9), dict(kernel=sp.KERNEL_SPEC, spec_rows=12, spec_mode=sp.SPEC_LDS),
            dict(kernel=sp.KERNEL_SPEC, spec_rows=20, spec_ksplit=4)]
 
@@ -304,7 +366,8 @@ def test_spec_conv_integer_taps_bit_exact():
 def test_spec_rejects_what_it_does_not_cover():
     csr = synth.uniform_csr(16, 18, 0.5, 1, dtype=np.float16)
     with pytest.raises(sp.SparseRTError) as e:
-        sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 16, 18, 8, kernel=sp.KERNEL_SPEC, host_only=True)
+        sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 16, 18, 8, kernel=sp.KERNEL_SPEC, host_only=True,
+                   spec_mode=sp.SPEC_LDS)
     assert e.value.status == sp.EUNSUPPORTED
 
 
