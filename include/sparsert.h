@@ -81,8 +81,9 @@ typedef struct sparsert_options {
     int32_t spec_mode;       /* sparsert_spec_mode; 0 = automatic */
     int32_t spec_ksplit;     /* SPARSERT_KERNEL_SPEC, DIRECT: 2, 4 or 8 waves of a workgroup share one
                                 code block's rows and column tile and split its columns (equal
-                                nonzero shares, partial sums meet in LDS); 0/1 = no split.  Sets
-                                the workgroup width, spec_tiles is then ignored */
+                                nonzero shares, partial sums meet in LDS, in several phases if
+                                they exceed it); 0/1 = no split.  Sets the workgroup width,
+                                spec_tiles is then ignored */
     int32_t natural_order;   /* 1: load-balance ablation (Section 4.3): rows keep their input order
                                 (identity permutation), no row is split over waves, and the
                                 generated kernel's blocks are contiguous row ranges; 0 = balanced */

@@ -206,6 +206,7 @@ struct Gen {
     int vgpr_stage0 = 0, vgpr_ring0 = 0, n_vgpr = 0, lds_bytes = 0;
     int ring_size = 0;               // DIRECT: registers of the operand ring (>= D)
     int slot_bytes = 256;            // K split: bytes of one row's partial sums in the exchange area
+    int xchg_rows = 0;               // K split: rows exchanged per phase (all of them if they fit the LDS)
     int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
     Gen(const HostPlan &hp, SpecPlan &s)
         : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth), half(hp.dtype == SPARSERT_F16), esz(half ? 2 : 4) {}
@@ -330,43 +331,51 @@ struct Gen {
             if (h.conv) want_mask(-1);
             // Row i of the block belongs to wave i % parts.  Every wave leaves its partial sums of
             // the rows it does not own in LDS, and after one barrier adds the other waves'
-            // partials to its own rows in ascending wave order, then stores those rows.
+            // partials to its own rows in ascending wave order, then stores those rows.  Blocks
+            // whose partial sums do not fit the LDS at once exchange them xchg_rows rows at a
+            // time, with a second barrier before the area is overwritten.
             const int nr = (int)rows.size();
-            auto slot = [&](int i, int q) {   // byte offset of wave q's partial of row i, q != i % parts
+            const int c = std::max(1, xchg_rows);
+            auto slot = [&](int i, int q) {   // byte offset of wave q's partial of row i of the phase, q != owner
                 const int o = i % parts;
-                return (i * (parts - 1) + (q < o ? q : q - 1)) * slot_bytes;
+                return ((i % c) * (parts - 1) + (q < o ? q : q - 1)) * slot_bytes;
             };
             // ds offsets are 16 bits wide: one address register per 64 KiB of the exchange area
-            const int n_base = ((parts - 1) * nr * slot_bytes + 65535) / 65536;
+            const int n_base = ((parts - 1) * std::min(nr, c) * slot_bytes + 65535) / 65536;
             const int base0 = vgpr_ring0;          // the operand ring is free now
             for (int b = 1; b < n_base; ++b)
                 e.line("\tv_add_u32_e32 v%d, 0x%x, v%d", base0 + b, b * 65536, kVgprLds);
             auto base_of = [&](int off) { return off < 65536 ? kVgprLds : base0 + off / 65536; };
-            for (int i = 0; i < nr; ++i)
-                if (i % parts != part)
-                    e.line("\tds_write_b32 v%d, v%d offset:%d", base_of(slot(i, part)), kVgprAcc0 + i,
-                           slot(i, part) & 65535);
-            e.line("\ts_waitcnt lgkmcnt(0)");
-            e.line("\ts_barrier");
             const int tmp0 = base0 + std::max(n_base, 1);
             const int batch = std::max(1, std::min(12, ring_size - std::max(n_base, 1)));
-            std::vector<std::pair<int, int>> items;  // (row, source wave) in the order they are added
             std::vector<std::pair<int32_t, int>> mine;
-            for (int i = part; i < nr; i += parts) {
-                mine.push_back({rows[i], kVgprAcc0 + i});
-                for (int q = 0; q < parts; ++q)
-                    if (q != part) items.push_back({i, q});
-            }
-            for (size_t b0 = 0; b0 < items.size(); b0 += batch) {
-                const size_t b1 = std::min(items.size(), b0 + batch);
-                for (size_t t = b0; t < b1; ++t) {
-                    const int off = slot(items[t].first, items[t].second);
-                    e.line("\tds_read_b32 v%d, v%d offset:%d", tmp0 + (int)(t - b0), base_of(off), off & 65535);
+            for (int r0 = 0; r0 < nr; r0 += c) {
+                const int r1 = std::min(nr, r0 + c);
+                if (r0 > 0) e.line("\ts_barrier");   // every wave has read the previous phase
+                for (int i = r0; i < r1; ++i)
+                    if (i % parts != part)
+                        e.line("\tds_write_b32 v%d, v%d offset:%d", base_of(slot(i, part)), kVgprAcc0 + i,
+                               slot(i, part) & 65535);
+                e.line("\ts_waitcnt lgkmcnt(0)");
+                e.line("\ts_barrier");
+                std::vector<std::pair<int, int>> items;  // (row, source wave) in the order they are added
+                for (int i = r0; i < r1; ++i) {
+                    if (i % parts != part) continue;
+                    mine.push_back({rows[i], kVgprAcc0 + i});
+                    for (int q = 0; q < parts; ++q)
+                        if (q != part) items.push_back({i, q});
                 }
-                for (size_t t = b0; t < b1; ++t) {
-                    e.line("\ts_waitcnt lgkmcnt(%d)", (int)(b1 - 1 - t));
-                    e.line("\tv_add_f32_e32 v%d, v%d, v%d", kVgprAcc0 + items[t].first, kVgprAcc0 + items[t].first,
-                           tmp0 + (int)(t - b0));
+                for (size_t b0 = 0; b0 < items.size(); b0 += batch) {
+                    const size_t b1 = std::min(items.size(), b0 + batch);
+                    for (size_t t = b0; t < b1; ++t) {
+                        const int off = slot(items[t].first, items[t].second);
+                        e.line("\tds_read_b32 v%d, v%d offset:%d", tmp0 + (int)(t - b0), base_of(off), off & 65535);
+                    }
+                    for (size_t t = b0; t < b1; ++t) {
+                        e.line("\ts_waitcnt lgkmcnt(%d)", (int)(b1 - 1 - t));
+                        e.line("\tv_add_f32_e32 v%d, v%d, v%d", kVgprAcc0 + items[t].first, kVgprAcc0 + items[t].first,
+                               tmp0 + (int)(t - b0));
+                    }
                 }
             }
             stores(mine);
@@ -612,8 +621,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         gen.n_vgpr = gen.vgpr_ring0 + gen.ring_size;
         if (KS > 1) {
             gen.slot_bytes = 4 * max_lanes;   // lane l of a wave keeps its partial at byte 4*l of the slot
-            gen.lds_bytes = (KS - 1) * max_rows * gen.slot_bytes;
-            if (gen.lds_bytes > kMaxLdsBytes) { err = "spec_rows x spec_ksplit needs more than 160 KiB of LDS"; return SPARSERT_EINVAL; }
+            gen.xchg_rows = std::min(max_rows, kMaxLdsBytes / ((KS - 1) * gen.slot_bytes));
+            gen.lds_bytes = (KS - 1) * gen.xchg_rows * gen.slot_bytes;
             if (gen.lds_bytes == 0) gen.lds_bytes = 256;
         }
     }

@@ -124,8 +124,12 @@ def test_spec_ksplit_largest_block():
     got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=200, spec_ksplit=4, spec_depth=24)
     assert info["spec_lds_bytes"] == 3 * 200 * 256
     assert np.array_equal(got.astype(np.float64), Cref)
-    with pytest.raises(sp.SparseRTError, match="LDS"):
-        run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=200, spec_ksplit=8)
+    # 7 x 200 rows of partial sums do not fit the LDS at once: exchanged in phases of 91 rows
+    got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=200, spec_ksplit=8)
+    assert info["spec_lds_bytes"] == 7 * 91 * 256
+    assert np.array_equal(got.astype(np.float64), Cref)
+    got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=130, spec_ksplit=8, spec_swizzle=True)
+    assert np.array_equal(got.astype(np.float64), Cref)
 
 
 @pytest.mark.parametrize("name,opts", [("c3", dict(spec_rows=96, spec_ksplit=4)),
