@@ -65,6 +65,7 @@ def geomean(xs):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--only", default="", help="comma list of problem tags to run, e.g. t1_p9_90,t3_p3_95")
+    ap.add_argument("--batch", type=int, default=1, help="images per call for the Table 3 convolutions (the paper uses 1)")
     ap.add_argument("--markdown", default="", help="also write the results as a markdown summary to this path")
     ap.add_argument("--ablation", action="store_true",
                     help="also time, per problem, the best row-walk (not specialised) plan and the best plan "
@@ -81,17 +82,18 @@ def main():
     only = set(filter(None, args.only.split(",")))
     rows = []
 
-    def run(tag, csr, N, inp, out, dense_fn, conv=None):
+    def run(tag, csr, N, inp, out, dense_fn, conv=None, batch=0):
         cur = lambda: torch.cuda.current_stream().cuda_stream
         fn = sp.raw.sparsert_conv3x3 if conv else sp.raw.sparsert_spmm
         a, b = ctypes.c_void_p(inp.data_ptr()), ctypes.c_void_p(out.data_ptr())
 
         def tuned(untuned=False, **kw):
             if untuned:   # one fixed parameter choice: the generated kernel with the inspector's defaults
-                plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, conv=conv, kernel=sp.KERNEL_SPEC)
+                plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, conv=conv, batch=batch,
+                                  kernel=sp.KERNEL_SPEC)
             else:
                 plan, _ = sp.tune(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N,
-                                  inp.data_ptr(), out.data_ptr(), cur(), conv=conv, **kw)
+                                  inp.data_ptr(), out.data_ptr(), cur(), conv=conv, batch=batch, **kw)
             h = ctypes.c_void_p(plan.handle)
 
             def sparse():
@@ -130,7 +132,7 @@ def main():
         plan.destroy()
         return {"tag": tag, "sparse_us": round(t_sparse, 3), "dense_us": round(t_dense, 3),
                 "speedup": round(t_dense / t_sparse, 3), "dense_timing": dense_how,
-                "gflops": round(2.0 * csr.nnz * N / t_sparse / 1e3, 1),
+                "gflops": round(2.0 * csr.nnz * N * max(1, batch) / t_sparse / 1e3, 1),
                 "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit", "spec_swizzle")},
                 **extra}
 
@@ -155,12 +157,13 @@ def main():
                 continue
             seed = synth.BASE_SEED + 5000 + 100 * i + pct
             csr, Wd = synth.conv_weights_csr(Cout, Cin, sparsity, seed)
-            X = torch.from_numpy(synth.normal_dense(Cin, img * img, seed + 1).reshape(1, Cin, img, img)).to(dev)
-            Y = torch.empty((1, Cout, img, img), device=dev)
+            nb = max(1, args.batch)
+            X = torch.from_numpy(synth.normal_dense(nb * Cin, img * img, seed + 1).reshape(nb, Cin, img, img)).to(dev)
+            Y = torch.empty((nb, Cout, img, img), device=dev)
             Wt = torch.from_numpy(Wd).to(dev)
             r = run(tag, csr, img * img, X, Y, lambda: torch.nn.functional.conv2d(X, Wt, padding=1),
-                    conv=(Cin, img, img))
-            r.update(image=img, Cin=Cin, Cout=Cout, sparsity=sparsity, paper_speedup_t4=PAPER_T3[sparsity][i])
+                    conv=(Cin, img, img), batch=nb)
+            r.update(image=img, Cin=Cin, Cout=Cout, batch=nb, sparsity=sparsity, paper_speedup_t4=PAPER_T3[sparsity][i])
             rows.append(r)
             print(json.dumps(r), file=sys.stderr, flush=True)
 

@@ -66,7 +66,8 @@ typedef struct sparsert_options {
     int32_t kernel;          /* sparsert_kernel; AUTO lets the inspector choose */
     int32_t conv;            /* 0: SpMM plan.  1: 3x3 / pad 1 / stride 1 convolution plan */
     int32_t Cin, H, W;       /* conv only: K must equal 9*Cin and N must equal H*W */
-    int32_t batch;           /* conv only: images per call, 1..65535 (0 is read as 1) */
+    int32_t batch;           /* problems per call, 1..65535 (0 is read as 1): images of a convolution,
+                                or B/C pairs of an SpMM stored back to back (one more grid dimension) */
     int32_t host_only;       /* 1: analyse only; no HIP call is made, the plan can be
                                 exported but not executed */
     int32_t vec;             /* columns of C per lane; 0 = automatic, else 1,2,4 (,8 for f16) */
@@ -132,6 +133,10 @@ int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void 
  *   B_dev  DEVICE, K x N row-major, plan's dtype, 16-byte aligned, read only
  *   C_dev  DEVICE, M x N row-major, plan's dtype, 16-byte aligned, written
  *   stream a hipStream_t (NULL = the null stream)
+ *
+ * With opt->batch = b the call multiplies b matrices stored back to back, B_dev as
+ * [b, K, N] and C_dev as [b, M, N], by the same A in one launch (larger N is where the
+ * method is expected to do best, Section 4.3; the batch is one more grid dimension).
  *
  * Asynchronous on `stream`; allocates nothing; does not synchronise.  The plan
  * is read only, so concurrent calls on different streams are legal provided
@@ -240,7 +245,7 @@ enum {
     SPARSERT_INFO_NATURAL_ORDER,  /* 1 if the plan was built with natural_order */
     SPARSERT_INFO_SPEC_LANES,     /* SPEC plans: lanes per column tile in use (balanced, <= spec_lanes) */
     SPARSERT_INFO_SPEC_SWIZZLE,   /* SPEC plans: 1 if blocks were formed by similarity */
-    SPARSERT_INFO_BATCH,          /* conv plans: images per call; 0 for SpMM plans */
+    SPARSERT_INFO_BATCH,          /* problems per call (>= 1) */
     SPARSERT_INFO_COUNT = 32      /* remaining entries are zero */
 };
 

@@ -56,12 +56,12 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (opt.spec_rows < 0) { err = "spec_rows must be >= 0"; return SPARSERT_EINVAL; }
     if (opt.split_threshold < 0) { err = "split_threshold must be >= 0"; return SPARSERT_EINVAL; }
     const int64_t esz = opt.dtype == SPARSERT_F16 ? 2 : 4;
+    if (opt.batch < 0 || opt.batch > 65535) { err = "batch must be in 0..65535"; return SPARSERT_EINVAL; }
     if (opt.conv) {
         if (opt.conv != 1) { err = "conv must be 0 or 1"; return SPARSERT_EINVAL; }
         if (opt.Cin <= 0 || opt.H <= 0 || opt.W <= 0) { err = "conv needs Cin, H, W > 0"; return SPARSERT_EINVAL; }
         if ((int64_t)K != 9ll * opt.Cin) { err = "conv needs K == 9*Cin"; return SPARSERT_EINVAL; }
         if ((int64_t)N != (int64_t)opt.H * opt.W) { err = "conv needs N == H*W"; return SPARSERT_EINVAL; }
-        if (opt.batch < 0 || opt.batch > 65535) { err = "batch must be in 0..65535"; return SPARSERT_EINVAL; }
         if (((int64_t)opt.Cin * opt.H * opt.W + opt.W + 1) * esz >= (1ll << 27)) {
             err = "conv input too large for 28-bit operand displacements"; return SPARSERT_EUNSUPPORTED;
         }
@@ -100,7 +100,7 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
     h.M = M; h.K = K; h.N = N; h.nnz = row_ptr[M];
     h.dtype = opt.dtype; h.conv = opt.conv ? 1 : 0;
     h.Cin = h.conv ? opt.Cin : 0; h.H = h.conv ? opt.H : 0; h.W = h.conv ? opt.W : 0;
-    h.batch = h.conv ? std::max(1, opt.batch) : 0;
+    h.batch = std::max(1, opt.batch);
     h.kernel = opt.kernel == SPARSERT_KERNEL_AUTO ? SPARSERT_KERNEL_ROWS : opt.kernel;
     const int esz = h.elem_size();
 

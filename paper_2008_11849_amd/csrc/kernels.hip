@@ -117,7 +117,7 @@ struct RowsArgs {
     int32_t n_split, n_wg_rows;
     int32_t n_tasks, tasks_per_xcd;
     int32_t H, W;
-    int64_t in_image_bytes, out_image_elems;   // conv: distance between the images of a batch (grid y)
+    int64_t in_image_bytes, out_image_elems;   // distance between the problems of a batch (grid y)
 };
 
 template <typename T, int V, bool CONV>
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kGy *kWave) void rows_kernel(const RowsArgs a) {
     const bool owns = lane < a.lanes_per_tile && vc < a.n_vec_cols;
     const int col = (owns ? vc : vc0) * V;
 
-    const gbytes in = (gbytes)a.in + (CONV ? (int64_t)blockIdx.y * a.in_image_bytes : 0);
+    const gbytes in = (gbytes)a.in + (int64_t)blockIdx.y * a.in_image_bytes;
     const uint32_t lane_off = (uint32_t)col * (uint32_t)sizeof(T);
     unsigned tap_ok = 0x1ff;
     if constexpr (CONV) {
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kGy *kWave) void rows_kernel(const RowsArgs a) {
     }
     if (owns) {
         const int row = a.perm[slot];
-        T *out = static_cast<T *>(a.out) + (CONV ? (int64_t)blockIdx.y * a.out_image_elems : 0);
+        T *out = static_cast<T *>(a.out) + (int64_t)blockIdx.y * a.out_image_elems;
         store_cols<T, V>(out + (size_t)row * a.N + col, acc);
     }
 }
@@ -298,9 +298,9 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
     a.n_split = h.n_split; a.n_wg_rows = h.n_wg_rows;
     a.n_tasks = (int32_t)n_tasks; a.tasks_per_xcd = (int32_t)((n_tasks + 7) / 8);
     a.H = h.H; a.W = h.W;
-    a.in_image_bytes = (int64_t)h.Cin * h.H * h.W * h.elem_size();
+    a.in_image_bytes = (h.conv ? (int64_t)h.Cin * h.H * h.W : (int64_t)h.K * h.N) * h.elem_size();
     a.out_image_elems = (int64_t)h.M * h.N;
-    const int images = h.conv ? h.batch : 1;
+    const int images = h.batch;
     if (images < 1 || images > 65535) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool f16 = h.dtype == SPARSERT_F16;
@@ -309,11 +309,11 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
         return f16 ? launch_one<_Float16, 1, true>(a, images, s, err) : launch_one<float, 1, true>(a, images, s, err);
     }
     switch (h.vec) {
-    case 1: return f16 ? launch_one<_Float16, 1, false>(a, 1, s, err) : launch_one<float, 1, false>(a, 1, s, err);
-    case 2: return f16 ? launch_one<_Float16, 2, false>(a, 1, s, err) : launch_one<float, 2, false>(a, 1, s, err);
-    case 4: return f16 ? launch_one<_Float16, 4, false>(a, 1, s, err) : launch_one<float, 4, false>(a, 1, s, err);
+    case 1: return f16 ? launch_one<_Float16, 1, false>(a, images, s, err) : launch_one<float, 1, false>(a, images, s, err);
+    case 2: return f16 ? launch_one<_Float16, 2, false>(a, images, s, err) : launch_one<float, 2, false>(a, images, s, err);
+    case 4: return f16 ? launch_one<_Float16, 4, false>(a, images, s, err) : launch_one<float, 4, false>(a, images, s, err);
     case 8:
-        if (f16) return launch_one<_Float16, 8, false>(a, 1, s, err);
+        if (f16) return launch_one<_Float16, 8, false>(a, images, s, err);
         [[fallthrough]];
     default: err = "unsupported vec for this dtype"; return SPARSERT_EINVAL;
     }
@@ -337,7 +337,7 @@ int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
     if (sp.ksplit > 1 && (lds || sp.ksplit != tpw || sp.n_blocks != sp.n_groups * sp.ksplit)) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     const unsigned gx = (lds || sp.ksplit > 1) ? (unsigned)sp.n_tiles : (unsigned)((sp.n_tiles + tpw - 1) / tpw);
     const unsigned gy = lds ? (unsigned)(sp.n_blocks / tpw) : (unsigned)sp.n_groups;
-    const unsigned gz = h.conv ? (unsigned)h.batch : 1u;   // the generated prologue offsets X and Y by image
+    const unsigned gz = (unsigned)h.batch;   // the generated prologue offsets the operand and the result by problem
     if (gz < 1 || gz > 65535) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     HIP_TRY(hipModuleLaunchKernel(static_cast<hipFunction_t>(d.spec_function), gx, gy, gz, tpw * kWave, 1, 1,
                                   0, static_cast<hipStream_t>(stream), nullptr, config));

@@ -53,7 +53,7 @@ struct HostPlan {
     int32_t vec = 1, lanes_per_tile = 0, n_tiles = 0, gy = kGy;
     int32_t split_threshold = 0, n_split = 0, n_wg_rows = 0;
     int32_t natural_order = 0;         // rows kept in input order (load-balance ablation)
-    int32_t batch = 0;                 // conv: images per call (>= 1); SpMM: 0
+    int32_t batch = 1;                 // problems per call: images of a convolution, B/C pairs of an SpMM
 
     std::vector<int32_t> row_nnz, hist, perm, inv_perm, p_row_ptr, p_col_idx;
     std::vector<uint8_t> p_vals;       // nnz * elem_size bytes, bit copies

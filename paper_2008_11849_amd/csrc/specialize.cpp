@@ -182,7 +182,7 @@ constexpr int kSgprOwns = 22;                  // s[22:23] lanes that own a colu
 constexpr int kSgprOffRing = 24, kOffRing = 8; // s[24:31] row-offset literals in flight
 constexpr int kSgprTap0 = 32;                  // conv: s[32:49] = lane masks of the 9 filter taps
 constexpr int kSgprFull = 50;                  // conv: s[50:51] = all lanes
-constexpr int kSgprImage = 52;                 // conv with batch > 1: workgroup id z = image
+constexpr int kSgprImage = 52;                 // batch > 1: workgroup id z = image / matrix of the batch
 constexpr int kSgprValRing = 54, kValRing = 8; // half plans: s[54:61] values of A on their way into v_fma_mix_f32
 constexpr int kNextFreeSgpr = 62;
 constexpr int kVgprOff = 0;                    // byte offset of the lane's column inside a row
@@ -643,7 +643,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\t.type\t%s,@function", sym);
     e.line("%s:", sym);
     // s[0:1] kernarg, s2 = workgroup id x, s3 = workgroup id y, (s4 = workgroup id z), v0 = thread id
-    const bool images = h.conv && h.batch > 1;
+    const bool images = h.batch > 1;
     if (images) e.line("\ts_mov_b32 s%d, s4", kSgprImage);   // s4 is about to receive a kernel argument
     e.line("\ts_load_dwordx4 s[%d:%d], s[0:1], 0x0", kSgprB, kSgprC + 1);
     e.line("\tv_lshrrev_b32_e32 v%d, 6, v0", kVgprT1);
@@ -726,8 +726,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         e.line("\ts_subb_u32 s%d, s%d, 0", kSgprB + 1, kSgprB + 1);
     }
     if (images) {
-        // image z of the batch: X and Y advance by one image each
-        const int64_t strides[2] = {(int64_t)h.Cin * N * esz, (int64_t)M * N * esz};
+        // problem z of the batch: the operand and the result advance by one image / matrix each
+        const int64_t strides[2] = {(h.conv ? (int64_t)h.Cin : (int64_t)h.K) * N * esz, (int64_t)M * N * esz};
         const int bases[2] = {kSgprB, kSgprC};
         for (int i = 0; i < 2; ++i) {
             e.line("\ts_mov_b32 s%d, 0x%llx", kSgprTmp2, (unsigned long long)strides[i]);

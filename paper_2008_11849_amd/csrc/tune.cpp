@@ -129,6 +129,21 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
         }
     }
 
+    // Assembling a candidate costs about 12 s per million nonzeros, so large matrices get a
+    // shorter list: the configurations that win on the large layers measured so far.
+    if (nnz > (256 << 10)) {
+        const bool tiny = nnz > (1 << 20);
+        auto keep = [&](const sparsert_options &o) {
+            if (o.kernel != SPARSERT_KERNEL_SPEC) return true;
+            if (o.spec_mode == SPARSERT_SPEC_LDS) return !tiny && o.spec_rows == 24 && o.spec_tiles == 8;
+            if (o.spec_ksplit > 1)
+                return (o.spec_rows == 96 && o.spec_ksplit == 4) || (!tiny && o.spec_rows == 48 && o.spec_ksplit == 8);
+            return o.spec_tiles == 4 && (o.spec_rows == 48 || (!tiny && (o.spec_rows == 8 || o.spec_rows == 24)));
+        };
+        cands.erase(std::remove_if(cands.begin(), cands.end(), [&](const sparsert_options &o) { return !keep(o); }),
+                    cands.end());
+    }
+
     float best_us = time_plan(best, conv, in_dev, out_dev, s, e0, e1, launches, repeats);
     auto log = [&](const sparsert_plan *p, float us) {
         if (!report || report->count >= SPARSERT_TUNE_MAX) return;

@@ -13,11 +13,14 @@ def _tdtype(dt):
 
 
 def run_spmm(csr, B, **opts):
+    """B is [K, N], or [batch, K, N] for a batched plan."""
     dev = torch.device("cuda:0")
-    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, B.shape[1], **opts)
+    if B.ndim == 3:
+        opts = dict(opts, batch=B.shape[0])
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, B.shape[-1], **opts)
     Bd = torch.from_numpy(np.ascontiguousarray(B)).to(dev)
     # poison the output so unwritten elements are caught
-    Cd = torch.full((csr.M, B.shape[1]), float("nan"), dtype=_tdtype(B.dtype), device=dev)
+    Cd = torch.full(B.shape[:-2] + (csr.M, B.shape[-1]), float("nan"), dtype=_tdtype(B.dtype), device=dev)
     sp.spmm(plan, Bd.data_ptr(), Cd.data_ptr(), torch.cuda.current_stream(dev).cuda_stream)
     torch.cuda.synchronize()
     out = Cd.cpu().numpy()

@@ -299,6 +299,68 @@ def test_spec_half_skewed_and_conv():
             check(got, Yref, S, np.float16)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_spmm_batch_of_matrices(dtype):
+    """opt->batch on an SpMM plan: [b, K, N] times the same A in one launch."""
+    half = dtype == np.float16
+    csr = synth.small_int_csr(40, 90, 0.8, 31, dtype=dtype, vmax=3)
+    B = np.stack([synth.small_int_dense(90, 130, 40 + i, dtype=dtype, bmax=4) for i in range(3)])
+    Cref = np.stack([_oracle(csr, B[i])[0] for i in range(3)])
+    assert np.abs(Cref).max() <= 2048
+    for opts in (dict(), dict(vec=2), dict(split_threshold=4), dict(kernel=sp.KERNEL_SPEC, spec_rows=7),
+                 dict(kernel=sp.KERNEL_SPEC, spec_rows=10, spec_ksplit=4)) + \
+            (() if half else (dict(kernel=sp.KERNEL_SPEC, spec_rows=5, spec_tiles=2, spec_mode=sp.SPEC_LDS),)):
+        got, info = run_spmm(csr, B, **opts)
+        assert info["batch"] == 3 and got.shape == (3, 40, 130)
+        assert np.array_equal(got.astype(np.float64), Cref), opts
+
+
+def test_launches_replay_from_a_hip_graph():
+    """The executors allocate nothing and only enqueue a kernel, so they can be captured; every
+    replay, with eager work on the same buffers in between, must give the eager result."""
+    dev = torch.device("cuda:0")
+    case = synth.config("c2")
+    csr = case.csr
+    ccsr, Wd = synth.conv_weights_csr(24, 16, 0.8, 5)
+    X = synth.normal_dense(2 * 16, 14 * 14, 6).reshape(2, 16, 14, 14)
+    plans = [sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N),
+             sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N, kernel=sp.KERNEL_SPEC,
+                        spec_rows=16, spec_ksplit=4),
+             sp.inspect(ccsr.row_ptr, ccsr.col_idx, ccsr.vals, 24, 144, 196, conv=(16, 14, 14), batch=2,
+                        kernel=sp.KERNEL_SPEC)]
+    Bd = torch.from_numpy(case.B).to(dev)
+    Xd = torch.from_numpy(X).to(dev)
+    outs = [torch.zeros((csr.M, case.N), device=dev), torch.zeros((csr.M, case.N), device=dev),
+            torch.zeros((2, 24, 14, 14), device=dev)]
+
+    def launch_all():
+        st = torch.cuda.current_stream(dev).cuda_stream
+        sp.spmm(plans[0], Bd.data_ptr(), outs[0].data_ptr(), st)
+        sp.spmm(plans[1], Bd.data_ptr(), outs[1].data_ptr(), st)
+        sp.conv3x3(plans[2], Xd.data_ptr(), outs[2].data_ptr(), st)
+
+    launch_all()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    Cref, S = _oracle(csr, case.B)
+    check(eager[1].cpu().numpy(), Cref, S, np.float32, gate_relative=True)
+    side = torch.cuda.Stream(dev)
+    with torch.cuda.stream(side):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            launch_all()
+    for rep in range(4):
+        for o in outs:
+            o.fill_(float(rep) - 7.0)      # eager work between replays, on the buffers the graph writes
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e), rep
+    for p in plans:
+        p.destroy()
+
+
 NATURAL = [dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=9), dict(kernel=sp.KERNEL_SPEC, spec_rows=12, spec_mode=sp.SPEC_LDS),
            dict(kernel=sp.KERNEL_SPEC, spec_rows=20, spec_ksplit=4)]
 
