@@ -38,10 +38,13 @@ typedef enum sparsert_status {
     SPARSERT_ECOMPILE = -5      /* assembling or loading a generated kernel failed */
 } sparsert_status;
 
-/* Storage type of vals, B/X and C/Y.  Accumulation is always IEEE binary32;
- * with SPARSERT_F16 each product of two halves is exact in binary32 and the
- * sum is rounded to half once, at the store. */
-typedef enum sparsert_dtype { SPARSERT_F32 = 0, SPARSERT_F16 = 1 } sparsert_dtype;
+/* Storage type of vals, B/X and C/Y.  Floating types accumulate in IEEE
+ * binary32; with SPARSERT_F16 each product of two halves is exact in binary32
+ * and the sum is rounded to half once, at the store.  SPARSERT_I8 (the low
+ * precision the paper leaves as future work, Section 6): vals and B/X are
+ * int8, C/Y is int32, sums are exact 32-bit integers (the inspector refuses a
+ * K long enough to overflow them); no scaling or requantisation is applied. */
+typedef enum sparsert_dtype { SPARSERT_F32 = 0, SPARSERT_F16 = 1, SPARSERT_I8 = 2 } sparsert_dtype;
 
 /* Executor families (options.kernel / INFO[SPARSERT_INFO_KERNEL]). */
 typedef enum sparsert_kernel {
@@ -70,7 +73,7 @@ typedef struct sparsert_options {
                                 or B/C pairs of an SpMM stored back to back (one more grid dimension) */
     int32_t host_only;       /* 1: analyse only; no HIP call is made, the plan can be
                                 exported but not executed */
-    int32_t vec;             /* columns of C per lane; 0 = automatic, else 1,2,4 (,8 for f16) */
+    int32_t vec;             /* columns of C per lane; 0 = automatic, else 1,2,4 (,8 for f16; 1 or 4 for int8) */
     int32_t split_threshold; /* rows with at least this many nonzeros are split over the
                                 waves of a workgroup; 0 = automatic */
     int32_t spec_rows;       /* SPARSERT_KERNEL_SPEC: rows of A per generated code block
@@ -108,7 +111,7 @@ typedef struct sparsert_options {
  *
  *   row_ptr  HOST int32[M+1], row_ptr[0] == 0, non-decreasing
  *   col_idx  HOST int32[nnz], 0 <= col < K, strictly ascending inside each row
- *   vals     HOST float[nnz] (SPARSERT_F32) or IEEE half[nnz] (SPARSERT_F16);
+ *   vals     HOST float[nnz] (SPARSERT_F32), IEEE half[nnz] (SPARSERT_F16) or int8[nnz] (SPARSERT_I8);
  *            explicit zeros, -0.0, NaN payloads are kept bit for bit
  *   M, K, N  > 0.  N is part of the plan (it fixes tiling and B row offsets).
  *   opt      may be NULL (= all zero)

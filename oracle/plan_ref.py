@@ -45,8 +45,8 @@ def _bin(x: np.ndarray) -> np.ndarray:
     return out
 
 
-def choose_vec(M, N, vmax):
-    cands = [v for v in (1, 2, 4, 8) if v <= vmax and N % v == 0]
+def choose_vec(M, N, vmax, skip=0):
+    cands = [v for v in (1, 2, 4, 8) if v <= vmax and N % v == 0 and v != skip]
     tiles = {v: -(-(N // v) // WAVE) for v in cands}
     work = {v: tiles[v] * v for v in cands}
     wmin = min(work.values())
@@ -60,7 +60,8 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, n
     col_idx = np.asarray(col_idx, dtype=np.int64)
     vals = np.asarray(vals)
     half = vals.dtype == np.float16
-    item = 2 if half else 4
+    int8 = vals.dtype == np.int8
+    item = 2 if half else 1 if int8 else 4
     nnz = int(row_ptr[M])
     row_nnz = np.diff(row_ptr)
     bins_of = _bin(row_nnz)
@@ -87,7 +88,7 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, n
         i = j
 
     vmax = 1 if conv else (8 if half else 4)
-    V = vec if vec else choose_vec(M, N, vmax)
+    V = vec if vec else choose_vec(M, N, vmax, skip=2 if int8 else 0)   # int8: one column or a packed dword of four
     nvc = N // V
     n_tiles = -(-nvc // WAVE)
     lanes_per_tile = -(-nvc // n_tiles)
@@ -102,7 +103,10 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, n
         share = -(-n // GY)
         segments[s] = p_row_ptr[s] + np.minimum(np.arange(GY + 1) * share, n)
 
-    val_bits = p_vals.astype(np.float32).view(np.uint32)  # half -> float is exact
+    if int8:
+        val_bits = p_vals.astype(np.int32).view(np.uint32)    # sign-extended
+    else:
+        val_bits = p_vals.astype(np.float32).view(np.uint32)  # half -> float is exact
     stream = np.zeros((nnz, 2), dtype=np.uint32)
     conv_seg = np.zeros((0,), dtype=np.int64)
     if not conv:
@@ -122,7 +126,7 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, n
             stream[a:b, 1] = val_bits[order]
             conv_seg[slot] = a + np.concatenate([[0], np.cumsum(np.bincount(t[a:b], minlength=9))])
 
-    info = dict(M=M, K=K, N=N, nnz=nnz, dtype=1 if half else 0, conv=1 if conv else 0,
+    info = dict(M=M, K=K, N=N, nnz=nnz, dtype=1 if half else 2 if int8 else 0, conv=1 if conv else 0,
                 Cin=conv[0] if conv else 0, H=conv[1] if conv else 0, W=conv[2] if conv else 0,
                 kernel=1, vec=V, lanes_per_tile=lanes_per_tile, n_tiles=n_tiles, gy=GY,
                 split_threshold=thr, n_split=n_split, n_wg_rows=n_wg_rows, n_bins=len(bins))

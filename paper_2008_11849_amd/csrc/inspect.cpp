@@ -20,7 +20,7 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
                     std::string &err) {
     if (!row_ptr) { err = "row_ptr is NULL"; return SPARSERT_EINVAL; }
     if (M <= 0 || K <= 0 || N <= 0) { err = "M, K and N must be positive"; return SPARSERT_EINVAL; }
-    if (opt.dtype != SPARSERT_F32 && opt.dtype != SPARSERT_F16) { err = "unknown dtype"; return SPARSERT_EINVAL; }
+    if (opt.dtype != SPARSERT_F32 && opt.dtype != SPARSERT_F16 && opt.dtype != SPARSERT_I8) { err = "unknown dtype"; return SPARSERT_EINVAL; }
     if (opt.kernel < SPARSERT_KERNEL_AUTO || opt.kernel > SPARSERT_KERNEL_SPEC) { err = "unknown kernel family"; return SPARSERT_EINVAL; }
     if (opt.natural_order != 0 && opt.natural_order != 1) { err = "natural_order must be 0 or 1"; return SPARSERT_EINVAL; }
     if (opt.spec_lanes != 0 && opt.spec_lanes != 16 && opt.spec_lanes != 32 && opt.spec_lanes != 64) { err = "spec_lanes must be 0,16,32,64"; return SPARSERT_EINVAL; }
@@ -45,7 +45,9 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     const int vmax = opt.dtype == SPARSERT_F16 ? 8 : 4;
     if (opt.vec != 0) {
         const int v = opt.vec;
-        if (!(v == 1 || v == 2 || v == 4 || v == 8) || v > vmax) { err = "vec must be 0,1,2,4 (8 for f16)"; return SPARSERT_EINVAL; }
+        if (!(v == 1 || v == 2 || v == 4 || v == 8) || v > vmax || (opt.dtype == SPARSERT_I8 && v == 2)) {
+            err = "vec must be 0,1,2,4 (8 for f16; 1 or 4 for int8)"; return SPARSERT_EINVAL;
+        }
         if (N % v != 0) { err = "N must be a multiple of vec"; return SPARSERT_EINVAL; }
         if (opt.conv && v != 1) { err = "conv plans use vec = 1"; return SPARSERT_EINVAL; }
     }
@@ -55,7 +57,10 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (opt.spec_mode < SPARSERT_SPEC_AUTO || opt.spec_mode > SPARSERT_SPEC_LDS) { err = "unknown spec_mode"; return SPARSERT_EINVAL; }
     if (opt.spec_rows < 0) { err = "spec_rows must be >= 0"; return SPARSERT_EINVAL; }
     if (opt.split_threshold < 0) { err = "split_threshold must be >= 0"; return SPARSERT_EINVAL; }
-    const int64_t esz = opt.dtype == SPARSERT_F16 ? 2 : 4;
+    const int64_t esz = opt.dtype == SPARSERT_F16 ? 2 : opt.dtype == SPARSERT_I8 ? 1 : 4;
+    const int64_t osz = opt.dtype == SPARSERT_F16 ? 2 : 4;
+    // int8: |sum| <= K * 128 * 128 must stay below 2^31
+    if (opt.dtype == SPARSERT_I8 && K >= (1 << 17)) { err = "K too long for exact 32-bit sums of int8 products"; return SPARSERT_EUNSUPPORTED; }
     if (opt.batch < 0 || opt.batch > 65535) { err = "batch must be in 0..65535"; return SPARSERT_EINVAL; }
     if (opt.conv) {
         if (opt.conv != 1) { err = "conv must be 0 or 1"; return SPARSERT_EINVAL; }
@@ -65,7 +70,8 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
         if (((int64_t)opt.Cin * opt.H * opt.W + opt.W + 1) * esz >= (1ll << 27)) {
             err = "conv input too large for 28-bit operand displacements"; return SPARSERT_EUNSUPPORTED;
         }
-    } else if ((int64_t)K * N * esz >= (1ll << 31) || (int64_t)M * N * esz >= (1ll << 31)) {
+        if ((int64_t)M * N * osz >= (1ll << 31)) { err = "one image of Y reaches 2 GiB"; return SPARSERT_EUNSUPPORTED; }
+    } else if ((int64_t)K * N * esz >= (1ll << 31) || (int64_t)M * N * osz >= (1ll << 31)) {
         err = "B or C reaches 2 GiB: operand offsets are 32-bit"; return SPARSERT_EUNSUPPORTED;
     }
     return SPARSERT_OK;
@@ -75,11 +81,12 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
 // issues V multiply-adds per nonzero per tile, so work(V) = n_tiles(V) * V.
 // Among the V dividing N whose work is within 7 % of the least, take the
 // largest that still leaves kFullTasks wave tasks; if none does, the smallest.
-static int choose_vec(int32_t M, int32_t N, int vmax) {
+// `skip` names a V the storage type has no kernel for (2 for int8), or 0.
+static int choose_vec(int32_t M, int32_t N, int vmax, int skip) {
     int cand[4], nc = 0;
     int64_t work[4], wmin = INT64_MAX;
     for (int v = 1; v <= vmax; v *= 2) {
-        if (N % v) continue;
+        if (N % v || v == skip) continue;
         const int64_t tiles = ((int64_t)N / v + kWave - 1) / kWave;
         cand[nc] = v; work[nc] = tiles * v; wmin = std::min(wmin, work[nc]); ++nc;
     }
@@ -147,7 +154,7 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
 
     // Column tiling.
     const int vmax = h.conv ? 1 : (h.dtype == SPARSERT_F16 ? 8 : 4);
-    h.vec = opt.vec ? opt.vec : choose_vec(M, N, vmax);
+    h.vec = opt.vec ? opt.vec : choose_vec(M, N, vmax, h.dtype == SPARSERT_I8 ? 2 : 0);
     const int32_t nvc = N / h.vec;  // vector columns
     h.n_tiles = (nvc + kWave - 1) / kWave;
     h.lanes_per_tile = (nvc + h.n_tiles - 1) / h.n_tiles;
@@ -168,13 +175,15 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
             h.segments[(size_t)i * (h.gy + 1) + g] = start + std::min<int64_t>((int64_t)g * share, n);
     }
 
-    // The nonzero stream the executor reads: {operand byte offset, value as binary32 bits}.
+    // The nonzero stream the executor reads: {operand byte offset, value as binary32 bits};
+    // int8 plans: the value sign-extended to 32 bits.
     h.stream.resize((size_t)h.nnz * 2);
     auto value_bits = [&](int32_t p) -> uint32_t {
         if (h.dtype == SPARSERT_F16) {
             uint16_t hb; std::memcpy(&hb, &h.p_vals[(size_t)p * 2], 2);
             return half_bits_to_float_bits(hb);
         }
+        if (h.dtype == SPARSERT_I8) return (uint32_t)(int32_t)(int8_t)h.p_vals[(size_t)p];
         uint32_t fb; std::memcpy(&fb, &h.p_vals[(size_t)p * 4], 4);
         return fb;
     };

@@ -25,39 +25,83 @@ template <typename T> struct VecOf<T, 1> { typedef T type; };
 // scalar base and a 32-bit per-lane offset.
 typedef const char __attribute__((address_space(1))) *gbytes;
 
-template <typename T, int V>
-__device__ __forceinline__ void load_cols(gbytes p, float (&out)[V]) {
+// Arithmetic of one storage type at V columns per lane: what an operand fetch yields, how a
+// nonzero is accumulated, and how the accumulators are stored.
+//   float / half: operands widened to fp32, fp32 multiply-add, the stream word is the fp32 value;
+//                 half results are rounded once, to nearest even, at the store.
+//   int8:         exact 32-bit integer sums; the stream word is the sign-extended value.  At
+//                 V = 4 a lane's four adjacent columns stay packed in one dword and
+//                 v_dot4_i32_i8 against the value placed in byte j picks out column j.
+template <typename T, int V> struct Ops {
+    typedef float acc_t;
+    typedef T out_t;
+    struct opd_t { float v[V]; };
     typedef typename VecOf<T, V>::type vec_t;
-    const vec_t v = *reinterpret_cast<const vec_t __attribute__((address_space(1))) *>(p);
-    if constexpr (V == 1) {
-        out[0] = (float)v;
-    } else {
+    static __device__ __forceinline__ opd_t load(gbytes p) {
+        const vec_t v = *reinterpret_cast<const vec_t __attribute__((address_space(1))) *>(p);
+        opd_t o;
+        if constexpr (V == 1) {
+            o.v[0] = (float)v;
+        } else {
 #pragma unroll
-        for (int j = 0; j < V; ++j) out[j] = (float)v[j];
+            for (int j = 0; j < V; ++j) o.v[j] = (float)v[j];
+        }
+        return o;
     }
-}
+    static __device__ __forceinline__ void mad(acc_t (&acc)[V], uint32_t word, const opd_t &b) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = __builtin_fmaf(__uint_as_float(word), b.v[j], acc[j]);
+    }
+    static __device__ __forceinline__ void store(out_t *dst, const acc_t (&acc)[V]) {
+        vec_t v;
+        if constexpr (V == 1) {
+            v = (T)acc[0];
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) v[j] = (T)acc[j];  // half: one round-to-nearest-even here
+        }
+        *reinterpret_cast<vec_t *>(dst) = v;
+    }
+};
 
-template <typename T, int V>
-__device__ __forceinline__ void store_cols(T *dst, const float (&acc)[V]) {
-    typedef typename VecOf<T, V>::type vec_t;
-    vec_t v;
-    if constexpr (V == 1) {
-        v = (T)acc[0];
-    } else {
-#pragma unroll
-        for (int j = 0; j < V; ++j) v[j] = (T)acc[j];  // f16: one round-to-nearest-even here
+template <int V> struct Ops<int8_t, V> {
+    static_assert(V == 1 || V == 4, "int8 plans use one or four columns per lane");
+    typedef int32_t acc_t;
+    typedef int32_t out_t;
+    struct opd_t { int32_t v; };   // V = 1: the operand; V = 4: four packed operands
+    static __device__ __forceinline__ opd_t load(gbytes p) {
+        opd_t o;
+        if constexpr (V == 1) o.v = *reinterpret_cast<const int8_t __attribute__((address_space(1))) *>(p);
+        else o.v = *reinterpret_cast<const int32_t __attribute__((address_space(1))) *>(p);
+        return o;
     }
-    *reinterpret_cast<vec_t *>(dst) = v;
-}
+    static __device__ __forceinline__ void mad(acc_t (&acc)[V], uint32_t word, const opd_t &b) {
+        if constexpr (V == 1) {
+            acc[0] += (int32_t)word * b.v;
+        } else {
+            const uint32_t a8 = word & 0xffu;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_sdot4(b.v, (int32_t)(a8 << (8 * j)), acc[j], false);
+        }
+    }
+    static __device__ __forceinline__ void store(out_t *dst, const acc_t (&acc)[V]) {
+        if constexpr (V == 1) {
+            *dst = acc[0];
+        } else {
+            typedef int32_t i4 __attribute__((ext_vector_type(4)));
+            *reinterpret_cast<i4 *>(dst) = i4{acc[0], acc[1], acc[2], acc[3]};
+        }
+    }
+};
 
 // One operand fetch.  SpMM: the stream word is the byte offset of B's row.  Convolution: the
 // top 4 bits name the filter tap (r*3+s), the low 28 bits are the signed byte displacement of
 // X[c, oh+r-1, ow+s-1] from X[0, oh, ow]; the caller only walks a tap's nonzeros with the lanes
 // whose tap lies inside the image, so no test is needed here.
 template <typename T, int V, bool CONV>
-__device__ __forceinline__ void fetch(gbytes in, uint32_t lane_off, uint32_t word, float (&b)[V]) {
+__device__ __forceinline__ typename Ops<T, V>::opd_t fetch(gbytes in, uint32_t lane_off, uint32_t word) {
     const int32_t disp = CONV ? (int32_t)(word << 4) >> 4 : (int32_t)word;
-    load_cols<T, V>(in + disp + lane_off, b);
+    return Ops<T, V>::load(in + disp + lane_off);
 }
 
 // acc[:] += sum over stream positions [p0, p1) of value * operand.  p0, p1, the stream and
@@ -67,7 +111,8 @@ __device__ __forceinline__ void fetch(gbytes in, uint32_t lane_off, uint32_t wor
 // never need a guard.
 template <typename T, int V, bool CONV>
 __device__ __forceinline__ void walk(const uint2 *__restrict__ stream, int p0, int p1,
-                                     gbytes in, uint32_t lane_off, float (&acc)[V]) {
+                                     gbytes in, uint32_t lane_off, typename Ops<T, V>::acc_t (&acc)[V]) {
+    typedef typename Ops<T, V>::opd_t opd_t;
     constexpr int U = 8;
     int p = p0;
     uint2 e[U];
@@ -75,15 +120,13 @@ __device__ __forceinline__ void walk(const uint2 *__restrict__ stream, int p0, i
     for (int i = 0; i < U; ++i) e[i] = stream[p + i];
     for (; p + U <= p1; p += U) {
         uint2 en[U];
-        float b[U][V];
+        opd_t b[U];
 #pragma unroll
         for (int i = 0; i < U; ++i) en[i] = stream[p + U + i];
 #pragma unroll
-        for (int i = 0; i < U; ++i) fetch<T, V, CONV>(in, lane_off, e[i].x, b[i]);
+        for (int i = 0; i < U; ++i) b[i] = fetch<T, V, CONV>(in, lane_off, e[i].x);
 #pragma unroll
-        for (int i = 0; i < U; ++i)
-#pragma unroll
-            for (int j = 0; j < V; ++j) acc[j] = __builtin_fmaf(__uint_as_float(e[i].y), b[i][j], acc[j]);
+        for (int i = 0; i < U; ++i) Ops<T, V>::mad(acc, e[i].y, b[i]);
 #pragma unroll
         for (int i = 0; i < U; ++i) e[i] = en[i];
     }
@@ -92,15 +135,12 @@ __device__ __forceinline__ void walk(const uint2 *__restrict__ stream, int p0, i
     // the multiply-adds are guarded (by a wave-uniform count).
     const int rem = p1 - p;
     if (rem > 0) {
-        float b[U - 1][V];
+        opd_t b[U - 1];
 #pragma unroll
-        for (int i = 0; i < U - 1; ++i) fetch<T, V, CONV>(in, lane_off, i < rem ? e[i].x : e[0].x, b[i]);
+        for (int i = 0; i < U - 1; ++i) b[i] = fetch<T, V, CONV>(in, lane_off, i < rem ? e[i].x : e[0].x);
 #pragma unroll
         for (int i = 0; i < U - 1; ++i)
-            if (i < rem) {
-#pragma unroll
-                for (int j = 0; j < V; ++j) acc[j] = __builtin_fmaf(__uint_as_float(e[i].y), b[i][j], acc[j]);
-            }
+            if (i < rem) Ops<T, V>::mad(acc, e[i].y, b[i]);
     }
 }
 
@@ -156,9 +196,10 @@ __global__ __launch_bounds__(kGy *kWave) void rows_kernel(const RowsArgs a) {
             }
     }
 
-    float acc[V];
+    typedef typename Ops<T, V>::acc_t acc_t;
+    acc_t acc[V];
 #pragma unroll
-    for (int j = 0; j < V; ++j) acc[j] = 0.0f;
+    for (int j = 0; j < V; ++j) acc[j] = 0;
 
     int slot, p0, p1;
     const bool split = wg_row < a.n_split;
@@ -188,14 +229,14 @@ __global__ __launch_bounds__(kGy *kWave) void rows_kernel(const RowsArgs a) {
     if (split) {
         // Section 3.3: partial tiles of the groups are reduced through shared memory at the
         // end.  Summed by wave 0 in wave order: deterministic, no atomics.
-        __shared__ float red[kGy][V][kWave];
+        __shared__ acc_t red[kGy][V][kWave];
 #pragma unroll
         for (int j = 0; j < V; ++j) red[wave][j][lane] = acc[j];
         __syncthreads();
         if (wave != 0) return;
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-            float s = red[0][j][lane];
+            acc_t s = red[0][j][lane];
 #pragma unroll
             for (int g = 1; g < kGy; ++g) s += red[g][j][lane];
             acc[j] = s;
@@ -203,8 +244,9 @@ __global__ __launch_bounds__(kGy *kWave) void rows_kernel(const RowsArgs a) {
     }
     if (owns) {
         const int row = a.perm[slot];
-        T *out = static_cast<T *>(a.out) + (int64_t)blockIdx.y * a.out_image_elems;
-        store_cols<T, V>(out + (size_t)row * a.N + col, acc);
+        typedef typename Ops<T, V>::out_t out_t;
+        out_t *out = static_cast<out_t *>(a.out) + (int64_t)blockIdx.y * a.out_image_elems;
+        Ops<T, V>::store(out + (size_t)row * a.N + col, acc);
     }
 }
 
@@ -304,6 +346,14 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
     if (images < 1 || images > 65535) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool f16 = h.dtype == SPARSERT_F16;
+    if (h.dtype == SPARSERT_I8) {
+        if (h.conv && h.vec != 1) { err = "conv plans use vec = 1"; return SPARSERT_EINVAL; }
+        if (h.conv) return launch_one<int8_t, 1, true>(a, images, s, err);
+        if (h.vec == 1) return launch_one<int8_t, 1, false>(a, images, s, err);
+        if (h.vec == 4) return launch_one<int8_t, 4, false>(a, images, s, err);
+        err = "unsupported vec for this dtype";
+        return SPARSERT_EINVAL;
+    }
     if (h.conv) {
         if (h.vec != 1) { err = "conv plans use vec = 1"; return SPARSERT_EINVAL; }
         return f16 ? launch_one<_Float16, 1, true>(a, images, s, err) : launch_one<float, 1, true>(a, images, s, err);

@@ -63,7 +63,8 @@ struct HostPlan {
     std::vector<int32_t> segments;     // [n_split][gy+1]
     SpecPlan spec;
 
-    int elem_size() const { return dtype == SPARSERT_F16 ? 2 : 4; }
+    int elem_size() const { return dtype == SPARSERT_F16 ? 2 : dtype == SPARSERT_I8 ? 1 : 4; }   // vals, B / X
+    int out_elem_size() const { return dtype == SPARSERT_F16 ? 2 : 4; }                            // C / Y
 };
 
 struct DevicePlan {

@@ -497,6 +497,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         err = "convolution plans use the DIRECT variant of the generated kernel";
         return SPARSERT_EUNSUPPORTED;
     }
+    if (h.dtype == SPARSERT_I8) { err = "int8 plans run on the row-walk kernel"; return SPARSERT_EUNSUPPORTED; }
     const bool half = h.dtype == SPARSERT_F16;
     const int esz = half ? 2 : 4;
     if (half && opt.spec_mode == SPARSERT_SPEC_LDS) {

@@ -65,7 +65,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
         sparsert_plan_destroy(best);
         return sparsert::set_error(SPARSERT_EHIP, "hipEventCreate failed");
     }
-    const bool conv = b.conv != 0, f16 = b.dtype == SPARSERT_F16;
+    const bool conv = b.conv != 0, f16 = b.dtype == SPARSERT_F16, i8 = b.dtype == SPARSERT_I8;
     const int family = b.kernel;   // AUTO: both executor families; else only that one
     const int64_t nnz = row_ptr[M];
     const int launches = 30, repeats = 3;
@@ -73,7 +73,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
     std::vector<sparsert_options> cands;
     if (!conv) {
         for (int v = 1; v <= (f16 ? 8 : 4); v *= 2) {
-            if (N % v) continue;
+            if (N % v || (i8 && v == 2)) continue;
             sparsert_options o = b;
             o.kernel = SPARSERT_KERNEL_ROWS; o.vec = v;
             cands.push_back(o);
@@ -88,7 +88,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
         }
     }
     if (family == SPARSERT_KERNEL_SPEC) cands.clear();
-    if (nnz <= (4 << 20) && family != SPARSERT_KERNEL_ROWS) {
+    if (nnz <= (4 << 20) && family != SPARSERT_KERNEL_ROWS && !i8) {
         const int64_t tiles = (N + 63) / 64;
         for (int r : {1, 2, 4, 8, 16, 24, 48}) {
             if (r > M) continue;

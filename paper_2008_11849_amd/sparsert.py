@@ -15,7 +15,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsparsert.so")
 
 OK, EINVAL, ENOMEM, EHIP, EUNSUPPORTED, ECOMPILE = 0, -1, -2, -3, -4, -5
-F32, F16 = 0, 1
+F32, F16, I8 = 0, 1, 2
+_DTYPE_OF = {np.dtype(np.float32): F32, np.dtype(np.float16): F16, np.dtype(np.int8): I8}
+_NP_OF = {F32: np.float32, F16: np.float16, I8: np.int8}
 KERNEL_AUTO, KERNEL_ROWS, KERNEL_SPEC = 0, 1, 2
 SPEC_AUTO, SPEC_DIRECT, SPEC_LDS = 0, 1, 2
 (FIELD_INFO, FIELD_ROW_NNZ, FIELD_HIST, FIELD_PERM, FIELD_INV_PERM, FIELD_P_ROW_PTR,
@@ -125,7 +127,7 @@ class Plan:
         need = ctypes.c_size_t(0)
         _check(_lib.sparsert_plan_export(self.handle, field, None, 0, ctypes.byref(need)))
         if field == FIELD_P_VALS:
-            dt = np.float16 if self.dtype == F16 else np.float32
+            dt = _NP_OF[self.dtype]
         else:
             dt = _FIELD_DTYPE.get(field, np.int32)
         out = np.empty(need.value // np.dtype(dt).itemsize, dtype=dt)
@@ -155,17 +157,14 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
             spec_rows: int = 0, spec_depth: int = 0, spec_tiles: int = 0,
             spec_mode: int = 0, spec_ksplit: int = 0, natural_order: bool = False,
             spec_lanes: int = 0, spec_swizzle: bool = False) -> Plan:
-    """sparsert_inspect.  `vals` must already be float32 or float16; it is not converted."""
+    """sparsert_inspect.  `vals` must already be float32, float16 or int8; it is not converted."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
     vals = np.ascontiguousarray(vals)
     if dtype is None:
-        if vals.dtype == np.float16:
-            dtype = F16
-        elif vals.dtype == np.float32:
-            dtype = F32
-        else:
-            raise TypeError("vals must be float32 or float16")
+        if vals.dtype not in _DTYPE_OF:
+            raise TypeError("vals must be float32, float16 or int8")
+        dtype = _DTYPE_OF[vals.dtype]
     opt = Options()
     opt.dtype, opt.kernel, opt.host_only = dtype, kernel, int(host_only)
     opt.vec, opt.split_threshold, opt.batch = vec, split_threshold, batch
@@ -189,10 +188,10 @@ def tune(row_ptr, col_idx, vals, M: int, K: int, N: int, in_dev: int, out_dev: i
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
     vals = np.ascontiguousarray(vals)
-    if vals.dtype not in (np.float16, np.float32):
-        raise TypeError("vals must be float32 or float16")
+    if vals.dtype not in _DTYPE_OF:
+        raise TypeError("vals must be float32, float16 or int8")
     opt = Options()
-    opt.dtype = F16 if vals.dtype == np.float16 else F32
+    opt.dtype = _DTYPE_OF[vals.dtype]
     opt.kernel, opt.natural_order, opt.batch = kernel, int(natural_order), batch
     if conv is not None:
         opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv

@@ -144,6 +144,20 @@ def small_int_csr(M, K, sparsity, seed, dtype=np.float32, vmax=4) -> CSR:
     return csr_from_mask(W.astype(dtype), mask)
 
 
+def int8_csr(M, K, sparsity, seed) -> CSR:
+    """Uniform mask, values uniform over the int8 range without zero (a quantised weight matrix)."""
+    rng = np.random.default_rng(seed)
+    mask = uniform_mask(M, K, sparsity, rng)
+    W = rng.integers(1, 128, size=(M, K)) * rng.choice([-1, 1], size=(M, K))
+    W[rng.random((M, K)) < 0.01] = -128          # the asymmetric end of the range shows up too
+    return csr_from_mask(W.astype(np.int8), mask)
+
+
+def int8_dense(K, N, seed) -> np.ndarray:
+    rng = np.random.default_rng(seed)
+    return rng.integers(-128, 128, size=(K, N)).astype(np.int8)
+
+
 def small_int_dense(K, N, seed, dtype=np.float32, bmax=8) -> np.ndarray:
     rng = np.random.default_rng(seed)
     return rng.integers(-bmax, bmax + 1, size=(K, N)).astype(dtype)

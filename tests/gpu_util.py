@@ -9,7 +9,15 @@ TOL = {np.dtype(np.float32): 1e-4, np.dtype(np.float16): 2e-2}
 
 
 def _tdtype(dt):
-    return torch.float16 if np.dtype(dt) == np.float16 else torch.float32
+    return {np.dtype(np.float16): torch.float16, np.dtype(np.int8): torch.int8}.get(np.dtype(dt), torch.float32)
+
+
+def _poisoned(shape, in_dtype, dev):
+    """Output buffer pre-filled with a value no correct result has: NaN, or for int8 plans
+    (int32 output) an integer beyond any reachable sum."""
+    if np.dtype(in_dtype) == np.int8:
+        return torch.full(shape, -(2 ** 31) + 12345, dtype=torch.int32, device=dev)
+    return torch.full(shape, float("nan"), dtype=_tdtype(in_dtype), device=dev)
 
 
 def run_spmm(csr, B, **opts):
@@ -20,7 +28,7 @@ def run_spmm(csr, B, **opts):
     plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, B.shape[-1], **opts)
     Bd = torch.from_numpy(np.ascontiguousarray(B)).to(dev)
     # poison the output so unwritten elements are caught
-    Cd = torch.full(B.shape[:-2] + (csr.M, B.shape[-1]), float("nan"), dtype=_tdtype(B.dtype), device=dev)
+    Cd = _poisoned(B.shape[:-2] + (csr.M, B.shape[-1]), B.dtype, dev)
     sp.spmm(plan, Bd.data_ptr(), Cd.data_ptr(), torch.cuda.current_stream(dev).cuda_stream)
     torch.cuda.synchronize()
     out = Cd.cpu().numpy()
@@ -35,7 +43,7 @@ def run_conv(csr, X, Cout, **opts):
     plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, Cout, 9 * Cin, H * W,
                       conv=(Cin, H, W), batch=batch, **opts)
     Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
-    Yd = torch.full((batch, Cout, H, W), float("nan"), dtype=_tdtype(X.dtype), device=dev)
+    Yd = _poisoned((batch, Cout, H, W), X.dtype, dev)
     sp.conv3x3(plan, Xd.data_ptr(), Yd.data_ptr(), torch.cuda.current_stream(dev).cuda_stream)
     torch.cuda.synchronize()
     out = Yd.cpu().numpy()

@@ -96,6 +96,38 @@ def test_plan_overrides(vec, thr):
                                            vec=vec, split_threshold=thr))
 
 
+@pytest.mark.parametrize("N,conv", [(64, None), (63, None), (100, None), (1024, None), (42, (4, 6, 7))])
+def test_int8_plan_is_bit_exact(N, conv):
+    if conv:
+        rng = np.random.default_rng(2)
+        Wd = (rng.integers(-128, 128, size=(9, 4, 3, 3)) * (rng.random((9, 4, 3, 3)) < 0.3)).astype(np.int8)
+        csr = synth.csr_from_mask(Wd.reshape(9, 36), Wd.reshape(9, 36) != 0)
+    else:
+        csr = synth.int8_csr(600 if N == 1024 else 50, 36, 0.8, 5)
+    plan = _host_plan(csr, N, conv=conv)
+    refp = plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, conv=conv)
+    _assert_plan_equal(plan, refp)
+    info = plan.info()
+    assert info["dtype"] == sp.I8 and info["vec"] == (4 if N == 1024 else 1)   # four packed columns once there is enough work
+    assert plan.export(sp.FIELD_P_VALS).dtype == np.int8
+    # the stream carries the sign-extended value
+    stream = plan.export(sp.FIELD_STREAM).reshape(-1, 2)
+    if not conv:
+        assert np.array_equal(stream[:, 1].view(np.int32), plan.export(sp.FIELD_P_VALS).astype(np.int32))
+    plan.destroy()
+    for bad in ({"vec": 2}, {"kernel": sp.KERNEL_SPEC}):
+        with pytest.raises(sp.SparseRTError):
+            _host_plan(csr, 64 if not conv else N, conv=conv, **bad)
+
+
+def test_int8_rejects_a_reduction_axis_that_could_overflow():
+    rp = np.array([0, 1], dtype=np.int32)
+    ci = np.array([0], dtype=np.int32)
+    v = np.ones(1, dtype=np.int8)
+    assert _inspect_rc(rp, ci, v, 1, (1 << 17) - 1, 4) == sp.OK
+    assert _inspect_rc(rp, ci, v, 1, 1 << 17, 4) == sp.EUNSUPPORTED
+
+
 def test_natural_order_plan_is_bit_exact():
     """Load-balance ablation: identity permutation, no split rows, contiguous code blocks."""
     csr = synth.skewed_csr(100, 200, 0.8, 3)

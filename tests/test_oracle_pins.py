@@ -116,6 +116,35 @@ def test_half_inputs_are_consumed_exactly():
     assert np.allclose(C, A @ B.astype(np.float64), rtol=1e-14, atol=1e-14)
 
 
+def test_int8_inputs_give_the_exact_integer_product():
+    """int8 storage: every product and every sum is an integer far below 2^53, so the float64
+    oracle is the exact integer result; pinned against NumPy's int64 matrix product, and at
+    the extreme of the range (all -128: each sum is K * 16384, the bound the 32-bit output
+    must hold)."""
+    csr = synth.int8_csr(37, 300, 0.8, 3)
+    B = synth.int8_dense(300, 29, 4)
+    assert csr.vals.dtype == np.int8 and B.dtype == np.int8 and (csr.vals == -128).any()
+    C, S = _spmm(csr, B)
+    want = csr.todense(np.int64) @ B.astype(np.int64)
+    assert np.array_equal(C, want.astype(np.float64))
+    assert np.array_equal(S, np.abs(csr.todense(np.int64)) @ np.abs(B.astype(np.int64)))
+    K = 1000
+    full = synth.csr_from_mask(np.full((2, K), -128, dtype=np.int8), np.ones((2, K), dtype=bool))
+    C, _ = _spmm(full, np.full((K, 3), -128, dtype=np.int8))
+    assert np.all(C == K * 16384.0) and K * 16384 < 2 ** 31
+
+
+def test_int8_conv_equals_integer_im2col_product():
+    rng = np.random.default_rng(8)
+    Wd = rng.integers(-128, 128, size=(5, 4, 3, 3)).astype(np.int8) * (rng.random((5, 4, 3, 3)) < 0.3)
+    X = rng.integers(-128, 128, size=(2, 4, 6, 7)).astype(np.int8)
+    Y, _ = ref.conv3x3(Wd, X)
+    for b in range(2):
+        cols = ref.im2col3x3(X[b]).astype(np.int64)
+        want = Wd.reshape(5, 36).astype(np.int64) @ cols
+        assert np.array_equal(Y[b].reshape(5, 42), want.astype(np.float64))
+
+
 # --------------------------------------------------------------- convolution
 
 def test_conv_all_ones_counts_taps(golden):
