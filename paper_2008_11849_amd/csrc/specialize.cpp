@@ -183,11 +183,12 @@ constexpr int kSgprOffRing = 24, kOffRing = 8; // s[24:31] row-offset literals i
 constexpr int kSgprTap0 = 32;                  // conv: s[32:49] = lane masks of the 9 filter taps
 constexpr int kSgprFull = 50;                  // conv: s[50:51] = all lanes
 constexpr int kSgprImage = 52;                 // batch > 1: workgroup id z = image / matrix of the batch
-constexpr int kSgprValRing = 54, kValRing = 8; // half plans: s[54:61] values of A on their way into v_fma_mix_f32
+constexpr int kSgprValRing = 54, kValRing = 8; // half / int8 plans: s[54:61] values of A on their way into the multiply-add
 constexpr int kNextFreeSgpr = 62;
 constexpr int kVgprOff = 0;                    // byte offset of the lane's column inside a row
 constexpr int kVgprLds = 1;                    // LDS byte address of the lane's 16-byte slot
 constexpr int kVgprT1 = 2, kVgprT2 = 3, kVgprAcc0 = 4;
+constexpr int kVgprOut = kVgprT2;               // byte offset of the lane's column inside a row of C (after the prologue)
 constexpr uint32_t kRsrcWord3 = 0x00020000u;   // raw 32-bit buffer, gfx9 family
 constexpr int kMaxChunkRows = 128;             // B rows per LDS buffer (32 KiB), two buffers
 constexpr int kMaxLdsBytes = 160 * 1024;        // LDS of one gfx950 compute unit, all of it usable by one workgroup
@@ -201,15 +202,18 @@ struct Gen {
     SpecPlan &sp;
     int N, K, D;
     bool half = false;   // B, C and the values of A are IEEE half; sums stay fp32
-    int esz = 4;
-    int val_pos = 0;     // half plans: next slot of the value ring
+    bool int8 = false;   // B and the values of A are int8, C is int32, sums are exact integers
+    int esz = 4;         // bytes of an element of B / X
+    int osz = 4;         // bytes of an element of C / Y
+    int val_pos = 0;     // half / int8 plans: next slot of the value ring
     int vgpr_stage0 = 0, vgpr_ring0 = 0, n_vgpr = 0, lds_bytes = 0;
     int ring_size = 0;               // DIRECT: registers of the operand ring (>= D)
     int slot_bytes = 256;            // K split: bytes of one row's partial sums in the exchange area
     int xchg_rows = 0;               // K split: rows exchanged per phase (all of them if they fit the LDS)
     int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
     Gen(const HostPlan &hp, SpecPlan &s)
-        : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth), half(hp.dtype == SPARSERT_F16), esz(half ? 2 : 4) {}
+        : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth), half(hp.dtype == SPARSERT_F16), int8(hp.dtype == SPARSERT_I8),
+          esz(half ? 2 : int8 ? 1 : 4), osz(half ? 2 : 4) {}
 
     void zero_accs(size_t n) {
         for (size_t i = 0; i < n; ++i) e.line("\tv_mov_b32_e32 v%d, 0", kVgprAcc0 + (int)i);
@@ -220,7 +224,17 @@ struct Gen {
     // register because this encoding takes no literal - and accumulates in fp32.
     void fmas(const std::vector<Term> &terms, int vb) {
         for (const Term &t : terms) {
-            if (!half) {
+            if (int8) {
+                // exact: both factors fit 24 bits; values in -16..64 are inline constants
+                const int32_t a = (int32_t)t.bits;
+                if (a >= -16 && a <= 64) {
+                    e.line("\tv_mad_i32_i24 v%d, %d, v%d, v%d", kVgprAcc0 + t.acc, a, vb, kVgprAcc0 + t.acc);
+                } else {
+                    const int sv = kSgprValRing + (val_pos++ % kValRing);
+                    e.line("\ts_movk_i32 s%d, %d", sv, a);
+                    e.line("\tv_mad_i32_i24 v%d, s%d, v%d, v%d", kVgprAcc0 + t.acc, sv, vb, kVgprAcc0 + t.acc);
+                }
+            } else if (!half) {
                 e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vb);
             } else {
                 const int sv = kSgprValRing + (val_pos++ % kValRing);
@@ -229,7 +243,7 @@ struct Gen {
             }
         }
     }
-    const char *load_op() const { return half ? "buffer_load_short_d16" : "buffer_load_dword"; }
+    const char *load_op() const { return half ? "buffer_load_short_d16" : int8 ? "buffer_load_sbyte" : "buffer_load_dword"; }
     void load_b_row(int k, int vdst, int ring_pos) {
         const int sreg = kSgprOffRing + (ring_pos % kOffRing);
         e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)k * N * esz));
@@ -241,11 +255,11 @@ struct Gen {
         e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
         for (size_t i = 0; i < rows.size(); ++i) {
             const int sreg = kSgprOffRing + ((int)i % kOffRing);
-            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i].first] * N * esz));
+            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i].first] * N * osz));
             // half storage: one rounding to nearest even, at the store
             if (half) e.line("\tv_cvt_f16_f32_e32 v%d, v%d", rows[i].second, rows[i].second);
             e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", half ? "buffer_store_short" : "buffer_store_dword",
-                   rows[i].second, kVgprOff, kRsrcC, kRsrcC + 3, sreg);
+                   rows[i].second, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
         }
     }
 
@@ -260,6 +274,8 @@ struct Gen {
                     uint16_t hb;
                     std::memcpy(&hb, &h.p_vals[(size_t)p * 2], 2);
                     bits = half_bits_to_float_bits(hb);
+                } else if (int8) {
+                    bits = (uint32_t)(int32_t)(int8_t)h.p_vals[(size_t)p];   // the integer value itself
                 } else {
                     std::memcpy(&bits, &h.p_vals[(size_t)p * 4], 4);
                 }
@@ -373,8 +389,8 @@ struct Gen {
                     }
                     for (size_t t = b0; t < b1; ++t) {
                         e.line("\ts_waitcnt lgkmcnt(%d)", (int)(b1 - 1 - t));
-                        e.line("\tv_add_f32_e32 v%d, v%d, v%d", kVgprAcc0 + items[t].first, kVgprAcc0 + items[t].first,
-                               tmp0 + (int)(t - b0));
+                        e.line("\t%s v%d, v%d, v%d", int8 ? "v_add_u32_e32" : "v_add_f32_e32", kVgprAcc0 + items[t].first,
+                               kVgprAcc0 + items[t].first, tmp0 + (int)(t - b0));
                     }
                 }
             }
@@ -497,11 +513,10 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         err = "convolution plans use the DIRECT variant of the generated kernel";
         return SPARSERT_EUNSUPPORTED;
     }
-    if (h.dtype == SPARSERT_I8) { err = "int8 plans run on the row-walk kernel"; return SPARSERT_EUNSUPPORTED; }
-    const bool half = h.dtype == SPARSERT_F16;
-    const int esz = half ? 2 : 4;
-    if (half && opt.spec_mode == SPARSERT_SPEC_LDS) {
-        err = "half-precision plans use the DIRECT variant of the generated kernel";
+    const bool half = h.dtype == SPARSERT_F16, int8 = h.dtype == SPARSERT_I8;
+    const int esz = half ? 2 : int8 ? 1 : 4, osz = half ? 2 : 4;
+    if ((half || int8) && opt.spec_mode == SPARSERT_SPEC_LDS) {
+        err = "half and int8 plans use the DIRECT variant of the generated kernel";
         return SPARSERT_EUNSUPPORTED;
     }
     const int32_t M = h.M, N = h.N;
@@ -593,7 +608,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     Gen gen(h, sp);
     Emitter &e = gen.e;
     const int64_t b_bytes = h.conv ? ((int64_t)h.Cin * N + 2 * (h.W + 1)) * esz : (int64_t)h.K * N * esz;
-    const int64_t c_bytes = (int64_t)M * N * esz;
+    const int64_t c_bytes = (int64_t)M * N * osz;
     // conv: pixel -> (oh, ow) by multiplication with ceil(2^32 / W); verified here for every pixel
     uint32_t magic = 0;
     if (h.conv && h.W > 1) {
@@ -636,7 +651,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\t.text");
     // The symbol carries the problem shape so that kernel traces tell the plans of a model apart.
     char sym[96];
-    snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d%s", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N, half ? "_f16" : "");
+    snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d%s", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N, half ? "_f16" : int8 ? "_i8" : "");
     sp.symbol = sym;
     e.line("\t.protected\t%s", sym);
     e.line("\t.globl\t%s", sym);
@@ -684,7 +699,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\ts_nop 4");
     // lanes without a column redo the tile's first column: loads stay in bounds, nothing is stored
     e.line("\tv_cndmask_b32_e64 v%d, v%d, v%d, s[%d:%d]", kVgprT1, kVgprT2, kVgprT1, kSgprOwns, kSgprOwns + 1);
-    e.line("\tv_lshlrev_b32_e32 v%d, %d, v%d", kVgprOff, half ? 1 : 2, kVgprT1);  // byte offset of the column inside a row
+    e.line("\tv_lshlrev_b32_e32 v%d, %d, v%d", kVgprOut, half ? 1 : 2, kVgprT1);           // byte offset of the column in a row of C
+    e.line("\tv_lshlrev_b32_e32 v%d, %d, v%d", kVgprOff, half ? 1 : int8 ? 0 : 2, kVgprT1);  // ... and in a row of B / X
     // from here on only lanes that own a column are active: idle lanes fetch nothing
     e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
     if (h.conv) {
@@ -728,7 +744,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     }
     if (images) {
         // problem z of the batch: the operand and the result advance by one image / matrix each
-        const int64_t strides[2] = {(h.conv ? (int64_t)h.Cin : (int64_t)h.K) * N * esz, (int64_t)M * N * esz};
+        const int64_t strides[2] = {(h.conv ? (int64_t)h.Cin : (int64_t)h.K) * N * esz, (int64_t)M * N * osz};
         const int bases[2] = {kSgprB, kSgprC};
         for (int i = 0; i < 2; ++i) {
             e.line("\ts_mov_b32 s%d, 0x%llx", kSgprTmp2, (unsigned long long)strides[i]);

@@ -88,7 +88,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
         }
     }
     if (family == SPARSERT_KERNEL_SPEC) cands.clear();
-    if (nnz <= (4 << 20) && family != SPARSERT_KERNEL_ROWS && !i8) {
+    if (nnz <= (4 << 20) && family != SPARSERT_KERNEL_ROWS) {
         const int64_t tiles = (N + 63) / 64;
         for (int r : {1, 2, 4, 8, 16, 24, 48}) {
             if (r > M) continue;
@@ -117,7 +117,7 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
                 cands.push_back(o);
             }
         }
-        if (!conv && !f16 && K >= 256 && (int64_t)M * tiles >= 1024) {
+        if (!conv && !f16 && !i8 && K >= 256 && (int64_t)M * tiles >= 1024) {
             for (int r : {12, 24, 48})
                 for (int w : {4, 8}) {
                     if (((int64_t)M + r - 1) / r < w) continue;

@@ -29,7 +29,10 @@ def test_int8_spmm_is_exact(N):
     csr = synth.int8_csr(77, 130, 0.85, N)
     B = synth.int8_dense(130, N, N + 1)
     want = _want(csr, B)
-    variants = [dict(), dict(vec=1), dict(vec=1, split_threshold=1), dict(split_threshold=7)]
+    variants = [dict(), dict(vec=1), dict(vec=1, split_threshold=1), dict(split_threshold=7),
+                dict(kernel=sp.KERNEL_SPEC, spec_rows=1), dict(kernel=sp.KERNEL_SPEC, spec_rows=9),
+                dict(kernel=sp.KERNEL_SPEC, spec_rows=20, spec_ksplit=4, spec_swizzle=True),
+                dict(kernel=sp.KERNEL_SPEC, spec_rows=77, spec_ksplit=8, spec_depth=3)]
     if N % 4 == 0:
         variants += [dict(vec=4), dict(vec=4, split_threshold=1), dict(vec=4, split_threshold=9)]
     for opts in variants:
@@ -47,7 +50,8 @@ def test_int8_extreme_values_and_empty_rows():
     csr = synth.csr_from_mask(vals, mask)
     B = np.full((K, 68), -128, dtype=np.int8)
     B[:, 1] = 127
-    for opts in (dict(vec=1), dict(vec=4), dict(vec=4, split_threshold=100)):
+    for opts in (dict(vec=1), dict(vec=4), dict(vec=4, split_threshold=100), dict(kernel=sp.KERNEL_SPEC, spec_rows=3),
+                 dict(kernel=sp.KERNEL_SPEC, spec_rows=3, spec_ksplit=8)):
         got, _ = run_spmm(csr, B, **opts)
         assert np.all(got[1] == 0)
         assert np.all(got[0, 0] == K * 16384) and np.all(got[2, 1] == -K * 128 * 127)
@@ -62,8 +66,9 @@ def test_int8_skewed_rows(M, K, N, s):
     q[q == 0] = 1
     csr = synth.CSR(M, K, f.row_ptr, f.col_idx, q)
     B = synth.int8_dense(K, N, 18)
-    got, info = run_spmm(csr, B)
-    assert np.array_equal(got.astype(np.int64), _want(csr, B)), info
+    for opts in (dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=16, spec_ksplit=4)):
+        got, info = run_spmm(csr, B, **opts)
+        assert np.array_equal(got.astype(np.int64), _want(csr, B)), info
 
 
 @pytest.mark.parametrize("Cin,Cout,H,W,batch", [(3, 5, 1, 1, 1), (4, 6, 2, 3, 2), (2, 3, 9, 1, 1), (16, 24, 14, 14, 3),
@@ -74,7 +79,8 @@ def test_int8_conv_is_exact(Cin, Cout, H, W, batch):
     csr = synth.csr_from_mask(Wd.reshape(Cout, -1), Wd.reshape(Cout, -1) != 0)
     X = rng.integers(-128, 128, size=(batch, Cin, H, W)).astype(np.int8)
     want = ref.conv3x3(Wd, X, want_scale=False)[0].astype(np.int64)
-    for opts in (dict(), dict(split_threshold=1)):
+    for opts in (dict(), dict(split_threshold=1), dict(kernel=sp.KERNEL_SPEC, spec_rows=3),
+                 dict(kernel=sp.KERNEL_SPEC, spec_rows=4, spec_ksplit=2)):
         got, info = run_conv(csr, X, Cout, **opts)
         assert got.dtype == np.int32 and info["batch"] == batch
         assert np.array_equal(got.astype(np.int64), want), opts
@@ -84,14 +90,15 @@ def test_int8_batched_spmm_and_tune():
     csr = synth.int8_csr(300, 256, 0.9, 5)
     B = np.stack([synth.int8_dense(256, 512, 6 + i) for i in range(2)])
     want = np.stack([_want(csr, B[i]) for i in range(2)])
-    got, info = run_spmm(csr, B)
-    assert info["batch"] == 2 and np.array_equal(got.astype(np.int64), want)
+    for opts in (dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=24, spec_ksplit=4)):
+        got, info = run_spmm(csr, B, **opts)
+        assert info["batch"] == 2 and np.array_equal(got.astype(np.int64), want)
     dev = torch.device("cuda:0")
     Bd = torch.from_numpy(B[0]).to(dev)
     Cd = torch.zeros((300, 512), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
     plan, report = sp.tune(csr.row_ptr, csr.col_idx, csr.vals, 300, 256, 512, Bd.data_ptr(), Cd.data_ptr(), stream)
-    assert len(report) >= 2 and {r["vec"] for r in report} <= {1, 4}
+    assert len(report) >= 4 and {r["kernel"] for r in report} == {sp.KERNEL_ROWS, sp.KERNEL_SPEC}
     Cd.fill_(POISON)
     sp.spmm(plan, Bd.data_ptr(), Cd.data_ptr(), stream)
     torch.cuda.synchronize()
