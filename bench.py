@@ -34,7 +34,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
-    ap.add_argument("--dtype", default="f32", choices=["f32", "f16"])
+    ap.add_argument("--dtype", default="f32", choices=["f32", "f16", "i8"],
+                    help="storage type; i8: int8 weights and activations, exact int32 results")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cases", action="store_true", help="skip the side table of the other configs")
     ap.add_argument("--kernel", default="tune", choices=["tune", "rows", "spec"],
@@ -61,18 +62,34 @@ class Layer:
         dev = torch.device("cuda:0")
         self.is_conv = case.conv is not None
         self.M, self.K, self.N, self.nnz = csr.M, csr.K, case.N, csr.nnz
-        tdt = torch.float16 if csr.vals.dtype == np.float16 else torch.float32
-        self.esize = 2 if tdt == torch.float16 else 4
+        self.int8 = csr.vals.dtype == np.int8
+        tdt = torch.float16 if csr.vals.dtype == np.float16 else torch.int32 if self.int8 else torch.float32
+        self.esize = 2 if tdt == torch.float16 else 1 if self.int8 else 4       # bytes of an input element
+        self.osize = 2 if tdt == torch.float16 else 4                           # bytes of an output element
+        # dense twin: same storage type; int8 has no dense convolution here and int8 GEMM only through
+        # torch._int_mm, so int8 layers are compared with the half-precision dense kernels (values exact in half)
+        ddt = torch.float16 if self.int8 else tdt
+        self.dense_kind = "f16 (int8 operands widened)" if self.int8 else str(ddt).replace("torch.", "")
         if self.is_conv:
             self.inp = torch.from_numpy(case.X).to(dev)
             self.out = torch.empty((1, csr.M, case.conv[1], case.conv[2]), dtype=tdt, device=dev)
-            self.Wd = torch.from_numpy(case.Wdense).to(dev)
+            self.Wd = torch.from_numpy(case.Wdense).to(dev).to(ddt)
+            self.dense_in = self.inp.to(ddt)
             self.fn = sp.raw.sparsert_conv3x3
         else:
             self.inp = torch.from_numpy(case.B).to(dev)
             self.out = torch.empty((csr.M, case.N), dtype=tdt, device=dev)
-            self.Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
+            self.Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(ddt)
+            self.dense_in = self.inp.to(ddt)
             self.fn = sp.raw.sparsert_spmm
+            if self.int8:
+                try:   # the int8 GEMM of the BLAS library, where this build of torch has it
+                    A8 = torch.from_numpy(csr.todense(np.int8)).to(dev)
+                    torch._int_mm(A8, self.inp)
+                    torch.cuda.synchronize()
+                    self.Ad, self.dense_in, self.dense_kind = A8, self.inp, "int8 (torch._int_mm)"
+                except Exception:
+                    pass
         self.tuned = None
         if fixed is not None:
             self.plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N, conv=case.conv, **fixed)
@@ -98,7 +115,7 @@ class Layer:
         written once, the nonzero stream (8 B per nonzero) and the row pointers read once."""
         e = self.esize
         dense_in = (self.case.conv[0] * self.N if self.is_conv else self.K * self.N) * e
-        return dense_in + self.M * self.N * e + 8 * self.nnz + 4 * (self.M + 1)
+        return dense_in + self.M * self.N * self.osize + 8 * self.nnz + 4 * (self.M + 1)
 
     def launch(self, stream):
         rc = self.fn(self.args[0], self.args[1], self.args[2], stream)
@@ -107,8 +124,10 @@ class Layer:
 
     def dense(self):
         if self.is_conv:
-            return self.torch.nn.functional.conv2d(self.inp, self.Wd, padding=1)
-        return self.torch.matmul(self.Ad, self.inp)
+            return self.torch.nn.functional.conv2d(self.dense_in, self.Wd, padding=1)
+        if self.Ad.dtype == self.torch.int8:
+            return self.torch._int_mm(self.Ad, self.dense_in)
+        return self.torch.matmul(self.Ad, self.dense_in)
 
 
 def time_loop(torch, fn, iters, warmup):
@@ -166,7 +185,7 @@ def cpu_baseline(cases, gpu_outputs):
         else:
             want, scale = ref.spmm(csr.M, csr.K, case.N, csr.row_ptr, csr.col_idx, csr.vals, case.B, threads=threads)
         m = ref.error_metrics(got.reshape(want.shape), want, scale)
-        tol = 2e-2 if got.dtype.itemsize == 2 else 1e-4
+        tol = 2e-2 if got.dtype.itemsize == 2 else 0.0 if got.dtype.kind == "i" else 1e-4   # integer work: exact
         if not (m["componentwise"] <= tol and m["normwise"] <= tol and m["exact_on_zero_scale"]):
             print(f"bench.py: the timed plan of {case.name} disagrees with the oracle: {m}", file=sys.stderr)
             sys.exit(1)
@@ -192,7 +211,7 @@ def main():
         sys.exit(1)
     torch.backends.cuda.matmul.allow_tf32 = False
     torch.backends.cudnn.allow_tf32 = False
-    dt = np.float16 if args.dtype == "f16" else np.float32
+    dt = {"f16": np.float16, "i8": np.int8}.get(args.dtype, np.float32)
     kernel = args.kernel
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -244,7 +263,7 @@ def main():
         ms_dense = time_loop(torch, L.dense, max(50, iters // 10), 10)
         per_layer.append({"layer": L.case.name, "M": L.M, "K": L.K, "N": L.N, "nnz": L.nnz,
                           "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
-                          "dense_us": ms_dense * 1e3, "speedup_vs_dense": ms_dense / ms,
+                          "dense_us": ms_dense * 1e3, "speedup_vs_dense": ms_dense / ms, "dense_kind": L.dense_kind,
                           "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
                                                           "spec_tiles", "spec_ksplit", "spec_swizzle",
                                                           "spec_code_bytes")},

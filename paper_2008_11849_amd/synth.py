@@ -210,7 +210,13 @@ def config(name: str, dtype=np.float32) -> Case:
     c3  : Transformer FC: 3072x768 @ 95 % magnitude-pruned N(0, std 0.02), B 768x1024
     c3t : the transposed projection 768x3072 (independent draw), B 3072x1024
     c4  : 3x3 conv, 256 -> 256 channels, 14x14, pad 1, @ 90 % magnitude-pruned
+
+    dtype int8: the float32 case quantised - weights symmetric per tensor to -127..127 (kept
+    weights that round to zero become +-1, so the pattern is unchanged), activations times 32
+    and clipped to -128..127 (four standard deviations).
     """
+    if np.dtype(dtype) == np.int8:
+        return _quantised(config(name, np.float32))
     if name == "c1":
         s = BASE_SEED + 0
         return Case("c1", uniform_csr(256, 256, 0.90, s, dtype), 1024,
@@ -233,6 +239,33 @@ def config(name: str, dtype=np.float32) -> Case:
         X = normal_dense(256, 14 * 14, s + 1000, dtype).reshape(1, 256, 14, 14)
         return Case("c4", csr, 196, X=X, Wdense=Wd, conv=(256, 14, 14), sparsity=0.90)
     raise KeyError(name)
+
+
+def quantise_weights(w: np.ndarray) -> np.ndarray:
+    """Symmetric per-tensor int8; nonzero inputs stay nonzero."""
+    top = float(np.abs(w).max()) if w.size else 1.0
+    q = np.clip(np.rint(w / (top if top > 0 else 1.0) * 127.0), -127, 127).astype(np.int8)
+    lost = (q == 0) & (w != 0)
+    q[lost] = np.where(w[lost] > 0, 1, -1).astype(np.int8)
+    return q
+
+
+def quantise_activations(x: np.ndarray) -> np.ndarray:
+    return np.clip(np.rint(x * 32.0), -128, 127).astype(np.int8)
+
+
+def _quantised(case: Case) -> Case:
+    csr = case.csr
+    top = np.abs(case.Wdense).max() if case.Wdense is not None else None
+    q = CSR(csr.M, csr.K, csr.row_ptr, csr.col_idx, quantise_weights(csr.vals))
+    Wq = None
+    if case.Wdense is not None:   # same scale as the CSR values: both come from the same tensor
+        assert top == np.abs(csr.vals).max()
+        Wq = quantise_weights(case.Wdense)
+    return Case(case.name, q, case.N,
+                B=None if case.B is None else quantise_activations(case.B),
+                X=None if case.X is None else quantise_activations(case.X),
+                Wdense=Wq, conv=case.conv, sparsity=case.sparsity)
 
 
 def sweep_seed(M, K, N, sparsity, mask_kind, dtype) -> int:
