@@ -1,5 +1,6 @@
 // extern "C" boundary: argument checks, error strings, plan export.
 #include <cstring>
+#include <exception>
 #include <new>
 #include <string>
 
@@ -27,21 +28,18 @@ int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void 
     if (!plan) return fail(SPARSERT_ENOMEM, "out of host memory");
     std::string err;
     int rc;
-    try {
+    try {   // no exception may cross the C boundary
         rc = sparsert::build_host_plan(row_ptr, col_idx, vals, M, K, N, o, plan->host, err);
+        if (rc == SPARSERT_OK && plan->host.kernel == SPARSERT_KERNEL_SPEC)
+            rc = sparsert::build_spec_plan(plan->host, o, err);
+        if (rc == SPARSERT_OK && !o.host_only) {
+            rc = sparsert::upload_plan(plan->host, plan->dev, err);
+            plan->on_device = (rc == SPARSERT_OK);
+        }
     } catch (const std::bad_alloc &) {
         rc = SPARSERT_ENOMEM; err = "out of host memory";
-    }
-    if (rc == SPARSERT_OK && plan->host.kernel == SPARSERT_KERNEL_SPEC) {
-        try {
-            rc = sparsert::build_spec_plan(plan->host, o, err);
-        } catch (const std::bad_alloc &) {
-            rc = SPARSERT_ENOMEM; err = "out of host memory";
-        }
-    }
-    if (rc == SPARSERT_OK && !o.host_only) {
-        rc = sparsert::upload_plan(plan->host, plan->dev, err);
-        plan->on_device = (rc == SPARSERT_OK);
+    } catch (const std::exception &ex) {
+        rc = SPARSERT_EINVAL; err = std::string("internal error: ") + ex.what();
     }
     if (rc != SPARSERT_OK) {
         sparsert::free_device_plan(plan->dev);
@@ -59,6 +57,8 @@ static int check_exec(const sparsert_plan *plan, const void *in, void *outp, boo
     if (!plan->on_device) return fail(SPARSERT_EINVAL, "plan was made with host_only and cannot be executed");
     if ((plan->host.conv != 0) != conv)
         return fail(SPARSERT_EINVAL, conv ? "plan is not a convolution plan" : "plan is a convolution plan; use sparsert_conv3x3");
+    if (!sparsert::on_plan_device(plan->dev))
+        return fail(SPARSERT_EINVAL, "the plan's arrays live on another HIP device than the current one");
     return SPARSERT_OK;
 }
 

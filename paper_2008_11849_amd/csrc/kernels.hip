@@ -268,6 +268,11 @@ static int to_device(const U *src, size_t count, U **dst, std::string &err) {
     return SPARSERT_OK;
 }
 
+bool on_plan_device(const DevicePlan &d) {
+    int dev = -1;
+    return hipGetDevice(&dev) == hipSuccess && dev == d.device;
+}
+
 int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err) {
     HIP_TRY(hipGetDevice(&d.device));
     if (int rc = to_device(h.p_row_ptr.data(), h.p_row_ptr.size(), &d.p_row_ptr, err)) return rc;

@@ -92,6 +92,7 @@ int set_error(int code, const std::string &msg);
 // Device side (kernels.hip).
 int upload_plan(const HostPlan &h, DevicePlan &d, std::string &err);
 void free_device_plan(DevicePlan &d);
+bool on_plan_device(const DevicePlan &d);   // is the plan's device the calling thread's current device?
 int launch_rows(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
                 void *stream, std::string &err);
 int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,

@@ -7,6 +7,8 @@
 
 #include <algorithm>
 #include <cstring>
+#include <exception>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -37,10 +39,10 @@ float time_plan(sparsert_plan *p, bool conv, const void *in, void *out, hipStrea
 
 }  // namespace
 
-extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
-                             int32_t M, int32_t K, int32_t N, const sparsert_options *base,
-                             const void *in_dev, void *out_dev, void *stream,
-                             sparsert_plan **out, sparsert_tune_report *report) {
+static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
+                     int32_t M, int32_t K, int32_t N, const sparsert_options *base,
+                     const void *in_dev, void *out_dev, void *stream,
+                     sparsert_plan **out, sparsert_tune_report *report) {
     if (out) *out = nullptr;
     if (report) std::memset(report, 0, sizeof(*report));
     sparsert_options b;
@@ -197,4 +199,17 @@ extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, con
     }
     *out = best;
     return SPARSERT_OK;
+}
+
+extern "C" int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
+                             int32_t M, int32_t K, int32_t N, const sparsert_options *base,
+                             const void *in_dev, void *out_dev, void *stream,
+                             sparsert_plan **out, sparsert_tune_report *report) {
+    try {   // no exception may cross the C boundary
+        return tune_impl(row_ptr, col_idx, vals, M, K, N, base, in_dev, out_dev, stream, out, report);
+    } catch (const std::bad_alloc &) {
+        return sparsert::set_error(SPARSERT_ENOMEM, "out of host memory while tuning");
+    } catch (const std::exception &ex) {
+        return sparsert::set_error(SPARSERT_EINVAL, std::string("internal error while tuning: ") + ex.what());
+    }
 }
