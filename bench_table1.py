@@ -66,6 +66,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--only", default="", help="comma list of problem tags to run, e.g. t1_p9_90,t3_p3_95")
     ap.add_argument("--batch", type=int, default=1, help="images per call for the Table 3 convolutions (the paper uses 1)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the paper's list: the shape / sparsity sweep (M=K in 1024, 2048; N in 196, 1024, "
+                         "4096; 80, 90, 95, 98 %; uniform masks), effective GFLOP/s and speedup over dense per case")
     ap.add_argument("--markdown", default="", help="also write the results as a markdown summary to this path")
     ap.add_argument("--ablation", action="store_true",
                     help="also time, per problem, the best row-walk (not specialised) plan and the best plan "
@@ -136,7 +139,7 @@ def main():
                 "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit", "spec_swizzle")},
                 **extra}
 
-    for sparsity in (0.90, 0.95):
+    for sparsity in (() if args.sweep else (0.90, 0.95)):
         pct = int(round(sparsity * 100))
         for i, (M, K, N) in enumerate(TABLE1):
             tag = f"t1_p{i + 1}_{pct}"
@@ -167,7 +170,25 @@ def main():
             rows.append(r)
             print(json.dumps(r), file=sys.stderr, flush=True)
 
-    if args.ablation:
+    if args.sweep:
+        for MK in (1024, 2048):
+            for N in (196, 1024, 4096):
+                for sparsity in (0.80, 0.90, 0.95, 0.98):
+                    tag = f"sw_{MK}x{MK}x{N}_{int(round(sparsity * 100))}"
+                    if only and tag not in only:
+                        continue
+                    case = synth.sweep_case(MK, MK, N, sparsity, "uniform", np.float32)
+                    csr = case.csr
+                    B = torch.from_numpy(case.B).to(dev)
+                    C = torch.empty((MK, N), device=dev)
+                    Ad = torch.from_numpy(csr.todense(np.float32)).to(dev)
+                    r = run(tag, csr, N, B, C, lambda: torch.matmul(Ad, B))
+                    r.update(M=MK, K=MK, N=N, sparsity=sparsity, paper_speedup_t4="-")
+                    rows.append(r)
+                    print(json.dumps(r), file=sys.stderr, flush=True)
+                    del Ad, B, C
+
+    if args.ablation and not args.sweep:
         # the suite's weights are uniform; two skewed matrices (Zipf-like row lengths) show what the
         # load balancing is for
         for i, (M, K, N) in enumerate([(1024, 1024, 256), (3072, 768, 1024)]):
@@ -187,7 +208,7 @@ def main():
         return geomean([r["speedup"] for r in rows if r["tag"].startswith(prefix) and r["sparsity"] == s])
 
     ablation = None
-    if args.ablation:
+    if args.ablation and not args.sweep:
         suite = [r for r in rows if not r.get("skewed")]
         skew = [r for r in rows if r.get("skewed")]
         ablation = {"specialised_over_row_walk": geomean([r["rows_only_us"] / r["sparse_us"] for r in suite]),
@@ -197,7 +218,8 @@ def main():
                     "paper": "unrolled code over 10x faster than not unrolled; without load balancing comparable in "
                              "most cases; one fixed parameter choice about 2x slower (Section 4.3)"}
     result = {
-        "workload": "paper Table 1 (SpMM) and Table 3 (3x3 conv) shapes, synthetic magnitude-pruned weights, fp32",
+        "workload": ("shape / sparsity sweep, uniform masks, N(0,1) values, fp32" if args.sweep else
+                     "paper Table 1 (SpMM) and Table 3 (3x3 conv) shapes, synthetic magnitude-pruned weights, fp32"),
         "timing": f"{INNER} launches per HIP graph, 20 replays, HIP events; same for sparse and dense",
         "geomean_speedup_vs_dense": {"table1_90": gm("t1", 0.90), "table1_95": gm("t1", 0.95),
                                      "table3_90": gm("t3", 0.90), "table3_95": gm("t3", 0.95)},
@@ -209,7 +231,24 @@ def main():
         write_markdown(args.markdown, result, " ".join(["python3", "bench_table1.py"] + sys.argv[1:]))
 
 
+def write_sweep_markdown(path, res, command):
+    lines = ["# Shape / sparsity sweep on MI355X, uniform masks, fp32", "",
+             f"command: `{command}` (one MI355X; plans from sparsert_tune; sparse and dense both timed as",
+             f"{INNER} launches per HIP graph, 20 replays, HIP events; effective GFLOP/s = 2 nnz N / t).", "",
+             "| M = K | N | sparsity | sparse us | dense us | speedup | effective GFLOP/s | kernel | R | KS | swizzle |",
+             "|---|---|---|---|---|---|---|---|---|---|---|"]
+    for r in res["problems"]:
+        p = r["plan"]
+        lines.append(f"| {r['M']} | {r['N']} | {r['sparsity']:.2f} | {r['sparse_us']:.2f} | {r['dense_us']:.2f} | "
+                     f"{r['speedup']:.2f} | {r['gflops']:.0f} | {p['kernel']} | {p['spec_rows']} | {p['spec_ksplit']} | "
+                     f"{p['spec_swizzle']} |")
+    with open(path, "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+
 def write_markdown(path, res, command):
+    if res["workload"].startswith("shape"):
+        return write_sweep_markdown(path, res, command)
     g = res["geomean_speedup_vs_dense"]
     fmt = lambda x: "-" if x is None else f"{x:.2f}x"
     lines = ["# Paper's problem list (Table 1 SpMM, Table 3 3x3 conv) on MI355X, synthetic weights, fp32", "",

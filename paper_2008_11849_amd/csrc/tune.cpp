@@ -120,7 +120,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
             }
         }
         if (!conv && !f16 && !i8 && K >= 256 && (int64_t)M * tiles >= 1024) {
-            for (int r : {12, 24, 48})
+            for (int r : {12, 24, 48, 96})
                 for (int w : {4, 8}) {
                     if (((int64_t)M + r - 1) / r < w) continue;
                     sparsert_options o = b;
@@ -132,18 +132,29 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     }
 
     // Assembling a candidate costs about 12 s per million nonzeros, so large matrices get a
-    // shorter list: the configurations that win on the large layers measured so far.
+    // shorter list of generated kernels: those whose launch gives every SIMD of the chip two to
+    // eight waves, the ones with the most rows per block first (fewest fetches of B).
     if (nnz > (256 << 10)) {
-        const bool tiny = nnz > (1 << 20);
-        auto keep = [&](const sparsert_options &o) {
-            if (o.kernel != SPARSERT_KERNEL_SPEC) return true;
-            if (o.spec_mode == SPARSERT_SPEC_LDS) return !tiny && o.spec_rows == 24 && o.spec_tiles == 8;
-            if (o.spec_ksplit > 1)
-                return (o.spec_rows == 96 && o.spec_ksplit == 4) || (!tiny && o.spec_rows == 48 && o.spec_ksplit == 8);
-            return o.spec_tiles == 4 && (o.spec_rows == 48 || (!tiny && (o.spec_rows == 8 || o.spec_rows == 24)));
+        const size_t budget = nnz > (1 << 20) ? 3 : 6;
+        const int64_t tiles = (N + 63) / 64;
+        auto waves_of = [&](const sparsert_options &o) -> int64_t {
+            const int64_t blocks = (M + o.spec_rows - 1) / o.spec_rows;
+            return blocks * tiles * (o.spec_ksplit > 1 ? o.spec_ksplit : 1);   // DIRECT and LDS: one wave per block and tile
         };
-        cands.erase(std::remove_if(cands.begin(), cands.end(), [&](const sparsert_options &o) { return !keep(o); }),
-                    cands.end());
+        std::vector<sparsert_options> rows_family, spec_family;
+        for (const sparsert_options &o : cands) (o.kernel == SPARSERT_KERNEL_SPEC ? spec_family : rows_family).push_back(o);
+        auto in_range = [&](const sparsert_options &o) { const int64_t w = waves_of(o); return w >= 2048 && w <= 8192; };
+        std::stable_sort(spec_family.begin(), spec_family.end(), [&](const sparsert_options &a, const sparsert_options &b) {
+            if (in_range(a) != in_range(b)) return in_range(a);
+            return a.spec_rows > b.spec_rows;
+        });
+        // one configuration per (rows, split) pair is enough here: drop the T = 2 twins of T = 4
+        spec_family.erase(std::remove_if(spec_family.begin(), spec_family.end(), [](const sparsert_options &o) {
+                              return o.spec_mode == SPARSERT_SPEC_DIRECT && o.spec_ksplit <= 1 && o.spec_tiles == 2;
+                          }), spec_family.end());
+        if (spec_family.size() > budget) spec_family.resize(budget);
+        cands = rows_family;
+        cands.insert(cands.end(), spec_family.begin(), spec_family.end());
     }
 
     float best_us = time_plan(best, conv, in_dev, out_dev, s, e0, e1, launches, repeats);
