@@ -122,6 +122,30 @@ class Layer:
         if rc != 0:
             raise RuntimeError(self.sp.last_error())
 
+    def cold_us(self, iters=200, footprint=640 << 20):
+        """Microseconds per launch when every launch works on operands no cache holds: the input
+        and output rotate through enough copies to exceed twice the 256 MB memory-side cache
+        (the plan - weights, code - stays warm, as it does in an inference loop)."""
+        torch = self.torch
+        per_set = self.inp.numel() * self.inp.element_size() + self.out.numel() * self.out.element_size()
+        n = max(2, -(-footprint // per_set))
+        ins = [self.inp.clone() for _ in range(n)]
+        outs = [torch.empty_like(self.out) for _ in range(n)]
+        args = [(ctypes.c_void_p(i.data_ptr()), ctypes.c_void_p(o.data_ptr())) for i, o in zip(ins, outs)]
+        st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        for a, b in args:
+            self.fn(self.args[0], a, b, st)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for k in range(iters):
+            a, b = args[k % n]
+            if self.fn(self.args[0], a, b, st) != 0:
+                raise RuntimeError(self.sp.last_error())
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e3, n
+
     def dense(self):
         if self.is_conv:
             return self.torch.nn.functional.conv2d(self.dense_in, self.Wd, padding=1)
@@ -261,8 +285,10 @@ def main():
     for L in layers:
         ms = time_loop(torch, lambda L=L: L.launch(stream), iters, 50)
         ms_dense = time_loop(torch, L.dense, max(50, iters // 10), 10)
+        cold, n_sets = L.cold_us()
         per_layer.append({"layer": L.case.name, "M": L.M, "K": L.K, "N": L.N, "nnz": L.nnz,
                           "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
+                          "cold_us": cold, "cold_operand_sets": n_sets,
                           "dense_us": ms_dense * 1e3, "speedup_vs_dense": ms_dense / ms, "dense_kind": L.dense_kind,
                           "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
                                                           "spec_tiles", "spec_ksplit", "spec_swizzle",
@@ -296,6 +322,9 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(tag),
                      "kernel": "sparsert_spec_<M>x<K>x<N> (generated per layer) / sparsert::rows_kernel; see layers[].plan.kernel: 2 / 1",
                      "avg_launch_us": kernel_ms * 1e3,
+                     "avg_launch_us_cold_operands": sum(p["cold_us"] for p in per_layer) / len(per_layer),
+                     "frac_cold_operands": alg_bytes / (sum(p["cold_us"] for p in per_layer) / len(per_layer) * 1e-6) / 1e9
+                                           / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "alu_frac_of_fp32_vector_peak":
                          flops_step / len(layers) / (kernel_ms * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TF},
