@@ -361,6 +361,34 @@ def test_launches_replay_from_a_hip_graph():
         p.destroy()
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_small_cases_all_executors(seed):
+    """Seeded random shapes, densities, storage types and plan options; small integers, so every
+    executor must reproduce the oracle bit for bit whatever its summation order."""
+    rng = np.random.default_rng(1000 + seed)
+    for _ in range(6):
+        M, K, N = int(rng.integers(1, 90)), int(rng.integers(1, 200)), int(rng.integers(1, 300))
+        dtype = [np.float32, np.float16, np.int8][int(rng.integers(0, 3))]
+        density = float(rng.choice([0.02, 0.1, 0.4, 1.0]))
+        mask = rng.random((M, K)) < density
+        vals = (rng.integers(1, 4, size=(M, K)) * rng.choice([-1, 1], size=(M, K))).astype(dtype)
+        csr = synth.csr_from_mask(vals, mask)
+        B = rng.integers(-4, 5, size=(K, N)).astype(dtype)
+        want = _oracle(csr, B)[0]
+        assert np.abs(want).max() <= 2048
+        rows = int(rng.integers(1, 60))
+        ks = int(rng.choice([0, 2, 4, 8]))
+        variants = [dict(), dict(split_threshold=int(rng.integers(1, 9))),
+                    dict(kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_ksplit=ks, spec_swizzle=bool(rng.integers(0, 2)),
+                         spec_depth=int(rng.integers(1, 20)), natural_order=bool(rng.integers(0, 2)))]
+        if dtype == np.float32:
+            variants.append(dict(kernel=sp.KERNEL_SPEC, spec_rows=rows, spec_mode=sp.SPEC_LDS,
+                                 spec_tiles=int(rng.choice([1, 2, 4, 8]))))
+        for opts in variants:
+            got, _ = run_spmm(csr, B, **opts)
+            assert np.array_equal(got.astype(np.float64), want), (M, K, N, np.dtype(dtype).name, density, opts)
+
+
 NATURAL = [dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=9), dict(kernel=sp.KERNEL_SPEC, spec_rows=12, spec_mode=sp.SPEC_LDS),
            dict(kernel=sp.KERNEL_SPEC, spec_rows=20, spec_ksplit=4)]
 

@@ -1,0 +1,86 @@
+"""Property tests of the inspector (host only): for random small matrices, storage types and
+options the exported plan equals the NumPy statement of the plan specification byte for byte,
+and un-permuting the plan gives back the input."""
+import numpy as np
+import pytest
+from hypothesis import HealthCheck, given, settings, strategies as st
+
+from oracle import plan_ref
+from paper_2008_11849_amd import sparsert as sp
+from paper_2008_11849_amd import synth
+
+FIELDS = {"row_nnz": sp.FIELD_ROW_NNZ, "hist": sp.FIELD_HIST, "perm": sp.FIELD_PERM,
+          "inv_perm": sp.FIELD_INV_PERM, "p_row_ptr": sp.FIELD_P_ROW_PTR, "p_col_idx": sp.FIELD_P_COL_IDX,
+          "p_vals": sp.FIELD_P_VALS, "bins": sp.FIELD_BINS, "stream": sp.FIELD_STREAM,
+          "conv_seg": sp.FIELD_CONV_SEG, "segments": sp.FIELD_SEGMENTS}
+
+
+@st.composite
+def problems(draw):
+    M = draw(st.integers(1, 40))
+    K = draw(st.integers(1, 48))
+    N = draw(st.integers(1, 140))
+    density = draw(st.sampled_from([0.0, 0.05, 0.3, 0.9, 1.0]))
+    seed = draw(st.integers(0, 2 ** 31 - 1))
+    dtype = draw(st.sampled_from([np.float32, np.float16, np.int8]))
+    rng = np.random.default_rng(seed)
+    mask = rng.random((M, K)) < density
+    if dtype == np.int8:
+        vals = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    else:
+        vals = rng.standard_normal((M, K)).astype(dtype)
+    csr = synth.csr_from_mask(vals, mask)
+    allowed = [v for v in ((1, 4) if dtype == np.int8 else (1, 2, 4, 8) if dtype == np.float16 else (1, 2, 4)) if N % v == 0]
+    vec = draw(st.sampled_from([0] + allowed))
+    thr = draw(st.sampled_from([0, 1, 3, 1000]))
+    natural = draw(st.booleans())
+    return csr, N, vec, thr, natural
+
+
+@settings(max_examples=120, deadline=None, suppress_health_check=[HealthCheck.too_slow])
+@given(problems())
+def test_plan_equals_the_numpy_specification(problem):
+    csr, N, vec, thr, natural = problem
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, host_only=True,
+                      vec=vec, split_threshold=thr, natural_order=natural)
+    want = plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, vec=vec,
+                         split_threshold=thr, natural_order=natural)
+    info = plan.info()
+    for k, v in want["info"].items():
+        assert info[k] == v, (k, info[k], v)
+    for name, fid in FIELDS.items():
+        assert plan.export(fid).tobytes() == want[name].tobytes(), name
+    # un-permuting gives the input back, values bit for bit
+    perm, prp = plan.export(sp.FIELD_PERM), plan.export(sp.FIELD_P_ROW_PTR)
+    pci, pv = plan.export(sp.FIELD_P_COL_IDX), plan.export(sp.FIELD_P_VALS)
+    assert sorted(perm.tolist()) == list(range(csr.M))
+    for slot in range(csr.M):
+        r = perm[slot]
+        a, b = csr.row_ptr[r], csr.row_ptr[r + 1]
+        assert np.array_equal(pci[prp[slot]:prp[slot + 1]], csr.col_idx[a:b])
+        assert pv[prp[slot]:prp[slot + 1]].tobytes() == csr.vals[a:b].tobytes()
+    plan.destroy()
+
+
+@settings(max_examples=40, deadline=None, suppress_health_check=[HealthCheck.too_slow])
+@given(st.integers(1, 60), st.integers(1, 64), st.integers(0, 2 ** 31 - 1), st.integers(1, 70), st.booleans())
+def test_generated_kernel_groups_are_balanced_partitions(M, K, seed, rows, swizzle):
+    rng = np.random.default_rng(seed)
+    mask = rng.random((M, K)) < 0.2
+    csr = synth.csr_from_mask(rng.standard_normal((M, K)).astype(np.float32), mask)
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, M, K, 70, host_only=True, kernel=sp.KERNEL_SPEC,
+                      spec_rows=rows, spec_swizzle=swizzle, spec_depth=2)
+    groups = plan.export(sp.FIELD_SPEC_GROUPS)
+    info = plan.info()
+    R = min(rows, M)
+    assert info["spec_groups"] == -(-M // R) and groups.min() >= 0 and groups.max() < info["spec_groups"]
+    assert np.bincount(groups, minlength=info["spec_groups"]).max() <= R
+    nn = np.diff(plan.export(sp.FIELD_P_ROW_PTR))
+    per_block = np.bincount(groups, weights=nn, minlength=info["spec_groups"])
+    assert per_block.max() - per_block.min() <= max(1, nn.max())     # within one row's worth
+    if swizzle:
+        want = plan_ref.spec_groups_swizzled(plan.export(sp.FIELD_P_ROW_PTR), plan.export(sp.FIELD_P_COL_IDX), M, K, rows)
+    else:
+        want = plan_ref.spec_groups(M, rows)
+    assert groups.tobytes() == want.tobytes()
+    plan.destroy()
