@@ -98,7 +98,10 @@ typedef struct sparsert_options {
     int32_t spec_swizzle;    /* SPARSERT_KERNEL_SPEC: 1 = rows are dealt to code blocks by column-pattern
                                 similarity (the row swizzle the paper proposes as future work,
                                 Section 5), so a block touches fewer rows of B; 0 = serpentine deal */
-    int32_t reserved[2];     /* must be zero */
+    int32_t spec_vec;        /* SPARSERT_KERNEL_SPEC, DIRECT, SpMM: columns of C per lane; 0/1, or the 2 halves
+                                (half plans) / 4 int8 (int8 plans) that share the dword a lane loads,
+                                which halves / quarters the fetches per column; N must be a multiple */
+    int32_t reserved[1];     /* must be zero */
 } sparsert_options;
 
 /*
@@ -186,7 +189,7 @@ int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, 
  */
 #define SPARSERT_TUNE_MAX 64
 typedef struct sparsert_tune_entry {
-    int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles, spec_ksplit, spec_lanes, spec_swizzle;
+    int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles, spec_ksplit, spec_lanes, spec_swizzle, spec_vec;
     float microseconds; /* per launch; negative if the candidate failed */
 } sparsert_tune_entry;
 typedef struct sparsert_tune_report {
@@ -249,6 +252,7 @@ enum {
     SPARSERT_INFO_SPEC_LANES,     /* SPEC plans: lanes per column tile in use (balanced, <= spec_lanes) */
     SPARSERT_INFO_SPEC_SWIZZLE,   /* SPEC plans: 1 if blocks were formed by similarity */
     SPARSERT_INFO_BATCH,          /* problems per call (>= 1) */
+    SPARSERT_INFO_SPEC_VEC,       /* SPEC plans: columns per lane */
     SPARSERT_INFO_COUNT = 32      /* remaining entries are zero */
 };
 

@@ -37,6 +37,7 @@ struct SpecPlan {
     int32_t tiles_per_wg = 4;   // waves per workgroup
     std::string symbol;         // kernel symbol inside the code object
     int32_t swizzle = 0;        // blocks formed by column-pattern similarity
+    int32_t vec = 1;            // columns per lane (2 halves or 4 int8 packed in a dword)
     int32_t mode = 0;           // sparsert_spec_mode
     int32_t n_blocks = 0;       // code blocks (n_groups, padded to a multiple of the waves in LDS mode)
     int32_t lds_bytes = 0;

@@ -206,6 +206,8 @@ struct Gen {
     int esz = 4;         // bytes of an element of B / X
     int osz = 4;         // bytes of an element of C / Y
     int val_pos = 0;     // half / int8 plans: next slot of the value ring
+    int V = 1;           // columns per lane: 2 halves or 4 int8 packed in the dword a lane loads
+    int vgpr_unpack0 = 0;  // int8, V = 4: four registers holding the sign-extended bytes of the current operand
     int vgpr_stage0 = 0, vgpr_ring0 = 0, n_vgpr = 0, lds_bytes = 0;
     int ring_size = 0;               // DIRECT: registers of the operand ring (>= D)
     int slot_bytes = 256;            // K split: bytes of one row's partial sums in the exchange area
@@ -216,50 +218,68 @@ struct Gen {
           esz(half ? 2 : int8 ? 1 : 4), osz(half ? 2 : 4) {}
 
     void zero_accs(size_t n) {
-        for (size_t i = 0; i < n; ++i) e.line("\tv_mov_b32_e32 v%d, 0", kVgprAcc0 + (int)i);
+        for (size_t i = 0; i < n * (size_t)V; ++i) e.line("\tv_mov_b32_e32 v%d, 0", kVgprAcc0 + (int)i);
     }
     // fp32: the value of A is a literal of the multiply-add.  Half storage: the operand sits in
     // the low half of vb and v_fma_mix_f32 widens it on the fly (exact), multiplies by the
     // value - widened to fp32 at generation time, exact as well, and moved through a scalar
     // register because this encoding takes no literal - and accumulates in fp32.
+    int acc_reg(int row, int j = 0) const { return kVgprAcc0 + row * V + j; }
     void fmas(const std::vector<Term> &terms, int vb) {
+        if (terms.empty()) return;
+        if (int8 && V == 4)   // the four packed operands, sign-extended once per fetched row of B
+            for (int j = 0; j < 4; ++j) e.line("\tv_bfe_i32 v%d, v%d, %d, 8", vgpr_unpack0 + j, vb, 8 * j);
         for (const Term &t : terms) {
             if (int8) {
                 // exact: both factors fit 24 bits; values in -16..64 are inline constants
                 const int32_t a = (int32_t)t.bits;
+                char src[16];
                 if (a >= -16 && a <= 64) {
-                    e.line("\tv_mad_i32_i24 v%d, %d, v%d, v%d", kVgprAcc0 + t.acc, a, vb, kVgprAcc0 + t.acc);
+                    snprintf(src, sizeof(src), "%d", a);
                 } else {
                     const int sv = kSgprValRing + (val_pos++ % kValRing);
                     e.line("\ts_movk_i32 s%d, %d", sv, a);
-                    e.line("\tv_mad_i32_i24 v%d, s%d, v%d, v%d", kVgprAcc0 + t.acc, sv, vb, kVgprAcc0 + t.acc);
+                    snprintf(src, sizeof(src), "s%d", sv);
                 }
+                for (int j = 0; j < V; ++j)
+                    e.line("\tv_mad_i32_i24 v%d, %s, v%d, v%d", acc_reg(t.acc, j), src, V == 4 ? vgpr_unpack0 + j : vb,
+                           acc_reg(t.acc, j));
             } else if (!half) {
-                e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", kVgprAcc0 + t.acc, t.bits, vb);
+                e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", acc_reg(t.acc), t.bits, vb);
             } else {
                 const int sv = kSgprValRing + (val_pos++ % kValRing);
                 e.line("\ts_mov_b32 s%d, 0x%08x", sv, t.bits);
-                e.line("\tv_fma_mix_f32 v%d, s%d, v%d, v%d op_sel_hi:[0,1,0]", kVgprAcc0 + t.acc, sv, vb, kVgprAcc0 + t.acc);
+                for (int j = 0; j < V; ++j)   // V = 2: the low and the high half of the dword are adjacent columns
+                    e.line("\tv_fma_mix_f32 v%d, s%d, v%d, v%d op_sel:[0,%d,0] op_sel_hi:[0,1,0]", acc_reg(t.acc, j), sv, vb,
+                           acc_reg(t.acc, j), j);
             }
         }
     }
-    const char *load_op() const { return half ? "buffer_load_short_d16" : int8 ? "buffer_load_sbyte" : "buffer_load_dword"; }
+    const char *load_op() const {
+        return V > 1 ? "buffer_load_dword" : half ? "buffer_load_short_d16" : int8 ? "buffer_load_sbyte" : "buffer_load_dword";
+    }
     void load_b_row(int k, int vdst, int ring_pos) {
         const int sreg = kSgprOffRing + (ring_pos % kOffRing);
         e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)k * N * esz));
         e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", load_op(), vdst, kVgprOff, kRsrcB, kRsrcB + 3, sreg);
     }
-    // (slot of the permuted CSR, accumulator register) pairs: one row of C each
+    // (slot of the permuted CSR, first accumulator register of the row) pairs: one row of C each
     void stores(const std::vector<std::pair<int32_t, int>> &rows) {
         if (rows.empty()) return;
         e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
         for (size_t i = 0; i < rows.size(); ++i) {
-            const int sreg = kSgprOffRing + ((int)i % kOffRing);
+            const int sreg = kSgprOffRing + ((int)i % kOffRing), r = rows[i].second;
             e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i].first] * N * osz));
-            // half storage: one rounding to nearest even, at the store
-            if (half) e.line("\tv_cvt_f16_f32_e32 v%d, v%d", rows[i].second, rows[i].second);
-            e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", half ? "buffer_store_short" : "buffer_store_dword",
-                   rows[i].second, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
+            const char *op = "buffer_store_dword";
+            if (half) {   // one rounding to nearest even, at the store
+                for (int j = 0; j < V; ++j) e.line("\tv_cvt_f16_f32_e32 v%d, v%d", r + j, r + j);
+                if (V == 2) e.line("\tv_pack_b32_f16 v%d, v%d, v%d", r, r, r + 1);
+                else op = "buffer_store_short";
+            }
+            if (int8 && V == 4)
+                e.line("\tbuffer_store_dwordx4 v[%d:%d], v%d, s[%d:%d], s%d offen", r, r + 3, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
+            else
+                e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", op, r, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
         }
     }
 
@@ -365,32 +385,37 @@ struct Gen {
             const int tmp0 = base0 + std::max(n_base, 1);
             const int batch = std::max(1, std::min(12, ring_size - std::max(n_base, 1)));
             std::vector<std::pair<int32_t, int>> mine;
+            const int lane_bytes = slot_bytes / V;   // column j of a row sits j * lane_bytes into the row's slot
             for (int r0 = 0; r0 < nr; r0 += c) {
                 const int r1 = std::min(nr, r0 + c);
                 if (r0 > 0) e.line("\ts_barrier");   // every wave has read the previous phase
                 for (int i = r0; i < r1; ++i)
                     if (i % parts != part)
-                        e.line("\tds_write_b32 v%d, v%d offset:%d", base_of(slot(i, part)), kVgprAcc0 + i,
-                               slot(i, part) & 65535);
+                        for (int j = 0; j < V; ++j) {
+                            const int off = slot(i, part) + j * lane_bytes;
+                            e.line("\tds_write_b32 v%d, v%d offset:%d", base_of(off), acc_reg(i, j), off & 65535);
+                        }
                 e.line("\ts_waitcnt lgkmcnt(0)");
                 e.line("\ts_barrier");
-                std::vector<std::pair<int, int>> items;  // (row, source wave) in the order they are added
+                struct Item { int row, j, src; };
+                std::vector<Item> items;  // in the order they are added
                 for (int i = r0; i < r1; ++i) {
                     if (i % parts != part) continue;
-                    mine.push_back({rows[i], kVgprAcc0 + i});
+                    mine.push_back({rows[i], acc_reg(i)});
                     for (int q = 0; q < parts; ++q)
-                        if (q != part) items.push_back({i, q});
+                        if (q != part)
+                            for (int j = 0; j < V; ++j) items.push_back({i, j, q});
                 }
                 for (size_t b0 = 0; b0 < items.size(); b0 += batch) {
                     const size_t b1 = std::min(items.size(), b0 + batch);
                     for (size_t t = b0; t < b1; ++t) {
-                        const int off = slot(items[t].first, items[t].second);
+                        const int off = slot(items[t].row, items[t].src) + items[t].j * lane_bytes;
                         e.line("\tds_read_b32 v%d, v%d offset:%d", tmp0 + (int)(t - b0), base_of(off), off & 65535);
                     }
                     for (size_t t = b0; t < b1; ++t) {
+                        const int r = acc_reg(items[t].row, items[t].j);
                         e.line("\ts_waitcnt lgkmcnt(%d)", (int)(b1 - 1 - t));
-                        e.line("\t%s v%d, v%d, v%d", int8 ? "v_add_u32_e32" : "v_add_f32_e32", kVgprAcc0 + items[t].first,
-                               kVgprAcc0 + items[t].first, tmp0 + (int)(t - b0));
+                        e.line("\t%s v%d, v%d, v%d", int8 ? "v_add_u32_e32" : "v_add_f32_e32", r, r, tmp0 + (int)(t - b0));
                     }
                 }
             }
@@ -399,7 +424,7 @@ struct Gen {
             return nc;
         }
         std::vector<std::pair<int32_t, int>> all;
-        for (size_t i = 0; i < rows.size(); ++i) all.push_back({rows[i], kVgprAcc0 + (int)i});
+        for (size_t i = 0; i < rows.size(); ++i) all.push_back({rows[i], acc_reg((int)i)});
         stores(all);
         e.line("\ts_endpgm");
         return nc;
@@ -525,8 +550,15 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     // Column tiling with one column per lane, balanced tails (same rule as the row-walk plan at V = 1).
     const int max_lanes = opt.spec_lanes ? opt.spec_lanes : kWave;
     if (lds && max_lanes != kWave) { err = "spec_lanes applies to the DIRECT variant"; return SPARSERT_EINVAL; }
-    sp.n_tiles = (N + max_lanes - 1) / max_lanes;
-    sp.lanes_per_tile = (N + sp.n_tiles - 1) / sp.n_tiles;
+    // Columns per lane: 1, or the 2 halves / 4 int8 that share the dword a lane loads (SpMM only).
+    const int V = opt.spec_vec ? opt.spec_vec : 1;
+    if (!(V == 1 || (V == 2 && half) || (V == 4 && int8))) { err = "spec_vec must be 0/1, 2 for half plans or 4 for int8 plans"; return SPARSERT_EINVAL; }
+    if (V > 1 && (h.conv || lds)) { err = "spec_vec > 1 applies to SpMM plans of the DIRECT variant"; return SPARSERT_EINVAL; }
+    if (N % V) { err = "N must be a multiple of spec_vec"; return SPARSERT_EINVAL; }
+    sp.vec = V;
+    const int32_t nvc = N / V;   // vector columns
+    sp.n_tiles = (nvc + max_lanes - 1) / max_lanes;
+    sp.lanes_per_tile = (nvc + sp.n_tiles - 1) / sp.n_tiles;
     sp.tiles_per_wg = opt.spec_tiles ? opt.spec_tiles : 4;
     sp.ksplit = opt.spec_ksplit ? opt.spec_ksplit : 1;
     if (sp.ksplit != 1 && sp.ksplit != 2 && sp.ksplit != 4 && sp.ksplit != 8) { err = "spec_ksplit must be 0,1,2,4,8"; return SPARSERT_EINVAL; }
@@ -632,11 +664,13 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         const int n_chunks = (h.K + kChunkRows - 1) / kChunkRows;
         gen.lds_bytes = (n_chunks > 1 ? 2 : 1) * kChunkRows * 256;
     } else {
-        gen.vgpr_ring0 = kVgprAcc0 + max_rows;
+        gen.V = V;
+        gen.vgpr_ring0 = kVgprAcc0 + max_rows * V;
         gen.ring_size = KS > 1 ? std::max(D, 8) : D;   // the K-split exchange borrows the ring
-        gen.n_vgpr = gen.vgpr_ring0 + gen.ring_size;
+        gen.vgpr_unpack0 = gen.vgpr_ring0 + gen.ring_size;
+        gen.n_vgpr = gen.vgpr_unpack0 + (int8 && V == 4 ? 4 : 0);
         if (KS > 1) {
-            gen.slot_bytes = 4 * max_lanes;   // lane l of a wave keeps its partial at byte 4*l of the slot
+            gen.slot_bytes = 4 * V * max_lanes;   // a row's slot: V runs of max_lanes floats, lane l at byte 4*l of each
             gen.xchg_rows = std::min(max_rows, kMaxLdsBytes / ((KS - 1) * gen.slot_bytes));
             gen.lds_bytes = (KS - 1) * gen.xchg_rows * gen.slot_bytes;
             if (gen.lds_bytes == 0) gen.lds_bytes = 256;
@@ -651,7 +685,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\t.text");
     // The symbol carries the problem shape so that kernel traces tell the plans of a model apart.
     char sym[96];
-    snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d%s", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N, half ? "_f16" : int8 ? "_i8" : "");
+    snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d%s", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N,
+             half ? (V == 2 ? "_f16x2" : "_f16") : int8 ? (V == 4 ? "_i8x4" : "_i8") : "");
     sp.symbol = sym;
     e.line("\t.protected\t%s", sym);
     e.line("\t.globl\t%s", sym);
@@ -690,7 +725,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     }
     e.line("\ts_mul_i32 s%d, s%d, %d", kSgprTmp, kSgprTile, sp.lanes_per_tile);  // first column of the tile
     e.line("\tv_add_u32_e32 v%d, s%d, v%d", kVgprT1, kSgprTmp, kVgprOff);        // this lane's column
-    e.line("\ts_mov_b32 s%d, %d", kSgprTmp2, N);
+    e.line("\ts_mov_b32 s%d, %d", kSgprTmp2, nvc);
     e.line("\tv_cmp_gt_u32_e32 vcc, %d, v%d", sp.lanes_per_tile, kVgprOff);     // lane < lanes_per_tile
     e.line("\tv_cmp_gt_u32_e64 s[%d:%d], s%d, v%d", kSgprOwns, kSgprOwns + 1, kSgprTmp2, kVgprT1);  // column < N
     e.line("\ts_nop 4");
@@ -699,8 +734,9 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\ts_nop 4");
     // lanes without a column redo the tile's first column: loads stay in bounds, nothing is stored
     e.line("\tv_cndmask_b32_e64 v%d, v%d, v%d, s[%d:%d]", kVgprT1, kVgprT2, kVgprT1, kSgprOwns, kSgprOwns + 1);
-    e.line("\tv_lshlrev_b32_e32 v%d, %d, v%d", kVgprOut, half ? 1 : 2, kVgprT1);           // byte offset of the column in a row of C
-    e.line("\tv_lshlrev_b32_e32 v%d, %d, v%d", kVgprOff, half ? 1 : int8 ? 0 : 2, kVgprT1);  // ... and in a row of B / X
+    auto log2i = [](int x) { int l = 0; while ((1 << l) < x) ++l; return l; };
+    e.line("\tv_lshlrev_b32_e32 v%d, %d, v%d", kVgprOut, log2i(V * osz), kVgprT1);   // byte offset of the lane's column(s) in a row of C
+    e.line("\tv_lshlrev_b32_e32 v%d, %d, v%d", kVgprOff, log2i(V * esz), kVgprT1);   // ... and in a row of B / X
     // from here on only lanes that own a column are active: idle lanes fetch nothing
     e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
     if (h.conv) {

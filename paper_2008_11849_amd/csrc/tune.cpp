@@ -48,7 +48,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     sparsert_options b;
     if (base) b = *base; else std::memset(&b, 0, sizeof(b));
     b.host_only = 0;
-    b.vec = b.split_threshold = b.spec_rows = b.spec_depth = b.spec_tiles = b.spec_mode = b.spec_ksplit = b.spec_lanes = b.spec_swizzle = 0;
+    b.vec = b.split_threshold = b.spec_rows = b.spec_depth = b.spec_tiles = b.spec_mode = b.spec_ksplit = b.spec_lanes = b.spec_swizzle = b.spec_vec = 0;
     // First candidate: the inspector's own choice.  It also validates every argument.
     sparsert_plan *best = nullptr;
     {
@@ -92,33 +92,42 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     if (family == SPARSERT_KERNEL_SPEC) cands.clear();
     if (nnz <= (4 << 20) && family != SPARSERT_KERNEL_ROWS) {
         const int64_t tiles = (N + 63) / 64;
-        for (int r : {1, 2, 4, 8, 16, 24, 48}) {
-            if (r > M) continue;
-            const int64_t groups = (M + r - 1) / r;
-            if (r > 1 && groups * tiles < 256) continue;   // too few waves to be worth assembling
-            if (groups > 8192) continue;
-            for (int t : {2, 4}) {
-                sparsert_options o = b;
-                o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
-                o.spec_rows = r; o.spec_tiles = t;
-                cands.push_back(o);
+        // DIRECT and K-split candidates at V columns per lane (V > 1: the halves / int8 packed in one dword)
+        auto add_direct = [&](int V) {
+            const int64_t vtiles = (N / V + 63) / 64;
+            const int max_rows = 192 / V;   // accumulator registers
+            for (int r : {1, 2, 4, 8, 16, 24, 48}) {
+                if (r > M || r > max_rows) continue;
+                const int64_t groups = (M + r - 1) / r;
+                if (r > 1 && groups * vtiles < 256) continue;   // too few waves to be worth assembling
+                if (groups > 8192) continue;
+                for (int t : {2, 4}) {
+                    if (V > 1 && t == 2) continue;
+                    sparsert_options o = b;
+                    o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
+                    o.spec_rows = r; o.spec_tiles = t; o.spec_vec = V;
+                    cands.push_back(o);
+                }
             }
-        }
-        if (K >= 512) {   // long reduction axis: split it over the waves of a workgroup
-            const int rk[][2] = {{1, 8}, {2, 8}, {4, 8}, {8, 8}, {16, 8}, {24, 8}, {32, 8}, {48, 8}, {64, 8},
-                                 {1, 4}, {2, 4}, {4, 4}, {8, 4}, {16, 4}, {32, 4}, {48, 4}, {64, 4}, {96, 4},
-                                 {64, 2}, {96, 2}};
-            for (auto &c : rk) {
-                // worth timing with at least two waves for every SIMD of the chip, but not with
-                // more than sixteen (the blocks are then too small to reuse a fetched row)
-                const int64_t waves = (int64_t)((M + c[0] - 1) / c[0]) * tiles * c[1];
-                if (c[0] > M || waves < 2048 || waves > 16384) continue;
-                sparsert_options o = b;
-                o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
-                o.spec_rows = c[0]; o.spec_ksplit = c[1];
-                cands.push_back(o);
+            if (K >= 512) {   // long reduction axis: split it over the waves of a workgroup
+                const int rk[][2] = {{1, 8}, {2, 8}, {4, 8}, {8, 8}, {16, 8}, {24, 8}, {32, 8}, {48, 8}, {64, 8},
+                                     {1, 4}, {2, 4}, {4, 4}, {8, 4}, {16, 4}, {32, 4}, {48, 4}, {64, 4}, {96, 4},
+                                     {64, 2}, {96, 2}};
+                for (auto &c : rk) {
+                    // worth timing with at least two waves for every SIMD of the chip, but not with
+                    // more than sixteen (the blocks are then too small to reuse a fetched row)
+                    const int64_t waves = (int64_t)((M + c[0] - 1) / c[0]) * vtiles * c[1];
+                    if (c[0] > M || c[0] > max_rows || waves < 2048 || waves > 16384) continue;
+                    sparsert_options o = b;
+                    o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
+                    o.spec_rows = c[0]; o.spec_ksplit = c[1]; o.spec_vec = V;
+                    cands.push_back(o);
+                }
             }
-        }
+        };
+        add_direct(1);
+        if (!conv && f16 && N % 2 == 0) add_direct(2);
+        if (!conv && i8 && N % 4 == 0) add_direct(4);
         if (!conv && !f16 && !i8 && K >= 256 && (int64_t)M * tiles >= 1024) {
             for (int r : {12, 24, 48, 96})
                 for (int w : {4, 8}) {
@@ -136,10 +145,10 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     // eight waves, the ones with the most rows per block first (fewest fetches of B).
     if (nnz > (256 << 10)) {
         const size_t budget = nnz > (1 << 20) ? 3 : 6;
-        const int64_t tiles = (N + 63) / 64;
         auto waves_of = [&](const sparsert_options &o) -> int64_t {
             const int64_t blocks = (M + o.spec_rows - 1) / o.spec_rows;
-            return blocks * tiles * (o.spec_ksplit > 1 ? o.spec_ksplit : 1);   // DIRECT and LDS: one wave per block and tile
+            const int64_t vt = (N / std::max(1, o.spec_vec) + 63) / 64;
+            return blocks * vt * (o.spec_ksplit > 1 ? o.spec_ksplit : 1);   // DIRECT and LDS: one wave per block and tile
         };
         std::vector<sparsert_options> rows_family, spec_family;
         for (const sparsert_options &o : cands) (o.kernel == SPARSERT_KERNEL_SPEC ? spec_family : rows_family).push_back(o);
@@ -167,6 +176,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         t.spec_ksplit = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.ksplit : 0;
         t.spec_lanes = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.lanes_per_tile : 0;
         t.spec_swizzle = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.swizzle : 0;
+        t.spec_vec = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.vec : 0;
         t.microseconds = us;
     };
     log(best, best_us);
@@ -188,7 +198,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         const sparsert::SpecPlan &w = best->host.spec;
         sparsert_options o = b;
         o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = w.mode; o.spec_rows = w.rows_per_group;
-        o.spec_tiles = w.tiles_per_wg; o.spec_ksplit = w.ksplit; o.spec_swizzle = 1;
+        o.spec_tiles = w.tiles_per_wg; o.spec_ksplit = w.ksplit; o.spec_vec = w.vec; o.spec_swizzle = 1;
         sparsert_plan *p = nullptr;
         if (sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &p) == SPARSERT_OK) {
             const float us = time_plan(p, conv, in_dev, out_dev, s, e0, e1, launches, repeats);

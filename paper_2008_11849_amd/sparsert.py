@@ -26,7 +26,7 @@ SPEC_AUTO, SPEC_DIRECT, SPEC_LDS = 0, 1, 2
 INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", "vec",
               "lanes_per_tile", "n_tiles", "gy", "split_threshold", "n_split", "n_wg_rows",
               "n_bins", "spec_rows", "spec_groups", "spec_depth", "spec_code_bytes",
-              "spec_tiles", "spec_mode", "spec_lds_bytes", "spec_ksplit", "natural_order", "spec_lanes", "spec_swizzle", "batch"]
+              "spec_tiles", "spec_mode", "spec_lds_bytes", "spec_ksplit", "natural_order", "spec_lanes", "spec_swizzle", "batch", "spec_vec"]
 INFO_COUNT = 32
 
 EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_plan_export",
@@ -42,7 +42,7 @@ class Options(ctypes.Structure):
                 ("spec_tiles", ctypes.c_int32), ("spec_mode", ctypes.c_int32),
                 ("spec_ksplit", ctypes.c_int32), ("natural_order", ctypes.c_int32),
                 ("spec_lanes", ctypes.c_int32), ("spec_swizzle", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 2)]
+                ("spec_vec", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
 
 
 TUNE_MAX = 64
@@ -53,7 +53,7 @@ class TuneEntry(ctypes.Structure):
                 ("spec_mode", ctypes.c_int32), ("spec_rows", ctypes.c_int32),
                 ("spec_tiles", ctypes.c_int32), ("spec_ksplit", ctypes.c_int32),
                 ("spec_lanes", ctypes.c_int32), ("spec_swizzle", ctypes.c_int32),
-                ("microseconds", ctypes.c_float)]
+                ("spec_vec", ctypes.c_int32), ("microseconds", ctypes.c_float)]
 
 
 class TuneReport(ctypes.Structure):
@@ -156,7 +156,7 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
             vec: int = 0, split_threshold: int = 0, kernel: int = KERNEL_AUTO,
             spec_rows: int = 0, spec_depth: int = 0, spec_tiles: int = 0,
             spec_mode: int = 0, spec_ksplit: int = 0, natural_order: bool = False,
-            spec_lanes: int = 0, spec_swizzle: bool = False) -> Plan:
+            spec_lanes: int = 0, spec_swizzle: bool = False, spec_vec: int = 0) -> Plan:
     """sparsert_inspect.  `vals` must already be float32, float16 or int8; it is not converted."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -170,7 +170,7 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
     opt.vec, opt.split_threshold, opt.batch = vec, split_threshold, batch
     opt.spec_rows, opt.spec_depth, opt.spec_tiles = spec_rows, spec_depth, spec_tiles
     opt.spec_mode, opt.spec_ksplit, opt.natural_order = spec_mode, spec_ksplit, int(natural_order)
-    opt.spec_lanes, opt.spec_swizzle = spec_lanes, int(spec_swizzle)
+    opt.spec_lanes, opt.spec_swizzle, opt.spec_vec = spec_lanes, int(spec_swizzle), spec_vec
     if conv is not None:
         opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
     handle = _vp()

@@ -332,7 +332,8 @@ def test_generated_kernel_option_errors():
     csr = synth.uniform_csr(16, 18, 0.5, 1)
     args = (csr.row_ptr, csr.col_idx, csr.vals, 16, 18, 8)
     for kw in ({"spec_tiles": 3}, {"spec_mode": 9}, {"spec_depth": 99}, {"spec_rows": 500}, {"spec_lanes": 48},
-               {"spec_ksplit": 3}, {"spec_ksplit": 2, "spec_mode": sp.SPEC_LDS}, {"spec_lanes": 32, "spec_mode": sp.SPEC_LDS}):
+               {"spec_ksplit": 3}, {"spec_ksplit": 2, "spec_mode": sp.SPEC_LDS}, {"spec_lanes": 32, "spec_mode": sp.SPEC_LDS},
+               {"spec_vec": 2}, {"spec_vec": 4}, {"spec_vec": 3}):   # packed columns are for half / int8 plans
         with pytest.raises(sp.SparseRTError) as e:
             sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, **kw)
         assert e.value.status == sp.EINVAL, kw

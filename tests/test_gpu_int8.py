@@ -34,7 +34,10 @@ def test_int8_spmm_is_exact(N):
                 dict(kernel=sp.KERNEL_SPEC, spec_rows=20, spec_ksplit=4, spec_swizzle=True),
                 dict(kernel=sp.KERNEL_SPEC, spec_rows=77, spec_ksplit=8, spec_depth=3)]
     if N % 4 == 0:
-        variants += [dict(vec=4), dict(vec=4, split_threshold=1), dict(vec=4, split_threshold=9)]
+        variants += [dict(vec=4), dict(vec=4, split_threshold=1), dict(vec=4, split_threshold=9),
+                     dict(kernel=sp.KERNEL_SPEC, spec_vec=4, spec_rows=1), dict(kernel=sp.KERNEL_SPEC, spec_vec=4, spec_rows=9),
+                     dict(kernel=sp.KERNEL_SPEC, spec_vec=4, spec_rows=20, spec_ksplit=4, spec_swizzle=True),
+                     dict(kernel=sp.KERNEL_SPEC, spec_vec=4, spec_rows=48, spec_ksplit=8, spec_depth=3)]
     for opts in variants:
         got, info = run_spmm(csr, B, **opts)
         assert got.dtype == np.int32 and info["dtype"] == sp.I8
@@ -51,7 +54,8 @@ def test_int8_extreme_values_and_empty_rows():
     B = np.full((K, 68), -128, dtype=np.int8)
     B[:, 1] = 127
     for opts in (dict(vec=1), dict(vec=4), dict(vec=4, split_threshold=100), dict(kernel=sp.KERNEL_SPEC, spec_rows=3),
-                 dict(kernel=sp.KERNEL_SPEC, spec_rows=3, spec_ksplit=8)):
+                 dict(kernel=sp.KERNEL_SPEC, spec_rows=3, spec_ksplit=8), dict(kernel=sp.KERNEL_SPEC, spec_rows=3, spec_vec=4),
+                 dict(kernel=sp.KERNEL_SPEC, spec_rows=3, spec_vec=4, spec_ksplit=8)):
         got, _ = run_spmm(csr, B, **opts)
         assert np.all(got[1] == 0)
         assert np.all(got[0, 0] == K * 16384) and np.all(got[2, 1] == -K * 128 * 127)
@@ -90,7 +94,8 @@ def test_int8_batched_spmm_and_tune():
     csr = synth.int8_csr(300, 256, 0.9, 5)
     B = np.stack([synth.int8_dense(256, 512, 6 + i) for i in range(2)])
     want = np.stack([_want(csr, B[i]) for i in range(2)])
-    for opts in (dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=24, spec_ksplit=4)):
+    for opts in (dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=24, spec_ksplit=4),
+                 dict(kernel=sp.KERNEL_SPEC, spec_rows=24, spec_ksplit=4, spec_vec=4)):
         got, info = run_spmm(csr, B, **opts)
         assert info["batch"] == 2 and np.array_equal(got.astype(np.int64), want)
     dev = torch.device("cuda:0")

@@ -239,6 +239,8 @@ def test_conv_batch_generated_and_row_walk(batch):
 
 HALF_OPTS = [dict(spec_rows=1), dict(spec_rows=7), dict(spec_rows=20, spec_ksplit=4), dict(spec_rows=9, spec_swizzle=True),
              dict(spec_rows=50, spec_ksplit=8, spec_depth=3)]
+HALF_PAIRS = [dict(spec_vec=2, spec_rows=1), dict(spec_vec=2, spec_rows=7), dict(spec_vec=2, spec_rows=20, spec_ksplit=4),
+              dict(spec_vec=2, spec_rows=50, spec_ksplit=8, spec_depth=3, spec_swizzle=True)]
 
 
 @pytest.mark.parametrize("N", [1, 8, 65, 200, 520])
@@ -248,9 +250,10 @@ def test_spec_half_small_integers_bit_exact(N):
     B = synth.small_int_dense(90, N, N + 1, dtype=np.float16, bmax=4)
     Cref, _ = _oracle(csr, B)
     assert np.abs(Cref).max() <= 2048
-    for opts in HALF_OPTS:
+    for opts in HALF_OPTS + (HALF_PAIRS if N % 2 == 0 else []):   # pairs: two halves per lane in one dword
         got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, **opts)
         assert info["kernel"] == sp.KERNEL_SPEC and info["dtype"] == sp.F16 and got.dtype == np.float16
+        assert info["spec_vec"] == opts.get("spec_vec", 1)
         assert np.array_equal(got.astype(np.float64), Cref), (N, opts)
 
 
@@ -270,7 +273,8 @@ def test_spec_half_rounds_once_at_the_store():
     Bx[:, 1] = 2.0 ** -14
     want = _oracle(ones, Bx)[0].astype(np.float16)
     assert want[0, 0] == 2048 and want[1, 0] == 2052
-    for opts in (dict(spec_rows=2), dict(spec_rows=2, spec_ksplit=8), dict(kernel=sp.KERNEL_ROWS)):
+    for opts in (dict(spec_rows=2), dict(spec_rows=2, spec_ksplit=8), dict(kernel=sp.KERNEL_ROWS),
+                 dict(spec_rows=2, spec_vec=2), dict(spec_rows=2, spec_vec=2, spec_ksplit=4)):
         got, _ = run_spmm(ones, Bx, **{"kernel": sp.KERNEL_SPEC, **opts})
         assert got.tobytes() == want.tobytes(), opts
 
@@ -279,9 +283,10 @@ def test_spec_half_rounds_once_at_the_store():
 def test_spec_half_configs(name):
     case = synth.config(name, np.float16)
     opts = dict(spec_rows=48, spec_ksplit=8) if name == "c3t" else dict(spec_rows=4)
-    got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, **opts)
     Cref, S = _oracle(case.csr, case.B)
-    check(got, Cref, S, np.float16, gate_relative=True)
+    for extra in (dict(), dict(spec_vec=2)):
+        got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, **opts, **extra)
+        check(got, Cref, S, np.float16, gate_relative=True)
 
 
 def test_spec_half_skewed_and_conv():
