@@ -53,7 +53,7 @@ class Layer:
     """One sparse layer resident on the GPU: plan, input, output and its dense twin."""
 
     PLAN_KEYS = ("kernel", "vec", "split_threshold", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit",
-                 "spec_swizzle")
+                 "spec_swizzle", "spec_vec")
 
     def __init__(self, case, torch, sp, kernel="tune", fixed=None):
         import numpy as np
@@ -291,7 +291,7 @@ def main():
                           "cold_us": cold, "cold_operand_sets": n_sets,
                           "dense_us": ms_dense * 1e3, "speedup_vs_dense": ms_dense / ms, "dense_kind": L.dense_kind,
                           "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
-                                                          "spec_tiles", "spec_ksplit", "spec_swizzle",
+                                                          "spec_tiles", "spec_ksplit", "spec_swizzle", "spec_vec",
                                                           "spec_code_bytes")},
                           "tuned_candidates": len(L.tuned) if L.tuned else 0})
     kernel_ms = sum(p["us"] for p in per_layer) / 1e3 / len(layers)       # average launch
@@ -341,7 +341,7 @@ def main():
             side.append({"layer": n, "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
                          "dense_us": msd * 1e3, "speedup_vs_dense": msd / ms,
                          "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
-                                                         "spec_tiles", "spec_ksplit", "spec_swizzle")}})
+                                                         "spec_tiles", "spec_ksplit", "spec_swizzle", "spec_vec")}})
             L.plan.destroy()
         out["other_configs"] = side
 

@@ -136,7 +136,7 @@ def main():
         return {"tag": tag, "sparse_us": round(t_sparse, 3), "dense_us": round(t_dense, 3),
                 "speedup": round(t_dense / t_sparse, 3), "dense_timing": dense_how,
                 "gflops": round(2.0 * csr.nnz * N * max(1, batch) / t_sparse / 1e3, 1),
-                "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit", "spec_swizzle")},
+                "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit", "spec_swizzle", "spec_vec")},
                 **extra}
 
     for sparsity in (() if args.sweep else (0.90, 0.95)):
