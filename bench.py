@@ -38,6 +38,7 @@ def parse_args():
                     help="storage type; i8: int8 weights and activations, exact int32 results")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cases", action="store_true", help="skip the side table of the other configs")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-operand timing of every layer")
     ap.add_argument("--kernel", default="tune", choices=["tune", "rows", "spec"],
                     help="tune: sparsert_tune picks the executor per layer (default); rows/spec: fixed family")
     ap.add_argument("--plan-file", default=None,
@@ -285,7 +286,7 @@ def main():
     for L in layers:
         ms = time_loop(torch, lambda L=L: L.launch(stream), iters, 50)
         ms_dense = time_loop(torch, L.dense, max(50, iters // 10), 10)
-        cold, n_sets = L.cold_us()
+        cold, n_sets = (ms * 1e3, 0) if args.no_cold else L.cold_us()
         per_layer.append({"layer": L.case.name, "M": L.M, "K": L.K, "N": L.N, "nnz": L.nnz,
                           "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
                           "cold_us": cold, "cold_operand_sets": n_sets,
