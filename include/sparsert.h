@@ -264,6 +264,24 @@ enum {
 int sparsert_plan_export(const sparsert_plan *plan, int32_t field,
                          void *buf, size_t cap, size_t *need);
 
+/*
+ * Plan persistence (Section 2.3: the inspector runs once, offline; Section 3.7: so does the
+ * tuner).  sparsert_plan_save writes the whole plan - analysis arrays, executor choice and, for
+ * a generated kernel, its assembled code object - into `buf`; sparsert_plan_load rebuilds it,
+ * uploading to the current HIP device unless host_only is set, without analysing, generating
+ * or assembling anything.  A loaded plan exports and executes exactly like the one saved.
+ *
+ *   buf/cap  HOST buffer; with buf == NULL only *need (bytes required) is reported
+ *   size     bytes of a blob sparsert_plan_save wrote
+ *
+ * The blob is little endian and carries a format version and a checksum: a truncated,
+ * corrupted or foreign blob gives EINVAL (EUNSUPPORTED for another format version).  The
+ * checksum is no defence against a deliberately crafted blob: load only blobs this library
+ * wrote.  A blob is tied to gfx950 and to the N, dtype and batch it was planned for.
+ */
+int sparsert_plan_save(const sparsert_plan *plan, void *buf, size_t cap, size_t *need);
+int sparsert_plan_load(const void *buf, size_t size, int32_t host_only, sparsert_plan **out);
+
 /* Frees the plan's host and device memory.  NULL is ignored.  The caller must
  * make sure no launch that uses the plan is still in flight. */
 void sparsert_plan_destroy(sparsert_plan *plan);

@@ -30,7 +30,8 @@ INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", 
 INFO_COUNT = 32
 
 EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_plan_export",
-            "sparsert_plan_destroy", "sparsert_last_error", "sparsert_version"]
+            "sparsert_plan_save", "sparsert_plan_load", "sparsert_plan_destroy", "sparsert_last_error",
+            "sparsert_version"]
 
 
 class Options(ctypes.Structure):
@@ -94,6 +95,10 @@ _lib.sparsert_conv3x3.restype = ctypes.c_int
 _lib.sparsert_plan_export.argtypes = [_vp, _i32, _vp, ctypes.c_size_t,
                                       ctypes.POINTER(ctypes.c_size_t)]
 _lib.sparsert_plan_export.restype = ctypes.c_int
+_lib.sparsert_plan_save.argtypes = [_vp, _vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+_lib.sparsert_plan_save.restype = ctypes.c_int
+_lib.sparsert_plan_load.argtypes = [_vp, ctypes.c_size_t, _i32, ctypes.POINTER(_vp)]
+_lib.sparsert_plan_load.restype = ctypes.c_int
 _lib.sparsert_plan_destroy.argtypes = [_vp]
 _lib.sparsert_plan_destroy.restype = None
 _lib.sparsert_last_error.restype = ctypes.c_char_p
@@ -138,6 +143,14 @@ class Plan:
     def info(self) -> dict:
         raw = self.export(FIELD_INFO)
         return {k: int(raw[i]) for i, k in enumerate(INFO_NAMES)}
+
+    def save(self) -> bytes:
+        """sparsert_plan_save: the whole plan (with its generated code, if any) as bytes."""
+        need = ctypes.c_size_t(0)
+        _check(_lib.sparsert_plan_save(self.handle, None, 0, ctypes.byref(need)))
+        buf = ctypes.create_string_buffer(need.value)
+        _check(_lib.sparsert_plan_save(self.handle, buf, need.value, None))
+        return buf.raw
 
     def destroy(self):
         if self.handle:
@@ -202,6 +215,15 @@ def tune(row_ptr, col_idx, vals, M: int, K: int, N: int, in_dev: int, out_dev: i
     names = [f[0] for f in TuneEntry._fields_]
     entries = [{n: getattr(rep.entries[i], n) for n in names} for i in range(rep.count)]
     return Plan(handle.value, opt.dtype), entries
+
+
+def load(blob: bytes, host_only: bool = False) -> Plan:
+    """sparsert_plan_load: a plan from bytes written by Plan.save; nothing is analysed or assembled."""
+    handle = _vp()
+    _check(_lib.sparsert_plan_load(blob, len(blob), int(host_only), ctypes.byref(handle)))
+    plan = Plan(handle.value, F32)
+    plan.dtype = plan.info()["dtype"]
+    return plan
 
 
 def spmm(plan: Plan, B_dev: int, C_dev: int, stream: int = 0):

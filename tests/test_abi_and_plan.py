@@ -348,3 +348,66 @@ def test_generated_kernel_option_errors():
     out, rep = ctypes.c_void_p(1), sp.TuneReport()
     rc = sp.raw.sparsert_tune(None, None, None, 1, 1, 1, None, 16, 16, None, ctypes.byref(out), ctypes.byref(rep))
     assert rc == sp.EINVAL and out.value is None
+
+
+ALL_FIELDS = dict(FIELDS, spec_groups=sp.FIELD_SPEC_GROUPS, spec_columns=sp.FIELD_SPEC_COLUMNS,
+                  spec_code=sp.FIELD_SPEC_CODE, info=sp.FIELD_INFO)
+
+
+@pytest.mark.parametrize("opts", [dict(), dict(vec=2, split_threshold=3), dict(kernel=sp.KERNEL_SPEC, spec_rows=7, spec_ksplit=4),
+                                  dict(kernel=sp.KERNEL_SPEC, spec_rows=12, spec_mode=sp.SPEC_LDS, spec_tiles=2),
+                                  dict(natural_order=True, batch=3)])
+def test_saved_plan_loads_to_the_same_plan(opts):
+    """Plan persistence: every exported array, the info block and the generated code survive."""
+    csr = synth.skewed_csr(60, 300, 0.9, 4)
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 60, 300, 196, host_only=True, **opts)
+    blob = plan.save()
+    again = sp.load(blob, host_only=True)
+    for name, fid in ALL_FIELDS.items():
+        assert again.export(fid).tobytes() == plan.export(fid).tobytes(), name
+    assert again.save() == blob
+    plan.destroy()
+    again.destroy()
+
+
+def test_saved_conv_half_and_int8_plans_round_trip():
+    ccsr, _ = synth.conv_weights_csr(8, 6, 0.7, 2, dtype=np.float16)
+    for csr, kw in ((ccsr, dict(conv=(6, 5, 7), batch=2, kernel=sp.KERNEL_SPEC, spec_rows=3)),
+                    (synth.int8_csr(30, 64, 0.8, 3), dict(kernel=sp.KERNEL_SPEC, spec_rows=5, spec_vec=4))):
+        N = 35 if "conv" in kw else 64
+        plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, host_only=True, **kw)
+        again = sp.load(plan.save(), host_only=True)
+        assert again.dtype == plan.dtype
+        for name, fid in ALL_FIELDS.items():
+            assert again.export(fid).tobytes() == plan.export(fid).tobytes(), name
+        plan.destroy()
+        again.destroy()
+
+
+def test_load_rejects_damaged_blobs():
+    csr = synth.uniform_csr(20, 30, 0.8, 1)
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 20, 30, 64, host_only=True, kernel=sp.KERNEL_SPEC, spec_rows=4)
+    blob = plan.save()
+    plan.destroy()
+
+    def status(b):
+        try:
+            sp.load(b, host_only=True).destroy()
+            return sp.OK
+        except sp.SparseRTError as e:
+            assert str(e)
+            return e.status
+
+    assert status(blob) == sp.OK
+    assert status(blob[:10]) == sp.EINVAL                                   # too short for a header
+    assert status(blob[:-1]) == sp.EINVAL and status(blob + b"x") == sp.EINVAL   # truncated, padded
+    assert status(b"XXXX" + blob[4:]) == sp.EINVAL                          # not ours
+    flipped = bytearray(blob)
+    flipped[len(blob) // 2] ^= 0x40
+    assert status(bytes(flipped)) == sp.EINVAL                              # checksum
+    other = bytearray(blob)
+    other[4] = 99
+    assert status(bytes(other)) == sp.EUNSUPPORTED                          # another format version
+    h = ctypes.c_void_p()
+    assert sp.raw.sparsert_plan_load(None, 100, 1, ctypes.byref(h)) == sp.EINVAL
+    assert sp.raw.sparsert_plan_save(None, None, 0, None) == sp.EINVAL

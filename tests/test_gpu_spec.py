@@ -394,6 +394,43 @@ def test_random_small_cases_all_executors(seed):
             assert np.array_equal(got.astype(np.float64), want), (M, K, N, np.dtype(dtype).name, density, opts)
 
 
+def test_loaded_plans_execute_like_the_saved_ones():
+    """A tuned plan saved by one process and loaded by another must run the same kernel."""
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    case = synth.config("c2")
+    csr = case.csr
+    Bd = torch.from_numpy(case.B).to(dev)
+    for opts in (dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=16, spec_ksplit=4, spec_swizzle=True),
+                 dict(kernel=sp.KERNEL_SPEC, spec_rows=12, spec_mode=sp.SPEC_LDS)):
+        plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N, **opts)
+        again = sp.load(plan.save())
+        outs = []
+        for p in (plan, again):
+            Cd = torch.full((csr.M, case.N), float("nan"), device=dev)
+            sp.spmm(p, Bd.data_ptr(), Cd.data_ptr(), stream)
+            torch.cuda.synchronize()
+            outs.append(Cd)
+        assert torch.equal(outs[0], outs[1]), opts
+        Cref, S = _oracle(csr, case.B)
+        check(outs[1].cpu().numpy(), Cref, S, np.float32, gate_relative=True)
+        plan.destroy()
+        again.destroy()
+    ccsr, Wd = synth.conv_weights_csr(24, 16, 0.8, 5, dtype=np.float16)
+    X = synth.normal_dense(2 * 16, 14 * 14, 6, dtype=np.float16).reshape(2, 16, 14, 14)
+    plan = sp.inspect(ccsr.row_ptr, ccsr.col_idx, ccsr.vals, 24, 144, 196, conv=(16, 14, 14), batch=2,
+                      kernel=sp.KERNEL_SPEC, spec_rows=3)
+    again = sp.load(plan.save())
+    plan.destroy()
+    Xd = torch.from_numpy(X).to(dev)
+    Yd = torch.full((2, 24, 14, 14), float("nan"), dtype=torch.float16, device=dev)
+    sp.conv3x3(again, Xd.data_ptr(), Yd.data_ptr(), stream)
+    torch.cuda.synchronize()
+    Yref, S = ref.conv3x3(Wd, X)
+    check(Yd.cpu().numpy(), Yref, S, np.float16)
+    again.destroy()
+
+
 NATURAL = [dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=9), dict(kernel=sp.KERNEL_SPEC, spec_rows=12, spec_mode=sp.SPEC_LDS),
            dict(kernel=sp.KERNEL_SPEC, spec_rows=20, spec_ksplit=4)]
 
