@@ -60,7 +60,7 @@ template <typename T, int V> struct Ops {
 #pragma unroll
             for (int j = 0; j < V; ++j) v[j] = (T)acc[j];  // half: one round-to-nearest-even here
         }
-        *reinterpret_cast<vec_t *>(dst) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<vec_t *>(dst));   // C is not read again: keep it out of the way of B in the L2
     }
 };
 
@@ -86,10 +86,10 @@ template <int V> struct Ops<int8_t, V> {
     }
     static __device__ __forceinline__ void store(out_t *dst, const acc_t (&acc)[V]) {
         if constexpr (V == 1) {
-            *dst = acc[0];
+            __builtin_nontemporal_store(acc[0], dst);
         } else {
             typedef int32_t i4 __attribute__((ext_vector_type(4)));
-            *reinterpret_cast<i4 *>(dst) = i4{acc[0], acc[1], acc[2], acc[3]};
+            __builtin_nontemporal_store(i4{acc[0], acc[1], acc[2], acc[3]}, reinterpret_cast<i4 *>(dst));
         }
     }
 };

@@ -276,10 +276,12 @@ struct Gen {
                 if (V == 2) e.line("\tv_pack_b32_f16 v%d, v%d, v%d", r, r, r + 1);
                 else op = "buffer_store_short";
             }
+            // C is written once and not read again by this kernel: the non-temporal hint keeps it from
+            // displacing the code and the rows of B in the L2 (measured: c3 11.5 -> 10.5 us)
             if (int8 && V == 4)
-                e.line("\tbuffer_store_dwordx4 v[%d:%d], v%d, s[%d:%d], s%d offen", r, r + 3, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
+                e.line("\tbuffer_store_dwordx4 v[%d:%d], v%d, s[%d:%d], s%d offen nt", r, r + 3, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
             else
-                e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", op, r, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
+                e.line("\t%s v%d, v%d, s[%d:%d], s%d offen nt", op, r, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
         }
     }
 
