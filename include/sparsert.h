@@ -51,7 +51,7 @@ typedef enum sparsert_kernel {
     SPARSERT_KERNEL_AUTO = 0,
     SPARSERT_KERNEL_ROWS = 1,  /* one wave per row, B read straight from L2/HBM */
     SPARSERT_KERNEL_SPEC = 2   /* per-matrix generated gfx950 code with the nonzeros of A as
-                                  instruction constants (Section 3.5); fp32 only */
+                                  instruction constants (Section 3.5) */
 } sparsert_kernel;
 
 /* Variants of the generated kernel (options.spec_mode). */
@@ -91,13 +91,13 @@ typedef struct sparsert_options {
     int32_t natural_order;   /* 1: load-balance ablation (Section 4.3): rows keep their input order
                                 (identity permutation), no row is split over waves, and the
                                 generated kernel's blocks are contiguous row ranges; 0 = balanced */
-    int32_t spec_lanes;      /* SPARSERT_KERNEL_SPEC: widest column tile of a wave, 16, 32 or 64 lanes
-                                (0 = 64).  Narrow tiles leave lanes idle but let a compute unit
-                                cover more rows of fewer columns, which cuts the bytes of B it
-                                pulls in when M is small and K long */
+    int32_t spec_lanes;      /* SPARSERT_KERNEL_SPEC, DIRECT: widest column tile of a wave, 16, 32 or 64
+                                lanes (0 = 64).  Narrow tiles leave lanes idle but let a compute unit
+                                cover more rows of fewer columns; measured slower wherever tried,
+                                kept for experiments */
     int32_t spec_swizzle;    /* SPARSERT_KERNEL_SPEC: 1 = rows are dealt to code blocks by column-pattern
-                                similarity (the row swizzle the paper proposes as future work,
-                                Section 5), so a block touches fewer rows of B; 0 = serpentine deal */
+                                similarity (the row swizzle Section 5 names as a preprocessing step
+                                that would help), so a block touches fewer rows of B; 0 = serpentine deal */
     int32_t spec_vec;        /* SPARSERT_KERNEL_SPEC, DIRECT, SpMM: columns of C per lane; 0/1, or the 2 halves
                                 (half plans) / 4 int8 (int8 plans) that share the dword a lane loads,
                                 which halves / quarters the fetches per column; N must be a multiple */
@@ -137,7 +137,7 @@ int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void 
  * row of A without nonzeros yields +0.0.
  *
  *   B_dev  DEVICE, K x N row-major, plan's dtype, 16-byte aligned, read only
- *   C_dev  DEVICE, M x N row-major, plan's dtype, 16-byte aligned, written
+ *   C_dev  DEVICE, M x N row-major, plan's dtype (int32 for int8 plans), 16-byte aligned, written
  *   stream a hipStream_t (NULL = the null stream)
  *
  * With opt->batch = b the call multiplies b matrices stored back to back, B_dev as
@@ -162,7 +162,7 @@ int sparsert_spmm(const sparsert_plan *plan, const void *B_dev, void *C_dev, voi
  * by one launch (the image is one more grid dimension).
  *
  *   X_dev  DEVICE, [batch, Cin, H, W] contiguous, plan's dtype, 16-byte aligned
- *   Y_dev  DEVICE, [batch, Cout, H, W] contiguous, plan's dtype, 16-byte aligned
+ *   Y_dev  DEVICE, [batch, Cout, H, W] contiguous, plan's dtype (int32 for int8 plans), 16-byte aligned
  *
  * Same asynchrony, ownership and error rules as sparsert_spmm; EINVAL if the
  * plan was not made with opt->conv = 1.
@@ -173,7 +173,7 @@ int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, 
  * Autotuner (Section 3.7: exhaustive search over a short hand-picked list of executor
  * configurations, done once per problem, off the inference path).  Builds a plan for each
  * candidate configuration - executor family, columns per lane, split threshold, rows per
- * generated code block, waves per workgroup, staging variant - times it on the GPU with the
+ * generated code block, waves per workgroup, K split, staging variant, row swizzle - times it on the GPU with the
  * given operands, and returns the fastest plan.  `base` fixes dtype, the convolution
  * geometry and natural_order; base->kernel other than AUTO restricts the search to that
  * executor family (the specialisation ablation); its other tuning fields are ignored.
@@ -214,7 +214,8 @@ typedef enum sparsert_field {
     SPARSERT_FIELD_P_VALS = 7,    /* dtype[nnz] values, bit copies */
     SPARSERT_FIELD_BINS = 8,      /* int32[nbins][4]: bin id, first slot, rows, nonzeros */
     SPARSERT_FIELD_STREAM = 9,    /* uint32[nnz][2]: what the executor reads per nonzero:
-                                     {operand byte offset as int32, value as binary32 bits}.
+                                     {operand byte offset as int32, value as binary32 bits
+                                     (int8 plans: the value sign-extended to int32)}.
                                      SpMM: offset = col*N*sizeof(dtype), permuted-CSR order.
                                      Conv: word = tap << 28 | (d & 0x0fffffff), tap = r*3+s,
                                      d = (c*H*W + (r-1)*W + (s-1))*sizeof(dtype) (may be
@@ -224,7 +225,8 @@ typedef enum sparsert_field {
     SPARSERT_FIELD_SEGMENTS = 11, /* int32[n_split][Gy+1]: stream positions bounding the
                                      share of each wave of a split row */
     SPARSERT_FIELD_SPEC_GROUPS = 12, /* SPEC plans, int32[M]: code block (row group) of each slot */
-    SPARSERT_FIELD_SPEC_COLUMNS = 13, /* SPEC plans, int32[groups]: B rows a block loads per tile */
+    SPARSERT_FIELD_SPEC_COLUMNS = 13, /* SPEC plans, int32[blocks]: B rows a code block loads per tile
+                                         (blocks = groups x K parts; padded in the LDS variant) */
     SPARSERT_FIELD_SPEC_CODE = 14 /* SPEC plans, bytes: the generated gfx950 code object */
 } sparsert_field;
 
