@@ -52,7 +52,9 @@ template <typename T, int V> struct Ops {
 #pragma unroll
         for (int j = 0; j < V; ++j) acc[j] = __builtin_fmaf(__uint_as_float(word), b.v[j], acc[j]);
     }
-    static __device__ __forceinline__ void store(out_t *dst, const acc_t (&acc)[V]) {
+    // `stream`: C is not read again, so where a wave's store covers whole 128-byte lines it is
+    // written with the non-temporal hint and stays out of the way of B in the L2.
+    static __device__ __forceinline__ void store(out_t *dst, const acc_t (&acc)[V], bool stream) {
         vec_t v;
         if constexpr (V == 1) {
             v = (T)acc[0];
@@ -60,7 +62,8 @@ template <typename T, int V> struct Ops {
 #pragma unroll
             for (int j = 0; j < V; ++j) v[j] = (T)acc[j];  // half: one round-to-nearest-even here
         }
-        __builtin_nontemporal_store(v, reinterpret_cast<vec_t *>(dst));   // C is not read again: keep it out of the way of B in the L2
+        if (stream) __builtin_nontemporal_store(v, reinterpret_cast<vec_t *>(dst));
+        else *reinterpret_cast<vec_t *>(dst) = v;
     }
 };
 
@@ -84,12 +87,15 @@ template <int V> struct Ops<int8_t, V> {
             for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_sdot4(b.v, (int32_t)(a8 << (8 * j)), acc[j], false);
         }
     }
-    static __device__ __forceinline__ void store(out_t *dst, const acc_t (&acc)[V]) {
+    static __device__ __forceinline__ void store(out_t *dst, const acc_t (&acc)[V], bool stream) {
         if constexpr (V == 1) {
-            __builtin_nontemporal_store(acc[0], dst);
+            if (stream) __builtin_nontemporal_store(acc[0], dst);
+            else *dst = acc[0];
         } else {
             typedef int32_t i4 __attribute__((ext_vector_type(4)));
-            __builtin_nontemporal_store(i4{acc[0], acc[1], acc[2], acc[3]}, reinterpret_cast<i4 *>(dst));
+            const i4 v = {acc[0], acc[1], acc[2], acc[3]};
+            if (stream) __builtin_nontemporal_store(v, reinterpret_cast<i4 *>(dst));
+            else *reinterpret_cast<i4 *>(dst) = v;
         }
     }
 };
@@ -157,6 +163,7 @@ struct RowsArgs {
     int32_t n_split, n_wg_rows;
     int32_t n_tasks, tasks_per_xcd;
     int32_t H, W;
+    int32_t stream_stores;   // every wave store of C covers whole 128-byte lines
     int64_t in_image_bytes, out_image_elems;   // distance between the problems of a batch (grid y)
 };
 
@@ -246,7 +253,7 @@ __global__ __launch_bounds__(kGy *kWave) void rows_kernel(const RowsArgs a) {
         const int row = a.perm[slot];
         typedef typename Ops<T, V>::out_t out_t;
         out_t *out = static_cast<out_t *>(a.out) + (int64_t)blockIdx.y * a.out_image_elems;
-        Ops<T, V>::store(out + (size_t)row * a.N + col, acc);
+        Ops<T, V>::store(out + (size_t)row * a.N + col, acc, a.stream_stores != 0);
     }
 }
 
@@ -345,6 +352,8 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
     a.n_split = h.n_split; a.n_wg_rows = h.n_wg_rows;
     a.n_tasks = (int32_t)n_tasks; a.tasks_per_xcd = (int32_t)((n_tasks + 7) / 8);
     a.H = h.H; a.W = h.W;
+    a.stream_stores = ((int64_t)h.N * h.out_elem_size()) % 128 == 0 &&
+                      ((int64_t)h.lanes_per_tile * h.vec * h.out_elem_size()) % 128 == 0;
     a.in_image_bytes = (h.conv ? (int64_t)h.Cin * h.H * h.W : (int64_t)h.K * h.N) * h.elem_size();
     a.out_image_elems = (int64_t)h.M * h.N;
     const int images = h.batch;

@@ -212,6 +212,7 @@ struct Gen {
     int ring_size = 0;               // DIRECT: registers of the operand ring (>= D)
     int slot_bytes = 256;            // K split: bytes of one row's partial sums in the exchange area
     int xchg_rows = 0;               // K split: rows exchanged per phase (all of them if they fit the LDS)
+    bool stream_stores = false;      // every wave store of C covers whole 128-byte lines
     int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
     Gen(const HostPlan &hp, SpecPlan &s)
         : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth), half(hp.dtype == SPARSERT_F16), int8(hp.dtype == SPARSERT_I8),
@@ -276,12 +277,15 @@ struct Gen {
                 if (V == 2) e.line("\tv_pack_b32_f16 v%d, v%d, v%d", r, r, r + 1);
                 else op = "buffer_store_short";
             }
-            // C is written once and not read again by this kernel: the non-temporal hint keeps it from
-            // displacing the code and the rows of B in the L2 (measured: c3 11.5 -> 10.5 us)
+            // C is written once and not read again by this kernel: where a wave's store covers whole
+            // 128-byte lines the non-temporal hint keeps C from displacing the code and the rows of B
+            // in the L2 (measured: c3 11.5 -> 10.5 us); on partial lines (N = 49, 196, 784) the same
+            // hint costs 0.35 us, so it is left off there
+            const char *hint = stream_stores ? " nt" : "";
             if (int8 && V == 4)
-                e.line("\tbuffer_store_dwordx4 v[%d:%d], v%d, s[%d:%d], s%d offen nt", r, r + 3, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
+                e.line("\tbuffer_store_dwordx4 v[%d:%d], v%d, s[%d:%d], s%d offen%s", r, r + 3, kVgprOut, kRsrcC, kRsrcC + 3, sreg, hint);
             else
-                e.line("\t%s v%d, v%d, s[%d:%d], s%d offen nt", op, r, kVgprOut, kRsrcC, kRsrcC + 3, sreg);
+                e.line("\t%s v%d, v%d, s[%d:%d], s%d offen%s", op, r, kVgprOut, kRsrcC, kRsrcC + 3, sreg, hint);
         }
     }
 
@@ -640,6 +644,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     }
 
     Gen gen(h, sp);
+    gen.stream_stores = ((int64_t)N * osz) % 128 == 0 && ((int64_t)sp.lanes_per_tile * V * osz) % 128 == 0;
     Emitter &e = gen.e;
     const int64_t b_bytes = h.conv ? ((int64_t)h.Cin * N + 2 * (h.W + 1)) * esz : (int64_t)h.K * N * esz;
     const int64_t c_bytes = (int64_t)M * N * osz;
