@@ -31,6 +31,23 @@ def test_library_exports_every_declared_symbol():
     assert sp.version() >= 100
 
 
+def test_boundary_from_plain_c99(tmp_path):
+    """include/sparsert.h is strict C99 and the library can be driven without Python."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    exe = tmp_path / "c_abi_check"
+    libdir = os.path.dirname(sp.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c_abi_check.c"), "-o", str(exe), "-L", libdir, "-lsparsert",
+           "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    run = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0 and "c abi ok" in run.stdout, run.stdout + run.stderr
+
+
 def _header_struct_fields(name):
     """(field, element count) of a header struct whose members are all int32_t / float."""
     text = open(os.path.join(os.path.dirname(sp.LIB_PATH), "..", "include", "sparsert.h")).read()
