@@ -91,13 +91,14 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     }
     if (family == SPARSERT_KERNEL_SPEC) cands.clear();
     if (nnz <= (4 << 20) && family != SPARSERT_KERNEL_ROWS) {
-        const int64_t tiles = (N + 63) / 64;
+        const int64_t images = std::max(1, b.batch);   // every problem of a batch brings its own waves
+        const int64_t tiles = (N + 63) / 64 * images;
         // DIRECT and K-split candidates at V columns per lane (V > 1: the halves / int8 packed in one dword)
         auto add_direct = [&](int V) {
-            const int64_t vtiles = (N / V + 63) / 64;
+            const int64_t vtiles = (N / V + 63) / 64 * images;
             const int max_rows = 192 / V;   // accumulator registers
-            for (int r : {1, 2, 4, 8, 16, 24, 48}) {
-                if (r > M || r > max_rows) continue;
+            for (int r : {1, 2, 4, 8, 16, 24, 48, 96}) {
+                if (r > M || r > max_rows || (r == 96 && images == 1)) continue;
                 const int64_t groups = (M + r - 1) / r;
                 if (r > 1 && groups * vtiles < 256) continue;   // too few waves to be worth assembling
                 if (groups > 8192) continue;
@@ -147,7 +148,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         const size_t budget = nnz > (1 << 20) ? 3 : 6;
         auto waves_of = [&](const sparsert_options &o) -> int64_t {
             const int64_t blocks = (M + o.spec_rows - 1) / o.spec_rows;
-            const int64_t vt = (N / std::max(1, o.spec_vec) + 63) / 64;
+            const int64_t vt = (N / std::max(1, o.spec_vec) + 63) / 64 * std::max(1, b.batch);
             return blocks * vt * (o.spec_ksplit > 1 ? o.spec_ksplit : 1);   // DIRECT and LDS: one wave per block and tile
         };
         std::vector<sparsert_options> rows_family, spec_family;
