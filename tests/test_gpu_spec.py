@@ -431,6 +431,30 @@ def test_loaded_plans_execute_like_the_saved_ones():
     again.destroy()
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_small_convolutions_all_executors(seed):
+    """Seeded random convolution shapes, batches, storage types and plan options on small
+    integers: bit-exact against the direct-loop oracle whatever the executor."""
+    rng = np.random.default_rng(5000 + seed)
+    for _ in range(4):
+        Cin, Cout = int(rng.integers(1, 12)), int(rng.integers(1, 40))
+        H, W, batch = int(rng.integers(1, 12)), int(rng.integers(1, 12)), int(rng.integers(1, 4))
+        dtype = [np.float32, np.float16, np.int8][int(rng.integers(0, 3))]
+        Wd = (rng.integers(1, 4, size=(Cout, Cin, 3, 3)) * rng.choice([-1, 1], size=(Cout, Cin, 3, 3))
+              * (rng.random((Cout, Cin, 3, 3)) < float(rng.choice([0.05, 0.3, 1.0])))).astype(dtype)
+        csr = synth.csr_from_mask(Wd.reshape(Cout, -1), Wd.reshape(Cout, -1) != 0)
+        X = rng.integers(-4, 5, size=(batch, Cin, H, W)).astype(dtype)
+        want = ref.conv3x3(Wd, X, want_scale=False)[0]
+        assert np.abs(want).max() <= 2048
+        variants = [dict(), dict(split_threshold=int(rng.integers(1, 9))),
+                    dict(kernel=sp.KERNEL_SPEC, spec_rows=int(rng.integers(1, 30)), spec_ksplit=int(rng.choice([0, 2, 4, 8])),
+                         spec_swizzle=bool(rng.integers(0, 2)), spec_depth=int(rng.integers(1, 20)),
+                         natural_order=bool(rng.integers(0, 2)), spec_lanes=int(rng.choice([0, 16, 32])))]
+        for opts in variants:
+            got, _ = run_conv(csr, X, Cout, **opts)
+            assert np.array_equal(got.astype(np.float64), want), (Cin, Cout, H, W, batch, np.dtype(dtype).name, opts)
+
+
 NATURAL = [dict(), dict(kernel=sp.KERNEL_SPEC, spec_rows=9), dict(kernel=sp.KERNEL_SPEC, spec_rows=12, spec_mode=sp.SPEC_LDS),
            dict(kernel=sp.KERNEL_SPEC, spec_rows=20, spec_ksplit=4)]
 

@@ -84,3 +84,50 @@ def test_generated_kernel_groups_are_balanced_partitions(M, K, seed, rows, swizz
         want = plan_ref.spec_groups(M, rows)
     assert groups.tobytes() == want.tobytes()
     plan.destroy()
+
+
+@st.composite
+def generator_requests(draw):
+    dtype = draw(st.sampled_from([np.float32, np.float16, np.int8]))
+    conv = draw(st.booleans())
+    seed = draw(st.integers(0, 2 ** 31 - 1))
+    rng = np.random.default_rng(seed)
+    if conv:
+        Cin, Cout = draw(st.integers(1, 6)), draw(st.integers(1, 20))
+        H, W = draw(st.integers(1, 9)), draw(st.integers(1, 9))
+        M, K, N = Cout, 9 * Cin, H * W
+    else:
+        M, K, N = draw(st.integers(1, 30)), draw(st.integers(1, 40)), draw(st.integers(1, 150))
+    mask = rng.random((M, K)) < draw(st.sampled_from([0.0, 0.1, 0.5, 1.0]))
+    vals = rng.integers(-100, 100, size=(M, K)).astype(dtype)
+    csr = synth.csr_from_mask(vals, mask)
+    opts = dict(spec_rows=draw(st.sampled_from([0, 1, 3, 17, 200])), spec_ksplit=draw(st.sampled_from([0, 1, 2, 4, 8])),
+                spec_depth=draw(st.sampled_from([0, 1, 5, 48])), spec_lanes=draw(st.sampled_from([0, 16, 32, 64])),
+                spec_vec=draw(st.sampled_from([0, 1, 2, 4])), spec_swizzle=draw(st.booleans()),
+                natural_order=draw(st.booleans()), spec_mode=draw(st.sampled_from([0, 1, 2])),
+                spec_tiles=draw(st.sampled_from([0, 1, 2, 4, 8, 16])), batch=draw(st.sampled_from([0, 1, 3])))
+    return csr, N, ((K // 9, H, W) if conv else None), opts
+
+
+@settings(max_examples=150, deadline=None, suppress_health_check=[HealthCheck.too_slow])
+@given(generator_requests())
+def test_generator_accepts_or_refuses_but_never_breaks(request_):
+    """Any combination of generated-kernel options either assembles to a code object or comes back
+    as an error code with a message (host only: nothing is launched)."""
+    csr, N, conv, opts = request_
+    try:
+        plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, host_only=True, conv=conv,
+                          kernel=sp.KERNEL_SPEC, **opts)
+    except sp.SparseRTError as e:
+        assert e.status in (sp.EINVAL, sp.EUNSUPPORTED) and str(e)
+        return
+    info = plan.info()
+    code = plan.export(sp.FIELD_SPEC_CODE)
+    assert code[:4].tobytes() == b"\x7fELF" and info["spec_code_bytes"] == code.size
+    assert info["spec_lds_bytes"] <= 160 * 1024
+    groups = plan.export(sp.FIELD_SPEC_GROUPS)
+    assert groups.size == csr.M and groups.max() < info["spec_groups"]
+    again = sp.load(plan.save(), host_only=True)
+    assert again.export(sp.FIELD_SPEC_CODE).tobytes() == code.tobytes()
+    plan.destroy()
+    again.destroy()
