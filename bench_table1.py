@@ -66,6 +66,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--only", default="", help="comma list of problem tags to run, e.g. t1_p9_90,t3_p3_95")
     ap.add_argument("--batch", type=int, default=1, help="images per call for the Table 3 convolutions (the paper uses 1)")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "f16"],
+                    help="storage type of weights, activations and results (sums are fp32 either way); the dense "
+                         "baseline runs in the same type")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the paper's list: the shape / sparsity sweep (M=K in 1024, 2048; N in 196, 1024, "
                          "4096; 80, 90, 95, 98 %; uniform masks), effective GFLOP/s and speedup over dense per case")
@@ -82,6 +85,8 @@ def main():
     torch.backends.cuda.matmul.allow_tf32 = False
     torch.backends.cudnn.allow_tf32 = False
     dev = torch.device("cuda:0")
+    ndt = np.float16 if args.dtype == "f16" else np.float32
+    tdt = torch.float16 if args.dtype == "f16" else torch.float32
     only = set(filter(None, args.only.split(",")))
     rows = []
 
@@ -146,10 +151,10 @@ def main():
             if sparsity == 0.95 and i >= 11 or (only and tag not in only):
                 continue
             seed = synth.BASE_SEED + 1000 + 100 * i + pct
-            csr = synth.magnitude_csr(M, K, sparsity, seed)
-            B = torch.from_numpy(synth.normal_dense(K, N, seed + 1)).to(dev)
-            C = torch.empty((M, N), device=dev)
-            Ad = torch.from_numpy(csr.todense(np.float32)).to(dev)
+            csr = synth.magnitude_csr(M, K, sparsity, seed, 1.0, ndt)
+            B = torch.from_numpy(synth.normal_dense(K, N, seed + 1, ndt)).to(dev)
+            C = torch.empty((M, N), dtype=tdt, device=dev)
+            Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
             r = run(tag, csr, N, B, C, lambda: torch.matmul(Ad, B))
             r.update(M=M, K=K, N=N, sparsity=sparsity, paper_speedup_t4=PAPER_T1[sparsity][i])
             rows.append(r)
@@ -159,10 +164,10 @@ def main():
             if only and tag not in only:
                 continue
             seed = synth.BASE_SEED + 5000 + 100 * i + pct
-            csr, Wd = synth.conv_weights_csr(Cout, Cin, sparsity, seed)
+            csr, Wd = synth.conv_weights_csr(Cout, Cin, sparsity, seed, ndt)
             nb = max(1, args.batch)
-            X = torch.from_numpy(synth.normal_dense(nb * Cin, img * img, seed + 1).reshape(nb, Cin, img, img)).to(dev)
-            Y = torch.empty((nb, Cout, img, img), device=dev)
+            X = torch.from_numpy(synth.normal_dense(nb * Cin, img * img, seed + 1, ndt).reshape(nb, Cin, img, img)).to(dev)
+            Y = torch.empty((nb, Cout, img, img), dtype=tdt, device=dev)
             Wt = torch.from_numpy(Wd).to(dev)
             r = run(tag, csr, img * img, X, Y, lambda: torch.nn.functional.conv2d(X, Wt, padding=1),
                     conv=(Cin, img, img), batch=nb)
@@ -177,11 +182,11 @@ def main():
                     tag = f"sw_{MK}x{MK}x{N}_{int(round(sparsity * 100))}"
                     if only and tag not in only:
                         continue
-                    case = synth.sweep_case(MK, MK, N, sparsity, "uniform", np.float32)
+                    case = synth.sweep_case(MK, MK, N, sparsity, "uniform", ndt)
                     csr = case.csr
                     B = torch.from_numpy(case.B).to(dev)
-                    C = torch.empty((MK, N), device=dev)
-                    Ad = torch.from_numpy(csr.todense(np.float32)).to(dev)
+                    C = torch.empty((MK, N), dtype=tdt, device=dev)
+                    Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
                     r = run(tag, csr, N, B, C, lambda: torch.matmul(Ad, B))
                     r.update(M=MK, K=MK, N=N, sparsity=sparsity, paper_speedup_t4="-")
                     rows.append(r)
@@ -195,10 +200,10 @@ def main():
             tag = f"skew_p{i + 1}_95"
             if only and tag not in only:
                 continue
-            csr = synth.skewed_csr(M, K, 0.95, synth.BASE_SEED + 9000 + i)
-            B = torch.from_numpy(synth.normal_dense(K, N, synth.BASE_SEED + 9100 + i)).to(dev)
-            C = torch.empty((M, N), device=dev)
-            Ad = torch.from_numpy(csr.todense(np.float32)).to(dev)
+            csr = synth.skewed_csr(M, K, 0.95, synth.BASE_SEED + 9000 + i, ndt)
+            B = torch.from_numpy(synth.normal_dense(K, N, synth.BASE_SEED + 9100 + i, ndt)).to(dev)
+            C = torch.empty((M, N), dtype=tdt, device=dev)
+            Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
             r = run(tag, csr, N, B, C, lambda: torch.matmul(Ad, B))
             r.update(M=M, K=K, N=N, sparsity=0.95, paper_speedup_t4="-", skewed=True)
             rows.append(r)
@@ -218,8 +223,8 @@ def main():
                     "paper": "unrolled code over 10x faster than not unrolled; without load balancing comparable in "
                              "most cases; one fixed parameter choice about 2x slower (Section 4.3)"}
     result = {
-        "workload": ("shape / sparsity sweep, uniform masks, N(0,1) values, fp32" if args.sweep else
-                     "paper Table 1 (SpMM) and Table 3 (3x3 conv) shapes, synthetic magnitude-pruned weights, fp32"),
+        "workload": ("shape / sparsity sweep, uniform masks, N(0,1) values, " if args.sweep else
+                     "paper Table 1 (SpMM) and Table 3 (3x3 conv) shapes, synthetic magnitude-pruned weights, ") + args.dtype,
         "timing": f"{INNER} launches per HIP graph, 20 replays, HIP events; same for sparse and dense",
         "geomean_speedup_vs_dense": {"table1_90": gm("t1", 0.90), "table1_95": gm("t1", 0.95),
                                      "table3_90": gm("t3", 0.90), "table3_95": gm("t3", 0.95)},
@@ -232,7 +237,7 @@ def main():
 
 
 def write_sweep_markdown(path, res, command):
-    lines = ["# Shape / sparsity sweep on MI355X, uniform masks, fp32", "",
+    lines = [f"# Shape / sparsity sweep on MI355X, uniform masks, {res['workload'].split()[-1]}", "",
              f"command: `{command}` (one MI355X; plans from sparsert_tune; sparse and dense both timed as",
              f"{INNER} launches per HIP graph, 20 replays, HIP events; effective GFLOP/s = 2 nnz N / t).", "",
              "| M = K | N | sparsity | sparse us | dense us | speedup | effective GFLOP/s | kernel | R | KS | swizzle |",
@@ -251,10 +256,10 @@ def write_markdown(path, res, command):
         return write_sweep_markdown(path, res, command)
     g = res["geomean_speedup_vs_dense"]
     fmt = lambda x: "-" if x is None else f"{x:.2f}x"
-    lines = ["# Paper's problem list (Table 1 SpMM, Table 3 3x3 conv) on MI355X, synthetic weights, fp32", "",
+    lines = [f"# Paper's problem list (Table 1 SpMM, Table 3 3x3 conv) on MI355X, synthetic weights, {res['workload'].split()[-1]}", "",
              f"command: `{command}` (one MI355X; plans from sparsert_tune; sparse and dense both timed as",
              f"{INNER} launches per HIP graph, 20 replays, HIP events).", "",
-             "Geometric-mean speedup over the dense fp32 baseline (torch.matmul / conv2d) on the same GPU:", "",
+             "Geometric-mean speedup over the dense baseline of the same type (torch.matmul / conv2d) on the same GPU:", "",
              "| set | this build, MI355X | paper, Tesla T4 (context) |", "|---|---|---|",
              f"| Table 1, 90 % (20 problems) | {fmt(g['table1_90'])} | 3.4x |",
              f"| Table 1, 95 % (problems 1-11) | {fmt(g['table1_95'])} | 5.4x |",
