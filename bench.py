@@ -169,6 +169,30 @@ def time_loop(torch, fn, iters, warmup):
     return e0.elapsed_time(e1) / iters
 
 
+def graph_us(torch, fn, inner=20, replays=20):
+    """Microseconds per call of fn with `inner` calls captured in one HIP graph and replayed:
+    neither side pays per-call host overhead (what matters for the few-microsecond configurations)."""
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(inner):
+                fn()
+    for _ in range(3):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (replays * inner)
+
+
 def load_traffic(kernel_tag):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
     path = os.path.join(ROOT, "profiles", f"{kernel_tag}_pmc.txt")
@@ -202,6 +226,13 @@ def cpu_baseline(cases, gpu_outputs):
         one_pass()
         passes += 1
     per_pass = (time.perf_counter() - t0) / passes
+    threads_all, threads = threads, 1          # the same pass on one core, three times
+    one_pass()
+    t1 = time.perf_counter()
+    for _ in range(3):
+        one_pass()
+    per_pass_1 = (time.perf_counter() - t1) / 3
+    threads = threads_all
     worst = 0.0
     for case, got in zip(cases, gpu_outputs):
         csr = case.csr
@@ -216,6 +247,7 @@ def cpu_baseline(cases, gpu_outputs):
             sys.exit(1)
         worst = max(worst, m["componentwise"])
     return {"value": flops / per_pass / 1e9, "unit": "GFLOP/s", "cores": threads, "kind": "oracle",
+            "value_one_core": flops / per_pass_1 / 1e9,
             "parity_max_componentwise_error": worst,
             "sample": "every layer of the step, all rows, float64 oracle with OpenMP over rows; "
                       "%d passes in %.1f s, %.4f s per pass" % (passes, per_pass * passes, per_pass)}
@@ -339,8 +371,17 @@ def main():
             L = Layer(synth.config(n, dt), torch, sp, kernel)
             ms = time_loop(torch, lambda L=L: L.launch(stream), 500, 50)
             msd = time_loop(torch, L.dense, 100, 10)
+            cur = lambda: ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+            g_sparse = graph_us(torch, lambda L=L: L.launch(cur()))
+            try:
+                g_dense = graph_us(torch, L.dense)
+            except Exception:   # a library call that cannot be captured
+                torch.cuda.synchronize()
+                g_dense = None
             side.append({"layer": n, "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
                          "dense_us": msd * 1e3, "speedup_vs_dense": msd / ms,
+                         "graph_us": g_sparse, "dense_graph_us": g_dense,
+                         "speedup_vs_dense_graph": (g_dense / g_sparse) if g_dense else None,
                          "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
                                                          "spec_tiles", "spec_ksplit", "spec_swizzle", "spec_vec")}})
             L.plan.destroy()
