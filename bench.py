@@ -169,6 +169,23 @@ def time_loop(torch, fn, iters, warmup):
     return e0.elapsed_time(e1) / iters
 
 
+def time_repeats(torch, fn, iters, warmup, repeats=5):
+    """(median, min, max) milliseconds per call over `repeats` timed loops of `iters` calls."""
+    t = sorted(time_loop(torch, fn, iters, warmup if r == 0 else 0) for r in range(repeats))
+    return t[len(t) // 2], t[0], t[-1]
+
+
+def device_clocks():
+    """Current shader / memory clocks as rocm-smi prints them, or None (clocks are left at their defaults)."""
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
+        card = next(iter(json.loads(r.stdout).values()))
+        return {k: v for k, v in card.items() if "sclk" in k or "mclk" in k}
+    except Exception:
+        return None
+
+
 def graph_us(torch, fn, inner=20, replays=20):
     """Microseconds per call of fn with `inner` calls captured in one HIP graph and replayed:
     neither side pays per-call host overhead (what matters for the few-microsecond configurations)."""
@@ -316,11 +333,12 @@ def main():
     iters = max(200, min(args.steps, 2000))
     per_layer = []
     for L in layers:
-        ms = time_loop(torch, lambda L=L: L.launch(stream), iters, 50)
+        ms, ms_min, ms_max = time_repeats(torch, lambda L=L: L.launch(stream), iters, 50)
         ms_dense = time_loop(torch, L.dense, max(50, iters // 10), 10)
         cold, n_sets = (ms * 1e3, 0) if args.no_cold else L.cold_us()
         per_layer.append({"layer": L.case.name, "M": L.M, "K": L.K, "N": L.N, "nnz": L.nnz,
-                          "us": ms * 1e3, "gflops": L.flops / ms / 1e6,
+                          "us": ms * 1e3, "us_min": ms_min * 1e3, "us_max": ms_max * 1e3, "repeats": 5,
+                          "launches_per_repeat": iters, "gflops": L.flops / ms / 1e6,
                           "cold_us": cold, "cold_operand_sets": n_sets,
                           "dense_us": ms_dense * 1e3, "speedup_vs_dense": ms_dense / ms, "dense_kind": L.dense_kind,
                           "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
@@ -351,6 +369,7 @@ def main():
         "dense_ms_per_step": dense_ms,
         "kernel_ms_per_step": sparse_ms,
         "layers": per_layer,
+        "clocks": device_clocks(),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(tag),
                      "kernel": "sparsert_spec_<M>x<K>x<N> (generated per layer) / sparsert::rows_kernel; see layers[].plan.kernel: 2 / 1",
