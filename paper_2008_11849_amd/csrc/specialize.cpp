@@ -207,7 +207,8 @@ struct Gen {
     int osz = 4;         // bytes of an element of C / Y
     int val_pos = 0;     // half / int8 plans: next slot of the value ring
     int V = 1;           // columns per lane: 2 halves or 4 int8 packed in the dword a lane loads
-    int vgpr_unpack0 = 0;  // int8, V = 4: four registers holding the sign-extended bytes of the current operand
+    int vgpr_unpack0 = 0;  // int8, V = 4: four registers holding the sign-extended bytes of the current operand;
+                           // half, V = 2: one register holding the widened high half
     int vgpr_stage0 = 0, vgpr_ring0 = 0, n_vgpr = 0, lds_bytes = 0;
     int ring_size = 0;               // DIRECT: registers of the operand ring (>= D)
     int slot_bytes = 256;            // K split: bytes of one row's partial sums in the exchange area
@@ -221,15 +222,20 @@ struct Gen {
     void zero_accs(size_t n) {
         for (size_t i = 0; i < n * (size_t)V; ++i) e.line("\tv_mov_b32_e32 v%d, 0", kVgprAcc0 + (int)i);
     }
-    // fp32: the value of A is a literal of the multiply-add.  Half storage: the operand sits in
-    // the low half of vb and v_fma_mix_f32 widens it on the fly (exact), multiplies by the
-    // value - widened to fp32 at generation time, exact as well, and moved through a scalar
-    // register because this encoding takes no literal - and accumulates in fp32.
+    // The value of A is a literal of the multiply-add.  Half storage: the operand just fetched is
+    // widened to fp32 in place, once per fetched row of B (exact), and the value - widened to fp32
+    // at generation time, exact as well - is the literal, so a nonzero costs one instruction as in
+    // fp32 and the sums are the same fp32 multiply-adds.
     int acc_reg(int row, int j = 0) const { return kVgprAcc0 + row * V + j; }
     void fmas(const std::vector<Term> &terms, int vb) {
         if (terms.empty()) return;
         if (int8 && V == 4)   // the four packed operands, sign-extended once per fetched row of B
             for (int j = 0; j < 4; ++j) e.line("\tv_bfe_i32 v%d, v%d, %d, 8", vgpr_unpack0 + j, vb, 8 * j);
+        if (half) {
+            if (V == 2)   // the high half of the dword is the next column
+                e.line("\tv_cvt_f32_f16_sdwa v%d, v%d dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1", vgpr_unpack0, vb);
+            e.line("\tv_cvt_f32_f16_e32 v%d, v%d", vb, vb);
+        }
         for (const Term &t : terms) {
             if (int8) {
                 // exact: both factors fit 24 bits; values in -16..64 are inline constants
@@ -245,14 +251,9 @@ struct Gen {
                 for (int j = 0; j < V; ++j)
                     e.line("\tv_mad_i32_i24 v%d, %s, v%d, v%d", acc_reg(t.acc, j), src, V == 4 ? vgpr_unpack0 + j : vb,
                            acc_reg(t.acc, j));
-            } else if (!half) {
-                e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", acc_reg(t.acc), t.bits, vb);
             } else {
-                const int sv = kSgprValRing + (val_pos++ % kValRing);
-                e.line("\ts_mov_b32 s%d, 0x%08x", sv, t.bits);
-                for (int j = 0; j < V; ++j)   // V = 2: the low and the high half of the dword are adjacent columns
-                    e.line("\tv_fma_mix_f32 v%d, s%d, v%d, v%d op_sel:[0,%d,0] op_sel_hi:[0,1,0]", acc_reg(t.acc, j), sv, vb,
-                           acc_reg(t.acc, j), j);
+                e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", acc_reg(t.acc), t.bits, vb);
+                if (V == 2) e.line("\tv_fmac_f32_e32 v%d, 0x%08x, v%d", acc_reg(t.acc, 1), t.bits, vgpr_unpack0);
             }
         }
     }
@@ -675,7 +676,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         gen.vgpr_ring0 = kVgprAcc0 + max_rows * V;
         gen.ring_size = KS > 1 ? std::max(D, 8) : D;   // the K-split exchange borrows the ring
         gen.vgpr_unpack0 = gen.vgpr_ring0 + gen.ring_size;
-        gen.n_vgpr = gen.vgpr_unpack0 + (int8 && V == 4 ? 4 : 0);
+        gen.n_vgpr = gen.vgpr_unpack0 + (int8 && V == 4 ? 4 : half && V == 2 ? 1 : 0);
         if (KS > 1) {
             gen.slot_bytes = 4 * V * max_lanes;   // a row's slot: V runs of max_lanes floats, lane l at byte 4*l of each
             gen.xchg_rows = std::min(max_rows, kMaxLdsBytes / ((KS - 1) * gen.slot_bytes));
