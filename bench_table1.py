@@ -70,8 +70,12 @@ def main():
                     help="storage type of weights, activations and results (sums are fp32 either way); the dense "
                          "baseline runs in the same type")
     ap.add_argument("--sweep", action="store_true",
-                    help="instead of the paper's list: the shape / sparsity sweep (M=K in 1024, 2048; N in 196, 1024, "
-                         "4096; 80, 90, 95, 98 %; uniform masks), effective GFLOP/s and speedup over dense per case")
+                    help="instead of the paper's list: the shape / sparsity sweep (--shapes, default 1024x1024 and 2048x2048; N in 196, 1024, "
+                         "4096; 80, 90, 95, 98 %; --mask), effective GFLOP/s and speedup over dense per case")
+    ap.add_argument("--shapes", default="1024x1024,2048x2048",
+                    help="--sweep: comma list of MxK weight shapes")
+    ap.add_argument("--mask", default="uniform", choices=["uniform", "magnitude", "skewed"],
+                    help="--sweep: how the kept weights are chosen (skewed: rows of very different lengths)")
     ap.add_argument("--markdown", default="", help="also write the results as a markdown summary to this path")
     ap.add_argument("--ablation", action="store_true",
                     help="also time, per problem, the best row-walk (not specialised) plan and the best plan "
@@ -176,19 +180,19 @@ def main():
             print(json.dumps(r), file=sys.stderr, flush=True)
 
     if args.sweep:
-        for MK in (1024, 2048):
+        for M, K in (tuple(int(x) for x in mk.split("x")) for mk in args.shapes.split(",")):
             for N in (196, 1024, 4096):
                 for sparsity in (0.80, 0.90, 0.95, 0.98):
-                    tag = f"sw_{MK}x{MK}x{N}_{int(round(sparsity * 100))}"
+                    tag = f"sw_{M}x{K}x{N}_{int(round(sparsity * 100))}"
                     if only and tag not in only:
                         continue
-                    case = synth.sweep_case(MK, MK, N, sparsity, "uniform", ndt)
+                    case = synth.sweep_case(M, K, N, sparsity, args.mask, ndt)
                     csr = case.csr
                     B = torch.from_numpy(case.B).to(dev)
-                    C = torch.empty((MK, N), dtype=tdt, device=dev)
+                    C = torch.empty((M, N), dtype=tdt, device=dev)
                     Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
                     r = run(tag, csr, N, B, C, lambda: torch.matmul(Ad, B))
-                    r.update(M=MK, K=MK, N=N, sparsity=sparsity, paper_speedup_t4="-")
+                    r.update(M=M, K=K, N=N, sparsity=sparsity, paper_speedup_t4="-")
                     rows.append(r)
                     print(json.dumps(r), file=sys.stderr, flush=True)
                     del Ad, B, C
@@ -223,7 +227,7 @@ def main():
                     "paper": "unrolled code over 10x faster than not unrolled; without load balancing comparable in "
                              "most cases; one fixed parameter choice about 2x slower (Section 4.3)"}
     result = {
-        "workload": ("shape / sparsity sweep, uniform masks, N(0,1) values, " if args.sweep else
+        "workload": (f"shape / sparsity sweep, {args.mask} masks, N(0,1) values, " if args.sweep else
                      "paper Table 1 (SpMM) and Table 3 (3x3 conv) shapes, synthetic magnitude-pruned weights, ") + args.dtype,
         "timing": f"{INNER} launches per HIP graph, 20 replays, HIP events; same for sparse and dense",
         "geomean_speedup_vs_dense": {"table1_90": gm("t1", 0.90), "table1_95": gm("t1", 0.95),
@@ -237,14 +241,15 @@ def main():
 
 
 def write_sweep_markdown(path, res, command):
-    lines = [f"# Shape / sparsity sweep on MI355X, uniform masks, {res['workload'].split()[-1]}", "",
+    mask = res["workload"].split(",")[1].strip()
+    lines = [f"# Shape / sparsity sweep on MI355X, {mask}, {res['workload'].split()[-1]}", "",
              f"command: `{command}` (one MI355X; plans from sparsert_tune; sparse and dense both timed as",
              f"{INNER} launches per HIP graph, 20 replays, HIP events; effective GFLOP/s = 2 nnz N / t).", "",
-             "| M = K | N | sparsity | sparse us | dense us | speedup | effective GFLOP/s | kernel | R | KS | swizzle |",
-             "|---|---|---|---|---|---|---|---|---|---|---|"]
+             "| M | K | N | sparsity | sparse us | dense us | speedup | effective GFLOP/s | kernel | R | KS | swizzle |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|"]
     for r in res["problems"]:
         p = r["plan"]
-        lines.append(f"| {r['M']} | {r['N']} | {r['sparsity']:.2f} | {r['sparse_us']:.2f} | {r['dense_us']:.2f} | "
+        lines.append(f"| {r['M']} | {r['K']} | {r['N']} | {r['sparsity']:.2f} | {r['sparse_us']:.2f} | {r['dense_us']:.2f} | "
                      f"{r['speedup']:.2f} | {r['gflops']:.0f} | {p['kernel']} | {p['spec_rows']} | {p['spec_ksplit']} | "
                      f"{p['spec_swizzle']} |")
     with open(path, "w") as f:
