@@ -71,7 +71,7 @@ def main():
                          "baseline runs in the same type")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the paper's list: the shape / sparsity sweep (--shapes, default 1024x1024 and 2048x2048; N in 196, 1024, "
-                         "4096; 80, 90, 95, 98 %; --mask), effective GFLOP/s and speedup over dense per case")
+                         "4096; 80, 90, 95, 98 %%; --mask), effective GFLOP/s and speedup over dense per case")
     ap.add_argument("--shapes", default="1024x1024,2048x2048",
                     help="--sweep: comma list of MxK weight shapes")
     ap.add_argument("--mask", default="uniform", choices=["uniform", "magnitude", "skewed"],
