@@ -279,6 +279,29 @@ def test_spec_half_rounds_once_at_the_store():
         assert got.tobytes() == want.tobytes(), opts
 
 
+def test_half_subnormals_are_kept():
+    """Half subnormals in B and in A are operands like any other (no flush to zero on the way in),
+    and a result in the subnormal range is rounded to the nearest subnormal, not to zero."""
+    tiny = np.float16(2.0 ** -24)          # smallest positive half subnormal
+    K, N = 6, 70
+    B = np.full((K, N), tiny, dtype=np.float16)
+    B[1, :] = np.float16(3 * 2.0 ** -24)
+    B[:, 1] = -B[:, 1]
+    A = np.zeros((3, K), dtype=np.float16)
+    A[0, 0] = 1024.0                       # 2^10 * 2^-24 = 2^-14: smallest normal half
+    A[1, 1] = 1.0                          # subnormal in, same subnormal out
+    A[1, 2] = 1.0                          # 3*2^-24 + 2^-24 = 2^-22
+    A[2, 3] = tiny                         # subnormal value of A times a subnormal of B: 2^-48, rounds to +-0
+    A[2, 4] = 0.5                          # 2^-25: a tie, rounds to even = 0; together with 2^-48 just above the tie -> 2^-24
+    csr = synth.csr_from_mask(A, A != 0)
+    want = _oracle(csr, B)[0].astype(np.float16)
+    assert want[0, 0] == np.float16(2.0 ** -14) and want[1, 0] == np.float16(2.0 ** -22) and want[2, 0] == tiny
+    assert want[2, 1] == -tiny
+    for opts in (dict(kernel=sp.KERNEL_ROWS), dict(spec_rows=3), dict(spec_rows=1), dict(spec_rows=3, spec_vec=2)):
+        got, _ = run_spmm(csr, B, **{"kernel": sp.KERNEL_SPEC, **opts})
+        assert got.tobytes() == want.tobytes(), opts
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c3t"])
 def test_spec_half_configs(name):
     case = synth.config(name, np.float16)
