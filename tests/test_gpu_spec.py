@@ -302,6 +302,27 @@ def test_half_subnormals_are_kept():
         assert got.tobytes() == want.tobytes(), opts
 
 
+def test_single_precision_subnormals_are_kept():
+    """fp32 subnormals as operands, as values of A (literals of the generated code) and as results."""
+    K, N = 5, 67
+    B = np.full((K, N), np.float32(2.0 ** -149), dtype=np.float32)
+    B[2, :] = 1024.0
+    B[:, 1] = -B[:, 1]
+    A = np.zeros((3, K), dtype=np.float32)
+    A[0, 0] = 2.0 ** 20                    # 2^-129: subnormal result from a subnormal operand
+    A[1, 2] = 2.0 ** -140                  # subnormal value of A: 2^-130
+    A[2, 1] = 3.0                          # 3 * 2^-149 ...
+    A[2, 3] = 1.0                          # ... + 2^-149 = 2^-147
+    csr = synth.csr_from_mask(A, A != 0)
+    want = _oracle(csr, B)[0].astype(np.float32)
+    assert want[0, 0] == np.float32(2.0 ** -129) and want[1, 0] == np.float32(2.0 ** -130)
+    assert want[2, 0] == np.float32(2.0 ** -147) and want[2, 1] == -want[2, 0]
+    for opts in (dict(kernel=sp.KERNEL_ROWS), dict(spec_rows=3), dict(spec_rows=1),
+                 dict(spec_rows=3, spec_mode=sp.SPEC_LDS)):
+        got, _ = run_spmm(csr, B, **{"kernel": sp.KERNEL_SPEC, **opts})
+        assert got.tobytes() == want.tobytes(), opts
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c3t"])
 def test_spec_half_configs(name):
     case = synth.config(name, np.float16)
