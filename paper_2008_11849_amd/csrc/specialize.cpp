@@ -184,7 +184,8 @@ constexpr int kSgprTap0 = 32;                  // conv: s[32:49] = lane masks of
 constexpr int kSgprFull = 50;                  // conv: s[50:51] = all lanes
 constexpr int kSgprImage = 52;                 // batch > 1: workgroup id z = image / matrix of the batch
 constexpr int kSgprValRing = 54, kValRing = 8; // half / int8 plans: s[54:61] values of A on their way into the multiply-add
-constexpr int kNextFreeSgpr = 62;
+constexpr int kSgprTab = 62, kTab = 32;        // DIRECT: s[62:93] = i * (bytes between consecutive operand rows), i < 32
+constexpr int kNextFreeSgpr = 94;
 constexpr int kVgprOff = 0;                    // byte offset of the lane's column inside a row
 constexpr int kVgprLds = 1;                    // LDS byte address of the lane's 16-byte slot
 constexpr int kVgprT1 = 2, kVgprT2 = 3, kVgprAcc0 = 4;
@@ -357,9 +358,52 @@ struct Gen {
         const int nc = (int)order.size();
         cur_mask = -1;
         zero_accs(rows.size());
+        // Byte offset of operand row k from the descriptor base (convolution: Section 3.6, operand row
+        // k = c*9 + tap is the input plane c displaced by the tap).
+        auto offset_of = [&](int32_t k) -> int64_t {
+            if (!h.conv) return (int64_t)k * N * esz;
+            const int c = k / 9, tap = k % 9;
+            return ((int64_t)c * h.H * h.W + (tap / 3) * h.W + tap % 3) * esz;
+        };
+        // Where the rows a block fetches lie close together, their offsets come from a table of
+        // multiples of the row pitch kept in scalar registers, and the lane's address register is
+        // advanced when a row falls outside the table's reach: no scalar move per fetch.  Blocks
+        // whose rows are far apart would advance at every fetch and keep the move instead.
+        const int64_t unit = h.conv ? (int64_t)h.H * h.W * esz : (int64_t)N * esz;
+        bool use_tab = false;
+        int tab_used = 0;
+        {
+            int64_t base = 0;
+            int bumps = 0;
+            for (int j = 0; j < nc; ++j) {
+                const int64_t d = offset_of(order[j]) - base;
+                if (d < 0 || d % unit || d / unit >= kTab) { ++bumps; base += d; }
+                else tab_used = std::max(tab_used, (int)(d / unit) + 1);
+            }
+            tab_used = std::max(tab_used, 1);
+            use_tab = nc >= 16 && (int64_t)bumps * (h.conv ? 12 : 4) <= nc;
+        }
+        if (use_tab)
+            for (int i = 0; i < tab_used; ++i)
+                e.line("\ts_mov_b32 s%d, 0x%llx", kSgprTab + i, (unsigned long long)(i * unit));
+        int64_t cur_base = 0;   // bytes the address register has been advanced by so far
         auto issue = [&](int j) {
-            if (h.conv) { want_mask(order[j] % 9); load_x_row(order[j], vgpr_ring0 + (j % D), j); }
-            else load_b_row(order[j], vgpr_ring0 + (j % D), j);
+            const int vdst = vgpr_ring0 + (j % D);
+            if (!use_tab) {
+                if (h.conv) { want_mask(order[j] % 9); load_x_row(order[j], vdst, j); }
+                else load_b_row(order[j], vdst, j);
+                return;
+            }
+            int64_t d = offset_of(order[j]) - cur_base;
+            if (d < 0 || d % unit || d / unit >= kTab) {
+                if (h.conv) want_mask(-1);   // every lane's address moves, whatever tap mask is current
+                e.line("\tv_add_u32_e32 v%d, 0x%x, v%d", kVgprOff, (uint32_t)(int32_t)d, kVgprOff);
+                cur_base += d;
+                d = 0;
+            }
+            if (h.conv) want_mask(order[j] % 9);
+            e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", load_op(), vdst, kVgprOff, kRsrcB, kRsrcB + 3,
+                   kSgprTab + (int)(d / unit));
         };
         for (int j = 0; j < std::min(D, nc); ++j) issue(j);
         for (int j = 0; j < nc; ++j) {
