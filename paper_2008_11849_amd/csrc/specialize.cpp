@@ -34,6 +34,7 @@
 #include <dlfcn.h>
 #include <map>
 #include <mutex>
+#include <stdexcept>
 
 #include "plan.h"
 
@@ -416,58 +417,100 @@ struct Gen {
         }
         if (parts > 1) {
             if (h.conv) want_mask(-1);
-            // Row i of the block belongs to wave i % parts.  Every wave leaves its partial sums of
-            // the rows it does not own in LDS, and after one barrier adds the other waves'
-            // partials to its own rows in ascending wave order, then stores those rows.  Blocks
-            // whose partial sums do not fit the LDS at once exchange them xchg_rows rows at a
-            // time, with a second barrier before the area is overwritten.
+            // The rows of the block are dealt to the waves in contiguous runs of ceil(rows / parts).
+            // Every wave leaves its partial sums of the rows it does not own in LDS, and after
+            // one barrier adds the other waves' partials to its own rows in ascending wave order,
+            // then stores those rows.  The accumulators of a run are consecutive registers, so
+            // they travel four (two, one) at a time: a piece of n registers from one wave is an
+            // LDS region [lane][n dwords], written and read with one 16- (8-, 4-) byte access per
+            // lane.  Blocks whose partial sums do not fit the LDS at once exchange them in phases
+            // of xchg_rows rows, with a second barrier before the area is overwritten.
             const int nr = (int)rows.size();
-            const int c = std::max(1, xchg_rows);
-            auto slot = [&](int i, int q) {   // byte offset of wave q's partial of row i of the phase, q != owner
-                const int o = i % parts;
-                return ((i % c) * (parts - 1) + (q < o ? q : q - 1)) * slot_bytes;
+            const int chunk = (nr + parts - 1) / parts;
+            auto own_lo = [&](int q) { return std::min(nr, q * chunk); };
+            auto own_hi = [&](int q) { return std::min(nr, (q + 1) * chunk); };
+            const int rb = slot_bytes / V;                        // bytes of one register's partials over the lanes of a tile
+            const int cq = nr <= xchg_rows ? std::max(1, chunk) : std::max(1, xchg_rows / parts);   // rows per owner and phase
+            const int n_phases = (chunk + cq - 1) / cq;
+            struct Piece { int reg, len, off; };                  // first register, registers, byte offset of the region
+            // address registers: lane * 4n for the three piece sizes, one set per 64 KiB window of
+            // the area (ds offsets are 16 bits wide); they and the temporaries borrow the operand ring
+            const int n_win = (lds_bytes + 65535) / 65536;
+            const int base0 = vgpr_ring0;
+            auto addr_reg = [&](int len, int off) {
+                const int m = len == 4 ? 2 : len == 2 ? 1 : 0, w = off >> 16;
+                return m == 0 && w == 0 ? kVgprLds : base0 + m * n_win + w - 1;
             };
-            // ds offsets are 16 bits wide: one address register per 64 KiB of the exchange area
-            const int n_base = ((parts - 1) * std::min(nr, c) * slot_bytes + 65535) / 65536;
-            const int base0 = vgpr_ring0;          // the operand ring is free now
-            for (int b = 1; b < n_base; ++b)
-                e.line("\tv_add_u32_e32 v%d, 0x%x, v%d", base0 + b, b * 65536, kVgprLds);
-            auto base_of = [&](int off) { return off < 65536 ? kVgprLds : base0 + off / 65536; };
-            const int tmp0 = base0 + std::max(n_base, 1);
-            const int batch = std::max(1, std::min(12, ring_size - std::max(n_base, 1)));
+            for (int m = 0; m < 3; ++m)
+                for (int w = 0; w < n_win; ++w) {
+                    if (m == 0 && w == 0) continue;
+                    const int r = addr_reg(1 << m, w << 16);
+                    if (m == 0) e.line("\tv_add_u32_e32 v%d, 0x%x, v%d", r, w * 65536, kVgprLds);
+                    else if (w == 0) e.line("\tv_lshlrev_b32_e32 v%d, %d, v%d", r, m, kVgprLds);
+                    else e.line("\tv_add_u32_e32 v%d, 0x%x, v%d", r, w * 65536, addr_reg(1 << m, 0));
+                }
+            const int tmp0 = (base0 + 3 * n_win - 1 + 1) / 2 * 2;   // even: 64-bit and wider operands need aligned registers
+            const int n_tmp = vgpr_ring0 + ring_size - tmp0;
+            if (n_tmp < 4) throw std::runtime_error("operand ring too small for the partial-sum exchange");
+            static const char *const kWidth[5] = {"", "b32", "b64", "", "b128"};
+            auto vregs = [](int r, int len, char *buf, size_t cap) {
+                if (len == 1) snprintf(buf, cap, "v%d", r); else snprintf(buf, cap, "v[%d:%d]", r, r + len - 1);
+            };
             std::vector<std::pair<int32_t, int>> mine;
-            const int lane_bytes = slot_bytes / V;   // column j of a row sits j * lane_bytes into the row's slot
-            for (int r0 = 0; r0 < nr; r0 += c) {
-                const int r1 = std::min(nr, r0 + c);
-                if (r0 > 0) e.line("\ts_barrier");   // every wave has read the previous phase
-                for (int i = r0; i < r1; ++i)
-                    if (i % parts != part)
-                        for (int j = 0; j < V; ++j) {
-                            const int off = slot(i, part) + j * lane_bytes;
-                            e.line("\tds_write_b32 v%d, v%d offset:%d", base_of(off), acc_reg(i, j), off & 65535);
+            for (int i = own_lo(part); i < own_hi(part); ++i) mine.push_back({rows[i], acc_reg(i)});
+            for (int ph = 0; ph < n_phases; ++ph) {
+                // layout of the phase: for every owner q and every other wave s, the pieces of
+                // q's rows of this phase as s left them
+                std::vector<std::vector<std::vector<Piece>>> lay(parts, std::vector<std::vector<Piece>>(parts));
+                int area = 0;
+                for (int q = 0; q < parts; ++q) {
+                    const int lo = std::min(own_hi(q), own_lo(q) + ph * cq), hi = std::min(own_hi(q), lo + cq);
+                    for (int sw = 0; sw < parts; ++sw) {
+                        if (sw == q) continue;
+                        for (int f = lo * V; f < hi * V;) {
+                            const int reg = kVgprAcc0 + f;
+                            const int len = (reg & 1) ? 1 : f + 4 <= hi * V ? 4 : f + 2 <= hi * V ? 2 : 1;
+                            lay[q][sw].push_back({reg, len, area});
+                            area += len * rb;
+                            f += len;
                         }
+                    }
+                }
+                if (area > lds_bytes) throw std::runtime_error("partial-sum exchange exceeds its LDS area");
+                if (ph > 0) e.line("\ts_barrier");   // every wave has read the previous phase
+                char regs[32];
+                for (int q = 0; q < parts; ++q)
+                    for (const Piece &pc : lay[q][part]) {
+                        vregs(pc.reg, pc.len, regs, sizeof(regs));
+                        e.line("\tds_write_%s v%d, %s offset:%d", kWidth[pc.len], addr_reg(pc.len, pc.off), regs, pc.off & 65535);
+                    }
                 e.line("\ts_waitcnt lgkmcnt(0)");
                 e.line("\ts_barrier");
-                struct Item { int row, j, src; };
-                std::vector<Item> items;  // in the order they are added
-                for (int i = r0; i < r1; ++i) {
-                    if (i % parts != part) continue;
-                    mine.push_back({rows[i], acc_reg(i)});
-                    for (int q = 0; q < parts; ++q)
-                        if (q != part)
-                            for (int j = 0; j < V; ++j) items.push_back({i, j, q});
-                }
-                for (size_t b0 = 0; b0 < items.size(); b0 += batch) {
-                    const size_t b1 = std::min(items.size(), b0 + batch);
-                    for (size_t t = b0; t < b1; ++t) {
-                        const int off = slot(items[t].row, items[t].src) + items[t].j * lane_bytes;
-                        e.line("\tds_read_b32 v%d, v%d offset:%d", tmp0 + (int)(t - b0), base_of(off), off & 65535);
+                std::vector<Piece> items;   // ascending source wave: the order the partials are added in
+                for (int sw = 0; sw < parts; ++sw) items.insert(items.end(), lay[part][sw].begin(), lay[part][sw].end());
+                for (size_t b0 = 0; b0 < items.size();) {
+                    std::vector<int> at;   // temporary of each piece of the batch
+                    int cur = 0;
+                    size_t b1 = b0;
+                    for (; b1 < items.size() && (int)at.size() < kMaxLgkm; ++b1) {
+                        const int len = items[b1].len;
+                        const int start = len > 1 ? (cur + 1) / 2 * 2 : cur;
+                        if (start + len > n_tmp) break;
+                        at.push_back(tmp0 + start);
+                        cur = start + len;
                     }
                     for (size_t t = b0; t < b1; ++t) {
-                        const int r = acc_reg(items[t].row, items[t].j);
+                        vregs(at[t - b0], items[t].len, regs, sizeof(regs));
+                        e.line("\tds_read_%s %s, v%d offset:%d", kWidth[items[t].len], regs, addr_reg(items[t].len, items[t].off),
+                               items[t].off & 65535);
+                    }
+                    for (size_t t = b0; t < b1; ++t) {
                         e.line("\ts_waitcnt lgkmcnt(%d)", (int)(b1 - 1 - t));
-                        e.line("\t%s v%d, v%d, v%d", int8 ? "v_add_u32_e32" : "v_add_f32_e32", r, r, tmp0 + (int)(t - b0));
+                        for (int j = 0; j < items[t].len; ++j)
+                            e.line("\t%s v%d, v%d, v%d", int8 ? "v_add_u32_e32" : "v_add_f32_e32", items[t].reg + j, items[t].reg + j,
+                                   at[t - b0] + j);
                     }
+                    b0 = b1;
                 }
             }
             stores(mine);
@@ -718,11 +761,11 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     } else {
         gen.V = V;
         gen.vgpr_ring0 = kVgprAcc0 + max_rows * V;
-        gen.ring_size = KS > 1 ? std::max(D, 8) : D;   // the K-split exchange borrows the ring
+        gen.ring_size = KS > 1 ? std::max(D, 20) : D;   // the K-split exchange borrows the ring: address registers and temporaries
         gen.vgpr_unpack0 = gen.vgpr_ring0 + gen.ring_size;
         gen.n_vgpr = gen.vgpr_unpack0 + (int8 && V == 4 ? 4 : half && V == 2 ? 1 : 0);
         if (KS > 1) {
-            gen.slot_bytes = 4 * V * max_lanes;   // a row's slot: V runs of max_lanes floats, lane l at byte 4*l of each
+            gen.slot_bytes = V * ((4 * max_lanes + 15) / 16 * 16);   // a row's partial sums: V registers over the lanes of a tile, 16-byte granules
             gen.xchg_rows = std::min(max_rows, kMaxLdsBytes / ((KS - 1) * gen.slot_bytes));
             gen.lds_bytes = (KS - 1) * gen.xchg_rows * gen.slot_bytes;
             if (gen.lds_bytes == 0) gen.lds_bytes = 256;
