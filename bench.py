@@ -321,11 +321,15 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    r0.record()
     for _ in range(args.steps):
         step()
+    r1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    region_us_per_launch = r0.elapsed_time(r1) * 1e3 / (args.steps * len(layers))   # HIP events around the timed region
     ms_per_step = wall * 1e3 / args.steps
     flops_step = sum(L.flops for L in layers)
 
@@ -382,6 +386,8 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(tag),
                      "kernel": "sparsert_spec_<M>x<K>x<N> (generated per layer) / sparsert::rows_kernel; see layers[].plan.kernel: 2 / 1",
                      "avg_launch_us": kernel_ms * 1e3,
+                     "avg_launch_us_timed_region": region_us_per_launch,
+                     "frac_timed_region": alg_bytes / (region_us_per_launch * 1e-6) / 1e9 / HBM_PEAK_GBS,
                      "avg_launch_us_cold_operands": sum(p["cold_us"] for p in per_layer) / len(per_layer),
                      "frac_cold_operands": alg_bytes / (sum(p["cold_us"] for p in per_layer) / len(per_layer) * 1e-6) / 1e9
                                            / HBM_PEAK_GBS,
