@@ -18,6 +18,9 @@
 //           finally one store per row.  No loops, no index loads.
 //   DIRECT: workgroup = T waves running the same block on T adjacent tiles; b comes
 //           straight from L2/L1 with buffer loads.
+//   DIRECT with K split: workgroup = KS waves sharing one block and one tile, each walking
+//           a contiguous range of the block's columns with an equal share of its nonzeros
+//           (Section 3.4); the partial sums meet in LDS after the walk (Section 3.3).
 //   LDS   : workgroup = W waves running W adjacent blocks on the same tile.  The tile's
 //           B rows are staged once per workgroup through LDS in chunks of up to 128 rows
 //           (double buffered, one barrier per chunk; each wave fetches a 1/W share) and
@@ -358,7 +361,6 @@ struct Gen {
         }
         const int nc = (int)order.size();
         cur_mask = -1;
-        zero_accs(rows.size());
         // Byte offset of operand row k from the descriptor base (convolution: Section 3.6, operand row
         // k = c*9 + tap is the input plane c displaced by the tap).
         auto offset_of = [&](int32_t k) -> int64_t {
@@ -407,6 +409,9 @@ struct Gen {
                    kSgprTab + (int)(d / unit));
         };
         for (int j = 0; j < std::min(D, nc); ++j) issue(j);
+        // the accumulators are cleared while the first fetches are on their way
+        if (h.conv) want_mask(-1);
+        zero_accs(rows.size());
         for (int j = 0; j < nc; ++j) {
             // loads issued so far: columns [0, min(nc, j + D)); those after column j may stay in
             // flight.  (Waiting once per batch of columns was measured slower than once per column.)
