@@ -187,6 +187,7 @@ constexpr int kSgprOffRing = 24, kOffRing = 8; // s[24:31] row-offset literals i
 constexpr int kSgprTap0 = 32;                  // conv: s[32:49] = lane masks of the 9 filter taps
 constexpr int kSgprFull = 50;                  // conv: s[50:51] = all lanes
 constexpr int kSgprImage = 52;                 // batch > 1: workgroup id z = image / matrix of the batch
+constexpr int kSgprJump = 53;                  // offset of the block's code from the table
 constexpr int kSgprValRing = 54, kValRing = 8; // half / int8 plans: s[54:61] values of A on their way into the multiply-add
 constexpr int kSgprTab = 62, kTab = 32;        // DIRECT: s[62:93] = i * (bytes between consecutive operand rows), i < 32
 constexpr int kNextFreeSgpr = 94;
@@ -823,6 +824,14 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         e.line("\ts_mov_b32 s%d, s2", kSgprTile);
         e.line("\tv_lshlrev_b32_e32 v%d, 4, v%d", kVgprLds, kVgprOff);  // lane * 16
     }
+    // offset of this block's code, from a table kept in the text section: fetched now, needed
+    // at the end of the prologue, so its latency overlaps the kernel arguments' and the lane set-up
+    e.line("\ts_getpc_b64 s[%d:%d]", kSgprPc, kSgprPc + 1);
+    e.line(".Lpc:");
+    e.line("\ts_add_u32 s%d, s%d, .Ltable-.Lpc", kSgprPc, kSgprPc);
+    e.line("\ts_addc_u32 s%d, s%d, 0", kSgprPc + 1, kSgprPc + 1);
+    e.line("\ts_lshl_b32 s%d, s%d, 2", kSgprJump, kSgprBlock);
+    e.line("\ts_load_dword s%d, s[%d:%d], s%d", kSgprJump, kSgprPc, kSgprPc + 1, kSgprJump);
     e.line("\ts_mul_i32 s%d, s%d, %d", kSgprTmp, kSgprTile, sp.lanes_per_tile);  // first column of the tile
     e.line("\tv_add_u32_e32 v%d, s%d, v%d", kVgprT1, kSgprTmp, kVgprOff);        // this lane's column
     e.line("\ts_mov_b32 s%d, %d", kSgprTmp2, nvc);
@@ -898,15 +907,8 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("\ts_and_b32 s%d, s%d, 0xffff", kRsrcC + 1, kSgprC + 1);
     e.line("\ts_mov_b32 s%d, 0x%llx", kRsrcC + 2, (unsigned long long)c_bytes);
     e.line("\ts_mov_b32 s%d, 0x%x", kRsrcC + 3, kRsrcWord3);
-    // jump to the code of this block through a table of offsets kept in the text section
-    e.line("\ts_getpc_b64 s[%d:%d]", kSgprPc, kSgprPc + 1);
-    e.line(".Lpc:");
-    e.line("\ts_add_u32 s%d, s%d, .Ltable-.Lpc", kSgprPc, kSgprPc);
-    e.line("\ts_addc_u32 s%d, s%d, 0", kSgprPc + 1, kSgprPc + 1);
-    e.line("\ts_lshl_b32 s%d, s%d, 2", kSgprTmp, kSgprBlock);
-    e.line("\ts_load_dword s%d, s[%d:%d], s%d", kSgprTmp2, kSgprPc, kSgprPc + 1, kSgprTmp);
-    e.line("\ts_waitcnt lgkmcnt(0)");
-    e.line("\ts_add_u32 s%d, s%d, s%d", kSgprPc, kSgprPc, kSgprTmp2);
+    // jump to the code of this block (the table entry arrived with the kernel arguments)
+    e.line("\ts_add_u32 s%d, s%d, s%d", kSgprPc, kSgprPc, kSgprJump);
     e.line("\ts_addc_u32 s%d, s%d, 0", kSgprPc + 1, kSgprPc + 1);
     e.line("\ts_setpc_b64 s[%d:%d]", kSgprPc, kSgprPc + 1);
     e.line(".Lend:");
