@@ -375,22 +375,17 @@ struct Gen {
         // whose rows are far apart would advance at every fetch and keep the move instead.
         const int64_t unit = h.conv ? (int64_t)h.H * h.W * esz : (int64_t)N * esz;
         bool use_tab = false;
-        int tab_used = 0;
         {
             int64_t base = 0;
             int bumps = 0;
             for (int j = 0; j < nc; ++j) {
                 const int64_t d = offset_of(order[j]) - base;
                 if (d < 0 || d % unit || d / unit >= kTab) { ++bumps; base += d; }
-                else tab_used = std::max(tab_used, (int)(d / unit) + 1);
             }
-            tab_used = std::max(tab_used, 1);
             use_tab = nc >= 16 && (int64_t)bumps * (h.conv ? 12 : 4) <= nc;
         }
-        if (use_tab)
-            for (int i = 0; i < tab_used; ++i)
-                e.line("\ts_mov_b32 s%d, 0x%llx", kSgprTab + i, (unsigned long long)(i * unit));
-        int64_t cur_base = 0;   // bytes the address register has been advanced by so far
+        bool tab_ready[kTab] = {false};   // an entry is written right before its first use, so no fetch waits for the whole table
+        int64_t cur_base = 0;             // bytes the address register has been advanced by so far
         auto issue = [&](int j) {
             const int vdst = vgpr_ring0 + (j % D);
             if (!use_tab) {
@@ -406,8 +401,12 @@ struct Gen {
                 d = 0;
             }
             if (h.conv) want_mask(order[j] % 9);
-            e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", load_op(), vdst, kVgprOff, kRsrcB, kRsrcB + 3,
-                   kSgprTab + (int)(d / unit));
+            const int slot = (int)(d / unit);
+            if (!tab_ready[slot]) {
+                e.line("\ts_mov_b32 s%d, 0x%llx", kSgprTab + slot, (unsigned long long)(slot * unit));
+                tab_ready[slot] = true;
+            }
+            e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", load_op(), vdst, kVgprOff, kRsrcB, kRsrcB + 3, kSgprTab + slot);
         };
         for (int j = 0; j < std::min(D, nc); ++j) issue(j);
         // the accumulators are cleared while the first fetches are on their way
