@@ -77,7 +77,8 @@ typedef struct sparsert_options {
     int32_t split_threshold; /* rows with at least this many nonzeros are split over the
                                 waves of a workgroup; 0 = automatic */
     int32_t spec_rows;       /* SPARSERT_KERNEL_SPEC: rows of A per generated code block
-                                (accumulator registers per wave); 0 = automatic */
+                                (accumulator registers per wave); 0 = automatic: as many as leave
+                                the launch about two waves per SIMD of the chip, at most 96 */
     int32_t spec_depth;      /* SPARSERT_KERNEL_SPEC: B rows a wave keeps in flight; 0 = automatic */
     int32_t spec_tiles;      /* SPARSERT_KERNEL_SPEC: waves per workgroup (adjacent column tiles in
                                 DIRECT mode, adjacent code blocks in LDS mode): 1,2,4,8,16;
@@ -86,7 +87,9 @@ typedef struct sparsert_options {
     int32_t spec_ksplit;     /* SPARSERT_KERNEL_SPEC, DIRECT: 2, 4 or 8 waves of a workgroup share one
                                 code block's rows and column tile and split its columns (equal
                                 nonzero shares, partial sums meet in LDS, in several phases if
-                                they exceed it); 0/1 = no split.  Sets the workgroup width,
+                                they exceed it); 1 = no split; 0 = no split if spec_rows is given,
+                                automatic if spec_rows is 0 too (split where K >= 512 and the
+                                rows alone do not supply the waves).  Sets the workgroup width,
                                 spec_tiles is then ignored */
     int32_t natural_order;   /* 1: load-balance ablation (Section 4.3): rows keep their input order
                                 (identity permutation), no row is split over waves, and the

@@ -659,22 +659,33 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     sp.n_tiles = (nvc + max_lanes - 1) / max_lanes;
     sp.lanes_per_tile = (nvc + sp.n_tiles - 1) / sp.n_tiles;
     sp.tiles_per_wg = opt.spec_tiles ? opt.spec_tiles : 4;
-    sp.ksplit = opt.spec_ksplit ? opt.spec_ksplit : 1;
+    // Rows per block and K split.  Left at 0 they follow what the tuner's winners have in common
+    // on this chip: a launch of about two waves per SIMD (2048 waves), with as many rows per
+    // block as that allows, because rows per block is what saves fetches of B, and with the
+    // reduction axis split over the waves of a workgroup where it is long enough to supply them.
+    int R = opt.spec_rows;
+    int KS = opt.spec_ksplit;
+    if (KS == 0) KS = (!lds && R == 0 && h.K >= 512) ? 8 : 1;
+    if (R == 0 && lds) {
+        // LDS variant: R1 fills 1024 SIMDs with one wave each, R2 gives a wave about 400 multiply-adds
+        const int64_t r1 = (int64_t)M * sp.n_tiles / 1024;
+        const int64_t avg = std::max<int64_t>(1, h.nnz / M);
+        const int64_t r2 = (400 + avg - 1) / avg;
+        R = (int)std::min<int64_t>(96, std::max<int64_t>(4, std::max(r1, r2)));
+    } else if (R == 0) {
+        const int64_t tiles_all = (int64_t)sp.n_tiles * std::max(1, h.batch);
+        const int64_t target = KS > 1 ? 2048 : 1024;
+        R = (int)std::max<int64_t>(1, std::min<int64_t>(96 / V, (int64_t)M * tiles_all * KS / target));
+        if (opt.spec_ksplit == 0)   // fewer parts where the rows alone already supply the waves
+            while (KS > 1 && ((int64_t)M + R - 1) / R * tiles_all * (KS / 2) >= 2048) KS /= 2;
+    }
+    sp.ksplit = KS;
     if (sp.ksplit != 1 && sp.ksplit != 2 && sp.ksplit != 4 && sp.ksplit != 8) { err = "spec_ksplit must be 0,1,2,4,8"; return SPARSERT_EINVAL; }
     if (sp.ksplit > 1 && lds) { err = "spec_ksplit applies to the DIRECT variant"; return SPARSERT_EINVAL; }
     if (sp.ksplit > 1) sp.tiles_per_wg = sp.ksplit;   // the waves of a workgroup are the K parts
     const int W = sp.tiles_per_wg;
     int wshift = 0;
     while ((1 << wshift) < W) ++wshift;
-    // Rows per group: enough rows that a fetched B row is reused, few enough that the chip is
-    // filled: R1 fills 1024 SIMDs with one wave each, R2 gives a wave about 400 multiply-adds.
-    int R = opt.spec_rows;
-    if (R == 0) {
-        const int64_t r1 = (int64_t)M * sp.n_tiles / 1024;
-        const int64_t avg = std::max<int64_t>(1, h.nnz / M);
-        const int64_t r2 = (400 + avg - 1) / avg;
-        R = (int)std::min<int64_t>(96, std::max<int64_t>(4, std::max(r1, r2)));
-    }
     if (R < 1 || R > 200) { err = "spec_rows must be in 1..200"; return SPARSERT_EINVAL; }
     R = std::min(R, M);
     sp.rows_per_group = R;
@@ -686,7 +697,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     const int G = sp.n_groups;
     // LDS mode: a workgroup runs W consecutive blocks and every one of them takes part in the
     // staging and the barriers, so the block list is padded with empty blocks.
-    const int KS = sp.ksplit;
+    KS = sp.ksplit;
     const int n_blocks = lds ? (G + W - 1) / W * W : G * KS;
     sp.n_blocks = n_blocks;
     sp.group_of_slot.resize(M);

@@ -282,6 +282,26 @@ def test_null_pointers_and_host_only_execution_are_rejected():
     lib.sparsert_plan_destroy(None)
 
 
+@pytest.mark.parametrize("M,K,N,batch,rows,ksplit", [
+    (3072, 768, 1024, 1, 96, 4),     # c3: rows capped at 96, four parts already give 2048 waves
+    (768, 3072, 1024, 1, 48, 8),     # c3t: 16 blocks x 16 tiles x 8 parts = 2048 waves
+    (256, 128, 784, 1, 3, 1),        # short reduction axis: no split, about 1024 waves
+    (512, 512, 196, 1, 8, 8),
+    (512, 512, 196, 4, 32, 8),       # the problems of a batch bring their own waves
+    (64, 1024, 64, 1, 1, 8),         # tiny: one row per block, everything else from the split
+])
+def test_untuned_defaults_of_the_generated_kernel(M, K, N, batch, rows, ksplit):
+    """spec_rows = spec_ksplit = 0: as many rows per block as leave about two waves per SIMD
+    (2048 waves), the reduction axis split over up to eight waves where K >= 512."""
+    csr = synth.uniform_csr(M, K, 0.98, 11)
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, M, K, N, host_only=True, kernel=sp.KERNEL_SPEC, batch=batch)
+    info = plan.info()
+    assert (info["spec_rows"], info["spec_ksplit"]) == (rows, ksplit)
+    # an explicit row count keeps the split off unless it is asked for
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, M, K, N, host_only=True, kernel=sp.KERNEL_SPEC, spec_rows=2)
+    assert plan.info()["spec_ksplit"] == 1
+
+
 @pytest.mark.parametrize("mode", [sp.SPEC_DIRECT, sp.SPEC_LDS])
 @pytest.mark.parametrize("rows", [1, 7, 24])
 def test_generated_kernel_plan_assembles_on_the_host(rows, mode):
