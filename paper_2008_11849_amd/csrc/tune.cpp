@@ -6,10 +6,14 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
+#include <condition_variable>
 #include <cstring>
 #include <exception>
+#include <mutex>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "plan.h"
@@ -181,9 +185,67 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         t.microseconds = us;
     };
     log(best, best_us);
-    for (const sparsert_options &o : cands) {
+    // The host half of a candidate (analysis, code generation, assembling: seconds for a large
+    // matrix) is independent of every other candidate's, so a few host threads build the plans
+    // ahead, in list order and at most `window` beyond the one being timed; this thread uploads
+    // and times them one after the other.
+    struct Built { sparsert_plan *plan = nullptr; bool ready = false; };
+    std::vector<Built> built(cands.size());
+    std::mutex mu;
+    std::condition_variable cv;
+    size_t next = 0, consumed = 0;
+    bool stop = false;
+    const size_t window = 8;
+    auto worker = [&]() {
+        for (;;) {
+            size_t i;
+            {
+                std::unique_lock<std::mutex> lk(mu);
+                cv.wait(lk, [&] { return stop || next >= cands.size() || next < consumed + window; });
+                if (stop || next >= cands.size()) return;
+                i = next++;
+            }
+            sparsert_options o = cands[i];
+            o.host_only = 1;
+            sparsert_plan *p = nullptr;
+            if (sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &p) != SPARSERT_OK) p = nullptr;
+            {
+                std::lock_guard<std::mutex> lk(mu);
+                built[i].plan = p;
+                built[i].ready = true;
+            }
+            cv.notify_all();
+        }
+    };
+    struct Pool {   // joins on every way out; plans built but never consumed are released
+        std::vector<std::thread> threads;
+        std::mutex &mu; std::condition_variable &cv; bool &stop; std::vector<Built> &built;
+        ~Pool() {
+            { std::lock_guard<std::mutex> lk(mu); stop = true; }
+            cv.notify_all();
+            for (std::thread &t : threads) if (t.joinable()) t.join();
+            for (Built &b : built) if (b.plan) sparsert_plan_destroy(b.plan);
+        }
+    } pool{{}, mu, cv, stop, built};
+    const unsigned hw = std::thread::hardware_concurrency();
+    const size_t n_threads = std::min<size_t>(cands.size(), std::max(1u, std::min(4u, hw / 2)));
+    for (size_t t = 0; t < n_threads; ++t) pool.threads.emplace_back(worker);
+    for (size_t i = 0; i < cands.size(); ++i) {
         sparsert_plan *p = nullptr;
-        if (sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &p) != SPARSERT_OK) continue;
+        {
+            std::unique_lock<std::mutex> lk(mu);
+            cv.wait(lk, [&] { return built[i].ready; });
+            p = built[i].plan;
+            built[i].plan = nullptr;
+            consumed = i + 1;
+        }
+        cv.notify_all();
+        if (!p) continue;
+        {
+            std::string err;
+            if (sparsert::upload_plan(p->host, p->dev, err) != SPARSERT_OK) { sparsert_plan_destroy(p); continue; }
+            p->on_device = true;
+        }
         const float us = time_plan(p, conv, in_dev, out_dev, s, e0, e1, launches, repeats);
         log(p, us);
         if (us > 0.0f && (best_us <= 0.0f || us < best_us)) {
