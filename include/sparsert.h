@@ -16,6 +16,10 @@
  *   - Every function returns a status code (sparsert_status: 0 = ok, negative = error) and
  *     never aborts; sparsert_last_error() gives a thread-local message.
  *   - No torch / C++ types cross this boundary.
+ *   - Threads: every entry point may be called from several host threads at once; calls that
+ *     make a plan (inspect, tune, plan_load) each build their own, and a finished plan is
+ *     read only.  sparsert_tune starts a few short-lived host threads of its own to prepare
+ *     its candidates and joins them before it returns.
  */
 #ifndef SPARSERT_H
 #define SPARSERT_H

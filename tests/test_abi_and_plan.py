@@ -282,6 +282,37 @@ def test_null_pointers_and_host_only_execution_are_rejected():
     lib.sparsert_plan_destroy(None)
 
 
+def test_inspect_from_several_threads_at_once():
+    """Plans made concurrently (code generation and assembling included) equal the ones made alone."""
+    import threading
+    cases = [synth.magnitude_csr(150 + 10 * i, 200, 0.9, i) for i in range(6)]
+
+    def code_of(a):
+        p = sp.inspect(a.row_ptr, a.col_idx, a.vals, a.M, a.K, 196, kernel=sp.KERNEL_SPEC, spec_rows=8,
+                       spec_ksplit=2, host_only=True)
+        code = p.export(sp.FIELD_SPEC_CODE).tobytes()
+        p.destroy()
+        return code
+
+    alone = [code_of(a) for a in cases]
+    together, errors = [None] * len(cases), []
+
+    def work(i):
+        try:
+            for _ in range(3):
+                together[i] = code_of(cases[i])
+        except Exception as ex:   # reported by the asserting thread
+            errors.append((i, repr(ex)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(len(cases))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors
+    assert together == alone
+
+
 @pytest.mark.parametrize("M,K,N,batch,rows,ksplit", [
     (3072, 768, 1024, 1, 96, 4),     # c3: rows capped at 96, four parts already give 2048 waves
     (768, 3072, 1024, 1, 48, 8),     # c3t: 16 blocks x 16 tiles x 8 parts = 2048 waves
