@@ -20,8 +20,6 @@
 
 namespace {
 
-struct Candidate { sparsert_options opt; };
-
 float time_plan(sparsert_plan *p, bool conv, const void *in, void *out, hipStream_t s,
                 hipEvent_t e0, hipEvent_t e1, int launches, int repeats) {
     auto run = [&]() { return conv ? sparsert_conv3x3(p, in, out, s) : sparsert_spmm(p, in, out, s); };
