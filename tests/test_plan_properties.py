@@ -131,3 +131,30 @@ def test_generator_accepts_or_refuses_but_never_breaks(request_):
     assert again.export(sp.FIELD_SPEC_CODE).tobytes() == code.tobytes()
     plan.destroy()
     again.destroy()
+
+
+@pytest.mark.parametrize("dtype,vecs", [(np.float32, (1,)), (np.float16, (1, 2)), (np.int8, (1, 4))])
+def test_k_split_exchange_assembles_over_its_parameter_grid(dtype, vecs):
+    """Rows per block x K split x packed columns x tile width: every combination the register file
+    allows must generate and assemble (odd run lengths, several 64 KiB LDS windows, phases when the
+    partial sums exceed the LDS), and the exchange area never exceeds a compute unit's LDS."""
+    built = 0
+    for M, K in ((200, 48),):
+        a = synth.int8_csr(M, K, 0.6, 5) if dtype == np.int8 else synth.small_int_csr(M, K, 0.6, 5, dtype)
+        for rows in (1, 3, 13, 50, 96, 192):
+            for ks in (2, 4, 8):
+                for vec in vecs:
+                    for lanes, N in ((0, 128), (32, 64), (0, 196)):
+                        if N % vec or rows * vec > 220:
+                            continue
+                        try:
+                            plan = sp.inspect(a.row_ptr, a.col_idx, a.vals, M, K, N, kernel=sp.KERNEL_SPEC, spec_rows=rows,
+                                              spec_ksplit=ks, spec_vec=vec, spec_lanes=lanes, host_only=True)
+                        except sp.SparseRTError as ex:   # the only refusal allowed here: too many accumulators
+                            assert "register file" in str(ex), (M, K, rows, ks, vec, lanes, N, str(ex))
+                            continue
+                        info = plan.info()
+                        assert info["spec_ksplit"] == ks and 0 < info["spec_lds_bytes"] <= 160 * 1024
+                        plan.destroy()
+                        built += 1
+    assert built > 40
