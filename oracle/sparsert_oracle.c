@@ -6,11 +6,11 @@
  * plain, slow, obviously correct statement of what they must compute.  It
  * shares no code, header, table or helper with the HIP library.
  *
- * What is computed is the exact mathematical result the paper's method
- * reaches by skipping zero terms (Introduction: "start from a dense matrix
- * multiplication and remove unnecessary computations"; Section 3.5: keep
- * only the terms of nonzero A elements), so the oracle is that definition
- * written out, in double precision, with no blocking, fusion or reordering.
+ * What is computed is the exact product: the method reaches it by leaving out
+ * the terms of the zero elements of A and changes nothing else (the
+ * definition of Section 3.2, with Section 3.5's restriction to the nonzeros
+ * of A), so the oracle is that definition written out, in double precision,
+ * with no blocking, fusion or reordering.
  */
 #include <stddef.h>
 #include <stdint.h>
