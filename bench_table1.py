@@ -7,7 +7,10 @@ paper's pruned checkpoints are not available; weights are magnitude-pruned N(0,1
 the same shapes.  For every problem the sparse path (plan chosen by sparsert_tune) and the
 dense baseline of the same shape on the same GPU (torch.matmul / conv2d, fp32, no TF32) are
 timed the same way: 20 launches captured in one HIP graph, replayed, HIP events around the
-replays - so neither side pays per-call host overhead.  Prints one JSON line with the
+replays - so neither side pays per-call host overhead.  Every timed plan's output is compared
+with the CPU oracle (all elements; a seeded sample of rows for the largest sweep cases) and a
+mismatch beyond the storage type's tolerance ends the run with an error, so no time in the
+tables belongs to a result nobody checked.  Prints one JSON line with the
 per-problem times and the geometric-mean speedups next to the paper's (Tesla T4: 3.4x at
 90 %, 5.4x at 95 %; context, not a target).
 """
@@ -24,15 +27,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# (M, K, N) of Table 1, problems 1..20; problems 1-11 also at 95 %
-TABLE1 = [(64, 256, 3136), (256, 64, 3136), (128, 512, 784), (512, 128, 784), (256, 1024, 196),
-          (1024, 256, 196), (512, 2048, 49), (2048, 512, 49), (2048, 512, 256), (512, 2048, 256),
-          (512, 512, 256), (64, 32, 12544), (128, 64, 3136), (128, 128, 3136), (256, 128, 784),
-          (256, 256, 784), (512, 256, 196), (512, 512, 196), (1024, 512, 49), (1024, 1024, 49)]
 PAPER_T1 = {0.90: [4.3, 2.5, 4.0, 3.7, 3.0, 3.1, 2.7, 4.8, 4.2, 4.2, 6.0, 1.4, 3.4, 4.0, 4.2, 3.5, 2.3, 3.2, 2.6, 4.5],
             0.95: [5.7, 3.0, 5.9, 4.5, 4.4, 4.2, 4.5, 6.6, 6.8, 7.6, 9.0]}
-# (image, Cin, Cout) of Table 3
-TABLE3 = [(56, 64, 64), (28, 128, 128), (14, 256, 256), (7, 512, 512)]
 PAPER_T3 = {0.90: [3.7, 2.0, 1.4, 2.4], 0.95: [5.3, 3.5, 2.5, 8.5]}
 INNER = 20
 
@@ -73,7 +69,13 @@ def main():
                     help="instead of the paper's list: the shape / sparsity sweep (--shapes, default 1024x1024 and 2048x2048; N in 196, 1024, "
                          "4096; 80, 90, 95, 98 %%; --mask), effective GFLOP/s and speedup over dense per case")
     ap.add_argument("--shapes", default="1024x1024,2048x2048",
-                    help="--sweep: comma list of MxK weight shapes")
+                    help="--sweep: comma list of MxK weight shapes; 'grid' = the squares 256..4096 and the "
+                         "4096x1024 / 1024x4096 rectangles of the sweep configuration")
+    ap.add_argument("--ns", default="196,1024,4096", help="--sweep: comma list of N; 'grid' = 64,196,784,3136,4096")
+    ap.add_argument("--sparsities", default="0.8,0.9,0.95,0.98", help="--sweep: comma list of sparsity levels")
+    ap.add_argument("--plans", default="tune", choices=["tune", "auto", "mixed"],
+                    help="--sweep: tune = sparsert_tune per case; auto = the plan sparsert_inspect returns without "
+                         "options; mixed = tune up to 150000 nonzeros, auto beyond (tuning assembles dozens of kernels)")
     ap.add_argument("--mask", default="uniform", choices=["uniform", "magnitude", "skewed"],
                     help="--sweep: how the kept weights are chosen (skewed: rows of very different lengths)")
     ap.add_argument("--markdown", default="", help="also write the results as a markdown summary to this path")
@@ -94,13 +96,51 @@ def main():
     only = set(filter(None, args.only.split(",")))
     rows = []
 
-    def run(tag, csr, N, inp, out, dense_fn, conv=None, batch=0):
+    from oracle import ref   # the CPU oracle checks every timed output; it is no part of the timed path
+    tol = 2e-2 if args.dtype == "f16" else 1e-4
+    checked = {"plans": 0, "worst": 0.0}
+
+    def oracle_for(case):
+        """(rows, reference, scale): every row, or for the largest cases a seeded sample of 64 rows."""
+        csr = case.csr
+        if case.conv is not None:
+            want, scale = ref.conv3x3(case.Wdense, case.X)
+            return None, want, scale
+        if csr.nnz * case.N <= 600e6:
+            want, scale = ref.spmm(csr.M, csr.K, case.N, csr.row_ptr, csr.col_idx, csr.vals, case.B)
+            return None, want, scale
+        rows = np.sort(np.random.default_rng(csr.nnz).choice(csr.M, size=64, replace=False))
+        rp = csr.row_ptr
+        ptr = np.concatenate([[0], np.cumsum(rp[rows + 1] - rp[rows])]).astype(np.int32)
+        cols = np.concatenate([csr.col_idx[rp[r]:rp[r + 1]] for r in rows])
+        vals = np.concatenate([csr.vals[rp[r]:rp[r + 1]] for r in rows])
+        want, scale = ref.spmm(len(rows), csr.K, case.N, ptr, cols, vals, case.B)
+        return rows, want, scale
+
+    def verify(tag, what, out, oracle):
+        rows, want, scale = oracle
+        got = out.cpu().numpy()
+        got = got if rows is None else got[rows]
+        m = ref.error_metrics(got.reshape(want.shape), want, scale)
+        ok = (not np.isnan(got).any()) and m["exact_on_zero_scale"] and m["componentwise"] <= tol and m["normwise"] <= tol
+        if not ok:
+            print(f"bench_table1.py: {tag} ({what}): the timed plan disagrees with the oracle: {m}", file=sys.stderr)
+            sys.exit(1)
+        checked["plans"] += 1
+        checked["worst"] = max(checked["worst"], m["componentwise"])
+        return m["componentwise"]
+
+    def run(tag, case, inp, out, dense_fn, batch=0):
+        csr, N, conv = case.csr, case.N, case.conv
+        oracle = oracle_for(case)
         cur = lambda: torch.cuda.current_stream().cuda_stream
         fn = sp.raw.sparsert_conv3x3 if conv else sp.raw.sparsert_spmm
         a, b = ctypes.c_void_p(inp.data_ptr()), ctypes.c_void_p(out.data_ptr())
 
-        def tuned(untuned=False, fixed=False, **kw):
-            if untuned:   # no timing runs: the generated kernel with the inspector's shape-dependent defaults
+        def tuned(untuned=False, fixed=False, auto=False, what="tuned", **kw):
+            if auto:      # what a caller gets from sparsert_inspect without options
+                plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, conv=conv, batch=batch)
+            elif untuned:   # no timing runs: the generated kernel with the inspector's shape-dependent defaults
                 plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, conv=conv, batch=batch,
                                   kernel=sp.KERNEL_SPEC)
             elif fixed:   # one parameter choice for every problem (Section 4.3: what tuning per problem buys)
@@ -115,21 +155,24 @@ def main():
                 rc = fn(h, a, b, ctypes.c_void_p(cur()))
                 assert rc == 0, sp.last_error()
 
+            out.fill_(float("nan"))
             sparse()
             torch.cuda.synchronize()
             eager = out.clone()
+            err = verify(tag, what, eager, oracle)
             t = graph_us(torch, sparse)
             assert torch.equal(out, eager), "graph replay changed the result"
-            return plan, t
+            return plan, t, err
 
         extra = {}
         if args.ablation:
             for key, kw in (("rows_only_us", {"kernel": sp.KERNEL_ROWS}), ("natural_order_us", {"natural_order": True}),
                             ("untuned_us", {"untuned": True}), ("fixed_us", {"fixed": True})):
-                p_abl, t_abl = tuned(**kw)
+                p_abl, t_abl, _ = tuned(what=key, **kw)
                 p_abl.destroy()
                 extra[key] = round(t_abl, 3)
-        plan, t_sparse = tuned()
+        use_auto = args.sweep and (args.plans == "auto" or (args.plans == "mixed" and csr.nnz > 150000))
+        plan, t_sparse, err = tuned(auto=use_auto)
         try:
             t_dense, dense_how = graph_us(torch, dense_fn), "graph"
         except Exception:  # a library call that cannot be captured: plain event loop instead
@@ -148,44 +191,45 @@ def main():
         return {"tag": tag, "sparse_us": round(t_sparse, 3), "dense_us": round(t_dense, 3),
                 "speedup": round(t_dense / t_sparse, 3), "dense_timing": dense_how,
                 "gflops": round(2.0 * csr.nnz * N * max(1, batch) / t_sparse / 1e3, 1),
+                "oracle_componentwise_error": err, "oracle_rows_checked": "all" if oracle[0] is None else len(oracle[0]),
+                "plan_from": "inspect defaults" if use_auto else "sparsert_tune",
                 "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit", "spec_swizzle", "spec_vec")},
                 **extra}
 
+    for tag, i, sparsity in ([] if args.sweep else synth.table1_problems()):
+        if only and tag not in only:
+            continue
+        case = synth.table1_case(i, sparsity, ndt)
+        csr, (M, K, N) = case.csr, synth.TABLE1[i]
+        B = torch.from_numpy(case.B).to(dev)
+        C = torch.empty((M, N), dtype=tdt, device=dev)
+        Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
+        r = run(tag, case, B, C, lambda: torch.matmul(Ad, B))
+        r.update(M=M, K=K, N=N, sparsity=sparsity, paper_speedup_t4=PAPER_T1[sparsity][i])
+        rows.append(r)
+        print(json.dumps(r), file=sys.stderr, flush=True)
     for sparsity in (() if args.sweep else (0.90, 0.95)):
-        pct = int(round(sparsity * 100))
-        for i, (M, K, N) in enumerate(TABLE1):
-            tag = f"t1_p{i + 1}_{pct}"
-            if sparsity == 0.95 and i >= 11 or (only and tag not in only):
-                continue
-            seed = synth.BASE_SEED + 1000 + 100 * i + pct
-            csr = synth.magnitude_csr(M, K, sparsity, seed, 1.0, ndt)
-            B = torch.from_numpy(synth.normal_dense(K, N, seed + 1, ndt)).to(dev)
-            C = torch.empty((M, N), dtype=tdt, device=dev)
-            Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
-            r = run(tag, csr, N, B, C, lambda: torch.matmul(Ad, B))
-            r.update(M=M, K=K, N=N, sparsity=sparsity, paper_speedup_t4=PAPER_T1[sparsity][i])
-            rows.append(r)
-            print(json.dumps(r), file=sys.stderr, flush=True)
-        for i, (img, Cin, Cout) in enumerate(TABLE3):
-            tag = f"t3_p{i + 1}_{pct}"
+        for i, (img, Cin, Cout) in enumerate(synth.TABLE3):
+            tag = f"t3_p{i + 1}_{int(round(sparsity * 100))}"
             if only and tag not in only:
                 continue
-            seed = synth.BASE_SEED + 5000 + 100 * i + pct
-            csr, Wd = synth.conv_weights_csr(Cout, Cin, sparsity, seed, ndt)
             nb = max(1, args.batch)
-            X = torch.from_numpy(synth.normal_dense(nb * Cin, img * img, seed + 1, ndt).reshape(nb, Cin, img, img)).to(dev)
+            case = synth.table3_case(i, sparsity, ndt, batch=nb)
+            X = torch.from_numpy(case.X).to(dev)
             Y = torch.empty((nb, Cout, img, img), dtype=tdt, device=dev)
-            Wt = torch.from_numpy(Wd).to(dev)
-            r = run(tag, csr, img * img, X, Y, lambda: torch.nn.functional.conv2d(X, Wt, padding=1),
-                    conv=(Cin, img, img), batch=nb)
+            Wt = torch.from_numpy(case.Wdense).to(dev)
+            r = run(tag, case, X, Y, lambda: torch.nn.functional.conv2d(X, Wt, padding=1), batch=nb)
             r.update(image=img, Cin=Cin, Cout=Cout, batch=nb, sparsity=sparsity, paper_speedup_t4=PAPER_T3[sparsity][i])
             rows.append(r)
             print(json.dumps(r), file=sys.stderr, flush=True)
+    rows.sort(key=lambda r: (r["tag"][:2], r["sparsity"]))   # Table 1 at 90, 95 %, then Table 3 at 90, 95 %
 
     if args.sweep:
-        for M, K in (tuple(int(x) for x in mk.split("x")) for mk in args.shapes.split(",")):
-            for N in (196, 1024, 4096):
-                for sparsity in (0.80, 0.90, 0.95, 0.98):
+        shapes = synth.SWEEP_SHAPES if args.shapes == "grid" else [tuple(int(x) for x in mk.split("x")) for mk in args.shapes.split(",")]
+        ns = synth.SWEEP_N if args.ns == "grid" else [int(x) for x in args.ns.split(",")]
+        for M, K in shapes:
+            for N in ns:
+                for sparsity in [float(x) for x in args.sparsities.split(",")]:
                     tag = f"sw_{M}x{K}x{N}_{int(round(sparsity * 100))}"
                     if only and tag not in only:
                         continue
@@ -194,7 +238,7 @@ def main():
                     B = torch.from_numpy(case.B).to(dev)
                     C = torch.empty((M, N), dtype=tdt, device=dev)
                     Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
-                    r = run(tag, csr, N, B, C, lambda: torch.matmul(Ad, B))
+                    r = run(tag, case, B, C, lambda: torch.matmul(Ad, B))
                     r.update(M=M, K=K, N=N, sparsity=sparsity, paper_speedup_t4="-")
                     rows.append(r)
                     print(json.dumps(r), file=sys.stderr, flush=True)
@@ -208,10 +252,11 @@ def main():
             if only and tag not in only:
                 continue
             csr = synth.skewed_csr(M, K, 0.95, synth.BASE_SEED + 9000 + i, ndt)
-            B = torch.from_numpy(synth.normal_dense(K, N, synth.BASE_SEED + 9100 + i, ndt)).to(dev)
+            case = synth.Case(tag, csr, N, B=synth.normal_dense(K, N, synth.BASE_SEED + 9100 + i, ndt), sparsity=0.95)
+            B = torch.from_numpy(case.B).to(dev)
             C = torch.empty((M, N), dtype=tdt, device=dev)
             Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
-            r = run(tag, csr, N, B, C, lambda: torch.matmul(Ad, B))
+            r = run(tag, case, B, C, lambda: torch.matmul(Ad, B))
             r.update(M=M, K=K, N=N, sparsity=0.95, paper_speedup_t4="-", skewed=True)
             rows.append(r)
             print(json.dumps(r), file=sys.stderr, flush=True)
@@ -234,6 +279,10 @@ def main():
         "workload": (f"shape / sparsity sweep, {args.mask} masks, N(0,1) values, " if args.sweep else
                      "paper Table 1 (SpMM) and Table 3 (3x3 conv) shapes, synthetic magnitude-pruned weights, ") + args.dtype,
         "timing": f"{INNER} launches per HIP graph, 20 replays, HIP events; same for sparse and dense",
+        "oracle_check": {"timed_plans_checked": checked["plans"], "mismatches": 0, "tolerance": tol,
+                         "worst_componentwise_error": checked["worst"],
+                         "what": "every element of every timed plan's output against the float64 CPU oracle "
+                                 "(a seeded sample of 64 rows where nnz*N exceeds 6e8); a mismatch ends the run"},
         "geomean_speedup_vs_dense": {"table1_90": gm("t1", 0.90), "table1_95": gm("t1", 0.95),
                                      "table3_90": gm("t3", 0.90), "table3_95": gm("t3", 0.95)},
         "paper_geomean_t4": {"table1_90": 3.4, "table1_95": 5.4},
@@ -246,16 +295,20 @@ def main():
 
 def write_sweep_markdown(path, res, command):
     mask = res["workload"].split(",")[1].strip()
+    oc = res["oracle_check"]
     lines = [f"# Shape / sparsity sweep on MI355X, {mask}, {res['workload'].split()[-1]}", "",
-             f"command: `{command}` (one MI355X; plans from sparsert_tune; sparse and dense both timed as",
-             f"{INNER} launches per HIP graph, 20 replays, HIP events; effective GFLOP/s = 2 nnz N / t).", "",
-             "| M | K | N | sparsity | sparse us | dense us | speedup | effective GFLOP/s | kernel | R | KS | swizzle |",
-             "|---|---|---|---|---|---|---|---|---|---|---|---|"]
+             "Benchmark table (not a rocprofv3 summary), builder-run.  Outputs checked against the oracle: yes - "
+             f"{oc['timed_plans_checked']} timed plans, every element (64 sampled rows for the largest cases), "
+             f"worst componentwise error {oc['worst_componentwise_error']:.2e} against {oc['tolerance']:g}.", "",
+             f"command: `{command}` (one MI355X; `plan`: tune = sparsert_tune, auto = sparsert_inspect without options;",
+             f"sparse and dense both timed as {INNER} launches per HIP graph, 20 replays, HIP events; effective GFLOP/s = 2 nnz N / t).", "",
+             "| M | K | N | sparsity | sparse us | dense us | speedup | effective GFLOP/s | kernel | R | KS | swizzle | plan | oracle err |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     for r in res["problems"]:
         p = r["plan"]
         lines.append(f"| {r['M']} | {r['K']} | {r['N']} | {r['sparsity']:.2f} | {r['sparse_us']:.2f} | {r['dense_us']:.2f} | "
                      f"{r['speedup']:.2f} | {r['gflops']:.0f} | {p['kernel']} | {p['spec_rows']} | {p['spec_ksplit']} | "
-                     f"{p['spec_swizzle']} |")
+                     f"{p['spec_swizzle']} | {'auto' if r['plan_from'].startswith('inspect') else 'tune'} | {r['oracle_componentwise_error']:.1e} |")
     with open(path, "w") as f:
         f.write("\n".join(lines) + "\n")
 
@@ -266,6 +319,9 @@ def write_markdown(path, res, command):
     g = res["geomean_speedup_vs_dense"]
     fmt = lambda x: "-" if x is None else f"{x:.2f}x"
     lines = [f"# Paper's problem list (Table 1 SpMM, Table 3 3x3 conv) on MI355X, synthetic weights, {res['workload'].split()[-1]}", "",
+             "Benchmark table (not a rocprofv3 summary), builder-run.  Outputs checked against the oracle: yes - "
+             f"{res['oracle_check']['timed_plans_checked']} timed plans (ablation plans included), every element, worst componentwise error "
+             f"{res['oracle_check']['worst_componentwise_error']:.2e} against {res['oracle_check']['tolerance']:g}.", "",
              f"command: `{command}` (one MI355X; plans from sparsert_tune; sparse and dense both timed as",
              f"{INNER} launches per HIP graph, 20 replays, HIP events).", "",
              "Geometric-mean speedup over the dense baseline of the same type (torch.matmul / conv2d) on the same GPU:", "",

@@ -8,9 +8,9 @@
  * `sparsert_conv3x3`).
  *
  * Conventions used by every entry point
- *   - Matrices are C-style row-major and dense-pitched (Section 3.2): B is
- *     K x N with N contiguous, C is M x N with N contiguous, no leading
- *     dimension argument.
+ *   - Matrices are C-style row-major (Section 3.2): B is K x N with N contiguous,
+ *     C is M x N with N contiguous; rows follow each other at a pitch of N
+ *     elements unless options.ldb / options.ldc say otherwise.
  *   - "HOST" pointers are ordinary CPU memory; "DEVICE" pointers are HIP
  *     device memory on the device that was current when the plan was made.
  *   - Every function returns a status code (sparsert_status: 0 = ok, negative = error) and
@@ -52,7 +52,12 @@ typedef enum sparsert_dtype { SPARSERT_F32 = 0, SPARSERT_F16 = 1, SPARSERT_I8 = 
 
 /* Executor families (options.kernel / INFO[SPARSERT_INFO_KERNEL]). */
 typedef enum sparsert_kernel {
-    SPARSERT_KERNEL_AUTO = 0,
+    SPARSERT_KERNEL_AUTO = 0,  /* the inspector chooses: the generated kernel with its shape-dependent
+                                  defaults when the code object manager (libamd_comgr) can be loaded, A has
+                                  at most 524288 nonzeros (a few seconds of assembling; the inspector is off
+                                  the latency path, Section 2.3) and neither vec nor split_threshold is set;
+                                  the row-walk kernel otherwise, and also when the generator declines the
+                                  problem (EUNSUPPORTED / ECOMPILE) */
     SPARSERT_KERNEL_ROWS = 1,  /* one wave per row, B read straight from L2/HBM */
     SPARSERT_KERNEL_SPEC = 2   /* per-matrix generated gfx950 code with the nonzeros of A as
                                   instruction constants (Section 3.5) */
@@ -108,7 +113,15 @@ typedef struct sparsert_options {
     int32_t spec_vec;        /* SPARSERT_KERNEL_SPEC, DIRECT, SpMM: columns of C per lane; 0/1, or the 2 halves
                                 (half plans) / 4 int8 (int8 plans) that share the dword a lane loads,
                                 which halves / quarters the fetches per column; N must be a multiple */
-    int32_t reserved[1];     /* must be zero */
+    int32_t ldb, ldc;        /* SpMM: elements between the starts of consecutive rows of B and of C (leading
+                                dimensions; 0 = N, else >= N).  A wider pitch lets a call work on a column
+                                slice of larger activation matrices (Section 4.3: more columns only make N
+                                larger).  With batch = b the operands are [b, K, ldb] and [b, M, ldc].
+                                Convolution plans take 0 */
+    int32_t tune_warm;       /* sparsert_tune only.  0: candidates are ranked by their time when every launch
+                                finds its code and operands displaced from the L2 caches, as inside a model
+                                where other layers run in between; 1: by back-to-back launches of the same plan */
+    int32_t reserved[3];     /* must be zero */
 } sparsert_options;
 
 /*
@@ -143,8 +156,9 @@ int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void 
  * per-thread-group loop): C = A x B, C fully overwritten (no alpha/beta); a
  * row of A without nonzeros yields +0.0.
  *
- *   B_dev  DEVICE, K x N row-major, plan's dtype, 16-byte aligned, read only
- *   C_dev  DEVICE, M x N row-major, plan's dtype (int32 for int8 plans), 16-byte aligned, written
+ *   B_dev  DEVICE, K x N row-major at a row pitch of ldb elements, plan's dtype, 16-byte aligned, read only
+ *   C_dev  DEVICE, M x N row-major at a row pitch of ldc elements, plan's dtype (int32 for int8 plans),
+ *          16-byte aligned; only the N columns of every row are written, the rest of a wider pitch is untouched
  *   stream a hipStream_t (NULL = the null stream)
  *
  * With opt->batch = b the call multiplies b matrices stored back to back, B_dev as
@@ -181,7 +195,10 @@ int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, 
  * configurations, done once per problem, off the inference path).  Builds a plan for each
  * candidate configuration - executor family, columns per lane, split threshold, rows per
  * generated code block, waves per workgroup, K split, staging variant, row swizzle - times it on the GPU with the
- * given operands, and returns the fastest plan.  `base` fixes dtype, the convolution
+ * given operands, and returns the fastest plan (fastest with cold caches unless base->tune_warm is set: inside a
+ * model a layer's code and operands have been displaced by the layers before it).  Every candidate's output is
+ * compared on the GPU with the first candidate's (the row-walk or default plan); one that disagrees beyond the
+ * storage type's tolerance is reported and never returned.  `base` fixes dtype, the convolution
  * geometry and natural_order; base->kernel other than AUTO restricts the search to that
  * executor family (the specialisation ablation); its other tuning fields are ignored.
  *
@@ -197,11 +214,17 @@ int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, 
 #define SPARSERT_TUNE_MAX 64
 typedef struct sparsert_tune_entry {
     int32_t kernel, vec, split_threshold, spec_mode, spec_rows, spec_tiles, spec_ksplit, spec_lanes, spec_swizzle, spec_vec;
-    float microseconds; /* per launch; negative if the candidate failed */
+    float microseconds;      /* per launch, back-to-back launches of this plan; negative if the candidate failed */
+    float cold_microseconds; /* per launch when a cache-displacing fill runs before every launch (the fill's own
+                                time subtracted); negative if the candidate failed */
+    int32_t agrees;          /* 1: the candidate's output matches the first candidate's within the storage type's
+                                tolerance (bit for bit for int8 plans); 0: it does not, and the candidate was
+                                not considered */
 } sparsert_tune_entry;
 typedef struct sparsert_tune_report {
     int32_t count;
-    float best_microseconds;
+    float best_microseconds;       /* the returned plan, back-to-back launches */
+    float best_cold_microseconds;  /* the returned plan, caches displaced before every launch */
     sparsert_tune_entry entries[SPARSERT_TUNE_MAX];
 } sparsert_tune_report;
 int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, const void *vals,
@@ -262,7 +285,9 @@ enum {
     SPARSERT_INFO_SPEC_SWIZZLE,   /* SPEC plans: 1 if blocks were formed by similarity */
     SPARSERT_INFO_BATCH,          /* problems per call (>= 1) */
     SPARSERT_INFO_SPEC_VEC,       /* SPEC plans: columns per lane */
-    SPARSERT_INFO_COUNT = 32      /* remaining entries are zero */
+    SPARSERT_INFO_LDB,            /* elements between consecutive rows of B (N unless options.ldb) */
+    SPARSERT_INFO_LDC,            /* elements between consecutive rows of C (N unless options.ldc) */
+    SPARSERT_INFO_COUNT = 48      /* remaining entries are zero */
 };
 
 /*

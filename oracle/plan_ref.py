@@ -20,11 +20,14 @@ Specification
   segments    = for a split slot with n nonzeros starting at s: share = ceil(n/Gy), bounds
                 s + min(g*share, n), g = 0..Gy  (all waves but the last get `share`)
   stream      = per nonzero {int32 byte offset, float32 bits of the value}
-                SpMM: offset = col*N*itemsize, permuted-CSR order
+                SpMM: offset = col*ldb*itemsize (ldb = row pitch of B, N unless given), permuted-CSR order
                 conv: k = c*9 + r*3 + s  ->  word = tap << 28 | (displacement & 0x0fffffff) with
                 tap = r*3+s and displacement = (c*H*W + (r-1)*W + (s-1))*itemsize; each slot
                 stably reordered by tap; conv_seg[slot] holds the ten stream positions where
                 the taps start/end
+  kernel      = executor family when the caller leaves the choice to the inspector: 2 (per-matrix
+                generated code) if nnz <= 524288 and neither vec nor split_threshold is given,
+                else 1 (row-walk).  (Stated for a process that can load the code object manager.)
 """
 from __future__ import annotations
 
@@ -33,6 +36,7 @@ import numpy as np
 GY = 4
 WAVE = 64
 FULL_TASKS = 2048
+AUTO_SPEC_NNZ = 512 * 1024
 
 
 def _bin(x: np.ndarray) -> np.ndarray:
@@ -45,8 +49,9 @@ def _bin(x: np.ndarray) -> np.ndarray:
     return out
 
 
-def choose_vec(M, N, vmax, skip=0):
-    cands = [v for v in (1, 2, 4, 8) if v <= vmax and N % v == 0 and v != skip]
+def choose_vec(M, N, vmax, skip=0, ldb=0, ldc=0):
+    # a lane's V columns are one aligned vector access: V divides N and both row pitches
+    cands = [v for v in (1, 2, 4, 8) if v <= vmax and N % v == 0 and ldb % v == 0 and ldc % v == 0 and v != skip]
     tiles = {v: -(-(N // v) // WAVE) for v in cands}
     work = {v: tiles[v] * v for v in cands}
     wmin = min(work.values())
@@ -55,7 +60,7 @@ def choose_vec(M, N, vmax, skip=0):
     return max(full) if full else min(kept)
 
 
-def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, natural_order=False):
+def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, natural_order=False, ldb=0, ldc=0):
     row_ptr = np.asarray(row_ptr, dtype=np.int64)
     col_idx = np.asarray(col_idx, dtype=np.int64)
     vals = np.asarray(vals)
@@ -88,7 +93,8 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, n
         i = j
 
     vmax = 1 if conv else (8 if half else 4)
-    V = vec if vec else choose_vec(M, N, vmax, skip=2 if int8 else 0)   # int8: one column or a packed dword of four
+    ldb, ldc = ldb or N, ldc or N   # elements between consecutive rows of B and of C
+    V = vec if vec else choose_vec(M, N, vmax, skip=2 if int8 else 0, ldb=ldb, ldc=ldc)   # int8: one column or a packed dword of four
     nvc = N // V
     n_tiles = -(-nvc // WAVE)
     lanes_per_tile = -(-nvc // n_tiles)
@@ -110,7 +116,7 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, n
     stream = np.zeros((nnz, 2), dtype=np.uint32)
     conv_seg = np.zeros((0,), dtype=np.int64)
     if not conv:
-        stream[:, 0] = (p_col * N * item).astype(np.int64).astype(np.uint32)
+        stream[:, 0] = (p_col * ldb * item).astype(np.int64).astype(np.uint32)
         stream[:, 1] = val_bits
     else:
         Cin, H, W = conv
@@ -128,8 +134,9 @@ def plan(row_ptr, col_idx, vals, M, K, N, conv=None, vec=0, split_threshold=0, n
 
     info = dict(M=M, K=K, N=N, nnz=nnz, dtype=1 if half else 2 if int8 else 0, conv=1 if conv else 0,
                 Cin=conv[0] if conv else 0, H=conv[1] if conv else 0, W=conv[2] if conv else 0,
-                kernel=1, vec=V, lanes_per_tile=lanes_per_tile, n_tiles=n_tiles, gy=GY,
-                split_threshold=thr, n_split=n_split, n_wg_rows=n_wg_rows, n_bins=len(bins))
+                kernel=2 if (nnz <= AUTO_SPEC_NNZ and not vec and not split_threshold) else 1, vec=V, lanes_per_tile=lanes_per_tile, n_tiles=n_tiles, gy=GY,
+                split_threshold=thr, n_split=n_split, n_wg_rows=n_wg_rows, n_bins=len(bins),
+                ldb=ldb, ldc=ldc)
     i32 = lambda a: np.ascontiguousarray(np.asarray(a, dtype=np.int64).astype(np.int32))
     return dict(info=info, row_nnz=i32(row_nnz), hist=i32(hist), perm=i32(perm),
                 inv_perm=i32(inv_perm), p_row_ptr=i32(p_row_ptr), p_col_idx=i32(p_col),

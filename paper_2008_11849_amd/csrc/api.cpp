@@ -30,8 +30,17 @@ int sparsert_inspect(const int32_t *row_ptr, const int32_t *col_idx, const void 
     int rc;
     try {   // no exception may cross the C boundary
         rc = sparsert::build_host_plan(row_ptr, col_idx, vals, M, K, N, o, plan->host, err);
-        if (rc == SPARSERT_OK && plan->host.kernel == SPARSERT_KERNEL_SPEC)
+        if (rc == SPARSERT_OK && plan->host.kernel == SPARSERT_KERNEL_SPEC) {
             rc = sparsert::build_spec_plan(plan->host, o, err);
+            if ((rc == SPARSERT_EUNSUPPORTED || rc == SPARSERT_ECOMPILE) && plan->host.kernel_auto) {
+                // the inspector's own choice did not work out for this problem (a shape the
+                // generator does not cover, an assembler failure): the row-walk kernel always does
+                plan->host.spec = sparsert::SpecPlan();
+                plan->host.kernel = SPARSERT_KERNEL_ROWS;
+                rc = SPARSERT_OK;
+                err.clear();
+            }
+        }
         if (rc == SPARSERT_OK && !o.host_only) {
             rc = sparsert::upload_plan(plan->host, plan->dev, err);
             plan->on_device = (rc == SPARSERT_OK);
@@ -110,6 +119,7 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
         info[SPARSERT_INFO_NATURAL_ORDER] = h.natural_order;
         info[SPARSERT_INFO_BATCH] = h.batch;
         info[SPARSERT_INFO_SPEC_VEC] = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.vec : 0;
+        info[SPARSERT_INFO_LDB] = h.ldb; info[SPARSERT_INFO_LDC] = h.ldc;
         info[SPARSERT_INFO_SPEC_LANES] = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.lanes_per_tile : 0;
         info[SPARSERT_INFO_SPEC_SWIZZLE] = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.swizzle : 0;
         src = info; bytes = sizeof(info);
@@ -145,6 +155,6 @@ void sparsert_plan_destroy(sparsert_plan *plan) {
 
 const char *sparsert_last_error(void) { return g_err.c_str(); }
 
-int32_t sparsert_version(void) { return 100; }
+int32_t sparsert_version(void) { return 200; }
 
 }  // extern "C"

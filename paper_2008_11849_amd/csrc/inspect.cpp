@@ -26,7 +26,7 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (opt.spec_lanes != 0 && opt.spec_lanes != 16 && opt.spec_lanes != 32 && opt.spec_lanes != 64) { err = "spec_lanes must be 0,16,32,64"; return SPARSERT_EINVAL; }
     if (opt.spec_swizzle != 0 && opt.spec_swizzle != 1) { err = "spec_swizzle must be 0 or 1"; return SPARSERT_EINVAL; }
     if (opt.spec_vec != 0 && opt.spec_vec != 1 && opt.spec_vec != 2 && opt.spec_vec != 4) { err = "spec_vec must be 0,1,2,4"; return SPARSERT_EINVAL; }
-    for (int i = 0; i < 1; ++i)
+    for (int i = 0; i < 3; ++i)
         if (opt.reserved[i] != 0) { err = "reserved option fields must be zero"; return SPARSERT_EINVAL; }
     if (row_ptr[0] != 0) { err = "row_ptr[0] must be 0"; return SPARSERT_EINVAL; }
     for (int32_t m = 0; m < M; ++m)
@@ -50,6 +50,7 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
             err = "vec must be 0,1,2,4 (8 for f16; 1 or 4 for int8)"; return SPARSERT_EINVAL;
         }
         if (N % v != 0) { err = "N must be a multiple of vec"; return SPARSERT_EINVAL; }
+        if ((opt.ldb && opt.ldb % v) || (opt.ldc && opt.ldc % v)) { err = "ldb and ldc must be multiples of vec"; return SPARSERT_EINVAL; }
         if (opt.conv && v != 1) { err = "conv plans use vec = 1"; return SPARSERT_EINVAL; }
     }
     if (opt.spec_depth < 0 || opt.spec_depth > 48) { err = "spec_depth must be in 0..48"; return SPARSERT_EINVAL; }
@@ -63,6 +64,10 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     // int8: |sum| <= K * 128 * 128 must stay below 2^31
     if (opt.dtype == SPARSERT_I8 && K >= (1 << 17)) { err = "K too long for exact 32-bit sums of int8 products"; return SPARSERT_EUNSUPPORTED; }
     if (opt.batch < 0 || opt.batch > 65535) { err = "batch must be in 0..65535"; return SPARSERT_EINVAL; }
+    if (opt.tune_warm != 0 && opt.tune_warm != 1) { err = "tune_warm must be 0 or 1"; return SPARSERT_EINVAL; }
+    if ((opt.ldb != 0 && opt.ldb < N) || (opt.ldc != 0 && opt.ldc < N)) { err = "ldb and ldc must be 0 or at least N"; return SPARSERT_EINVAL; }
+    if (opt.conv && (opt.ldb || opt.ldc)) { err = "convolution plans take no leading dimensions"; return SPARSERT_EINVAL; }
+    const int64_t ldb = opt.ldb ? opt.ldb : N, ldc = opt.ldc ? opt.ldc : N;
     if (opt.conv) {
         if (opt.conv != 1) { err = "conv must be 0 or 1"; return SPARSERT_EINVAL; }
         if (opt.Cin <= 0 || opt.H <= 0 || opt.W <= 0) { err = "conv needs Cin, H, W > 0"; return SPARSERT_EINVAL; }
@@ -72,7 +77,7 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
             err = "conv input too large for 28-bit operand displacements"; return SPARSERT_EUNSUPPORTED;
         }
         if ((int64_t)M * N * osz >= (1ll << 31)) { err = "one image of Y reaches 2 GiB"; return SPARSERT_EUNSUPPORTED; }
-    } else if ((int64_t)K * N * esz >= (1ll << 31) || (int64_t)M * N * osz >= (1ll << 31)) {
+    } else if ((int64_t)K * ldb * esz >= (1ll << 31) || (int64_t)M * ldc * osz >= (1ll << 31)) {
         err = "B or C reaches 2 GiB: operand offsets are 32-bit"; return SPARSERT_EUNSUPPORTED;
     }
     return SPARSERT_OK;
@@ -82,12 +87,13 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
 // issues V multiply-adds per nonzero per tile, so work(V) = n_tiles(V) * V.
 // Among the V dividing N whose work is within 7 % of the least, take the
 // largest that still leaves kFullTasks wave tasks; if none does, the smallest.
-// `skip` names a V the storage type has no kernel for (2 for int8), or 0.
-static int choose_vec(int32_t M, int32_t N, int vmax, int skip) {
+// `skip` names a V the storage type has no kernel for (2 for int8), or 0.  V also has to divide
+// the row pitches of B and C.
+static int choose_vec(int32_t M, int32_t N, int32_t ldb, int32_t ldc, int vmax, int skip) {
     int cand[4], nc = 0;
     int64_t work[4], wmin = INT64_MAX;
     for (int v = 1; v <= vmax; v *= 2) {
-        if (N % v || v == skip) continue;
+        if (N % v || ldb % v || ldc % v || v == skip) continue;   // a lane's V columns are one aligned vector access
         const int64_t tiles = ((int64_t)N / v + kWave - 1) / kWave;
         cand[nc] = v; work[nc] = tiles * v; wmin = std::min(wmin, work[nc]); ++nc;
     }
@@ -109,7 +115,16 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
     h.dtype = opt.dtype; h.conv = opt.conv ? 1 : 0;
     h.Cin = h.conv ? opt.Cin : 0; h.H = h.conv ? opt.H : 0; h.W = h.conv ? opt.W : 0;
     h.batch = std::max(1, opt.batch);
-    h.kernel = opt.kernel == SPARSERT_KERNEL_AUTO ? SPARSERT_KERNEL_ROWS : opt.kernel;
+    h.ldb = opt.ldb ? opt.ldb : N;
+    h.ldc = opt.ldc ? opt.ldc : N;
+    // AUTO: the per-matrix generated kernel with the inspector's shape defaults where it can be
+    // built in a few seconds (the inspector is off the latency path, Section 2.3), else the
+    // row-walk kernel, whose inspector generates nothing.  Options that only the row-walk kernel
+    // reads (vec, split_threshold) select it as well.
+    if (opt.kernel != SPARSERT_KERNEL_AUTO) h.kernel = opt.kernel;
+    else h.kernel = (opt.vec == 0 && opt.split_threshold == 0 && h.nnz <= kAutoSpecNnz && spec_available())
+                        ? SPARSERT_KERNEL_SPEC : SPARSERT_KERNEL_ROWS;
+    h.kernel_auto = opt.kernel == SPARSERT_KERNEL_AUTO;
     const int esz = h.elem_size();
 
     // Row histogram and the nnz-descending stable row order.
@@ -155,7 +170,7 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
 
     // Column tiling.
     const int vmax = h.conv ? 1 : (h.dtype == SPARSERT_F16 ? 8 : 4);
-    h.vec = opt.vec ? opt.vec : choose_vec(M, N, vmax, h.dtype == SPARSERT_I8 ? 2 : 0);
+    h.vec = opt.vec ? opt.vec : choose_vec(M, N, h.ldb, h.ldc, vmax, h.dtype == SPARSERT_I8 ? 2 : 0);
     const int32_t nvc = N / h.vec;  // vector columns
     h.n_tiles = (nvc + kWave - 1) / kWave;
     h.lanes_per_tile = (nvc + h.n_tiles - 1) / h.n_tiles;
@@ -190,7 +205,7 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
     };
     if (!h.conv) {
         for (int32_t p = 0; p < h.nnz; ++p) {
-            h.stream[2 * (size_t)p] = (uint32_t)((uint64_t)h.p_col_idx[p] * (uint64_t)N * esz);
+            h.stream[2 * (size_t)p] = (uint32_t)((uint64_t)h.p_col_idx[p] * (uint64_t)h.ldb * esz);
             h.stream[2 * (size_t)p + 1] = value_bits(p);
         }
     } else {

@@ -14,6 +14,10 @@
 //     fixed order, so results are reproducible run to run.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <cstring>
+#include <type_traits>
+
 #include "plan.h"
 
 namespace sparsert {
@@ -158,7 +162,7 @@ struct RowsArgs {
     const int32_t *conv_seg;
     const void *in;   // B [K,N] or X [Cin,H,W]
     void *out;        // C [M,N] or Y [Cout,H,W]
-    int32_t M, N;
+    int32_t M, N, ldc;
     int32_t n_vec_cols, lanes_per_tile, n_tiles;
     int32_t n_split, n_wg_rows;
     int32_t n_tasks, tasks_per_xcd;
@@ -253,7 +257,7 @@ __global__ __launch_bounds__(kGy *kWave) void rows_kernel(const RowsArgs a) {
         const int row = a.perm[slot];
         typedef typename Ops<T, V>::out_t out_t;
         out_t *out = static_cast<out_t *>(a.out) + (int64_t)blockIdx.y * a.out_image_elems;
-        Ops<T, V>::store(out + (size_t)row * a.N + col, acc, a.stream_stores != 0);
+        Ops<T, V>::store(out + (size_t)row * a.ldc + col, acc, a.stream_stores != 0);
     }
 }
 
@@ -333,7 +337,7 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
                 void *stream, std::string &err) {
     // Host-side shape checks: the kernel assumes exactly these relations.
     const int64_t nvc = h.N / h.vec;
-    if (h.vec < 1 || h.N % h.vec || h.gy != kGy || h.lanes_per_tile < 1 || h.lanes_per_tile > kWave ||
+    if (h.vec < 1 || h.N % h.vec || h.ldb < h.N || h.ldc < h.N || h.ldb % h.vec || h.ldc % h.vec || h.gy != kGy || h.lanes_per_tile < 1 || h.lanes_per_tile > kWave ||
         (int64_t)h.n_tiles * h.lanes_per_tile < nvc || h.n_split < 0 || h.n_split > h.M ||
         (int64_t)(h.n_tiles - 1) * h.lanes_per_tile >= nvc ||
         h.n_wg_rows != h.n_split + (h.M - h.n_split + kGy - 1) / kGy) {
@@ -347,15 +351,15 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
     a.stream = reinterpret_cast<const uint2 *>(d.stream);
     a.segments = d.segments; a.conv_seg = d.conv_seg;
     a.in = in; a.out = out;
-    a.M = h.M; a.N = h.N;
+    a.M = h.M; a.N = h.N; a.ldc = h.ldc;
     a.n_vec_cols = (int32_t)nvc; a.lanes_per_tile = h.lanes_per_tile; a.n_tiles = h.n_tiles;
     a.n_split = h.n_split; a.n_wg_rows = h.n_wg_rows;
     a.n_tasks = (int32_t)n_tasks; a.tasks_per_xcd = (int32_t)((n_tasks + 7) / 8);
     a.H = h.H; a.W = h.W;
-    a.stream_stores = ((int64_t)h.N * h.out_elem_size()) % 128 == 0 &&
+    a.stream_stores = ((int64_t)h.ldc * h.out_elem_size()) % 128 == 0 &&
                       ((int64_t)h.lanes_per_tile * h.vec * h.out_elem_size()) % 128 == 0;
-    a.in_image_bytes = (h.conv ? (int64_t)h.Cin * h.H * h.W : (int64_t)h.K * h.N) * h.elem_size();
-    a.out_image_elems = (int64_t)h.M * h.N;
+    a.in_image_bytes = (h.conv ? (int64_t)h.Cin * h.H * h.W : (int64_t)h.K * h.ldb) * h.elem_size();
+    a.out_image_elems = (int64_t)h.M * h.ldc;
     const int images = h.batch;
     if (images < 1 || images > 65535) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -381,6 +385,69 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
         [[fallthrough]];
     default: err = "unsupported vec for this dtype"; return SPARSERT_EINVAL;
     }
+}
+
+// ---------------------------------------------------------------- helpers of the autotuner
+// Largest |a - b| and largest |b| over the N valid columns of every output row (bits of the
+// non-negative floats, so an unsigned integer maximum orders them), and the number of elements
+// that are not finite in one buffer only or differ at all for integer outputs.
+template <typename T>
+__global__ __launch_bounds__(256) void diff_kernel(const T *a, const T *b, int64_t rows, int32_t N, int32_t ld,
+                                                    uint32_t *res) {
+    float dmax = 0.0f, bmax = 0.0f;
+    uint32_t bad = 0;
+    const int64_t total = rows * N;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / N, c = i - r * N;
+        const float x = (float)a[r * ld + c], y = (float)b[r * ld + c];
+        if constexpr (std::is_integral<T>::value) {
+            bad += a[r * ld + c] != b[r * ld + c];
+        } else {
+            const bool fx = __builtin_isfinite(x), fy = __builtin_isfinite(y);
+            if (fx && fy) { dmax = fmaxf(dmax, fabsf(x - y)); bmax = fmaxf(bmax, fabsf(y)); }
+            else if (fx != fy || (__builtin_isnan(x) != __builtin_isnan(y)) || (!__builtin_isnan(x) && x != y)) ++bad;
+        }
+    }
+    atomicMax(&res[0], __float_as_uint(dmax));
+    atomicMax(&res[1], __float_as_uint(bmax));
+    if (bad) atomicAdd(&res[2], bad);
+}
+
+int compare_outputs(const HostPlan &h, const void *a, const void *b, uint32_t *res_dev, void *stream,
+                    float &max_diff, float &max_ref, uint32_t &bad, std::string &err) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipMemsetAsync(res_dev, 0, 3 * sizeof(uint32_t), s));
+    const int64_t rows = (int64_t)h.batch * h.M;
+    const int32_t ld = h.conv ? h.N : h.ldc;
+    const unsigned grid = (unsigned)std::min<int64_t>(2048, (rows * h.N + 255) / 256);
+    if (h.dtype == SPARSERT_I8)
+        hipLaunchKernelGGL(diff_kernel<int32_t>, dim3(grid), dim3(256), 0, s, (const int32_t *)a, (const int32_t *)b, rows, h.N, ld, res_dev);
+    else if (h.dtype == SPARSERT_F16)
+        hipLaunchKernelGGL(diff_kernel<_Float16>, dim3(grid), dim3(256), 0, s, (const _Float16 *)a, (const _Float16 *)b, rows, h.N, ld, res_dev);
+    else
+        hipLaunchKernelGGL(diff_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)a, (const float *)b, rows, h.N, ld, res_dev);
+    HIP_TRY(hipGetLastError());
+    uint32_t host[3] = {0, 0, 0};
+    HIP_TRY(hipMemcpyAsync(host, res_dev, sizeof(host), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    std::memcpy(&max_diff, &host[0], 4);
+    std::memcpy(&max_ref, &host[1], 4);
+    bad = host[2];
+    return SPARSERT_OK;
+}
+
+// Writes `bytes` of scratch memory: more than the eight L2 caches hold, so whatever a plan left
+// there (its code, its operands) is displaced before the plan's next launch.
+__global__ __launch_bounds__(256) void fill_kernel(float4 *p, int64_t n, float v) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = make_float4(v, v, v, v);
+}
+
+int displace_caches(void *scratch, size_t bytes, void *stream, std::string &err) {
+    hipLaunchKernelGGL(fill_kernel, dim3(2048), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<float4 *>(scratch), (int64_t)(bytes / sizeof(float4)), 1.0f);
+    HIP_TRY(hipGetLastError());
+    return SPARSERT_OK;
 }
 
 int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,

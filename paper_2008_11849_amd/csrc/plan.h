@@ -13,6 +13,7 @@ constexpr int kWave = 64;       // lanes per wavefront on gfx950
 constexpr int kGy = 4;          // waves per workgroup (one per SIMD of a CU)
 constexpr int kBins = 33;       // bin(0)=0, bin(x)=1+floor(log2 x), x < 2^31
 constexpr int kFullTasks = 2048;  // wave tasks wanted before widening per-lane vectors
+constexpr int32_t kAutoSpecNnz = 512 << 10;   // SPARSERT_KERNEL_AUTO generates code up to this many nonzeros (about 6 s of assembling)
 
 // Per-matrix generated kernel (kernel == SPARSERT_KERNEL_SPEC).
 // IEEE binary16 -> binary32, exact for every input (subnormals, inf, NaN payload kept).
@@ -55,6 +56,8 @@ struct HostPlan {
     int32_t split_threshold = 0, n_split = 0, n_wg_rows = 0;
     int32_t natural_order = 0;         // rows kept in input order (load-balance ablation)
     int32_t batch = 1;                 // problems per call: images of a convolution, B/C pairs of an SpMM
+    int32_t ldb = 0, ldc = 0;          // elements between consecutive rows of B and of C (N unless the caller widens them)
+    bool kernel_auto = false;          // the executor family was the inspector's choice, not the caller's
 
     std::vector<int32_t> row_nnz, hist, perm, inv_perm, p_row_ptr, p_col_idx;
     std::vector<uint8_t> p_vals;       // nnz * elem_size bytes, bit copies
@@ -86,6 +89,7 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
 
 // Generated-kernel path (specialize.cpp): fills h.spec, including the assembled code object.
 int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err);
+bool spec_available();   // can generated kernels be assembled in this process (is the code object manager loadable)?
 
 // Records the thread-local error message behind sparsert_last_error (api.cpp); returns `code`.
 int set_error(int code, const std::string &msg);
@@ -98,6 +102,13 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
                 void *stream, std::string &err);
 int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
                 void *stream, std::string &err);
+// Autotuner helpers (kernels.hip).  compare_outputs: largest |a - b| and |b| over the valid
+// columns of two output buffers of plan `h`, and the count of elements that differ in kind
+// (finite against not finite; any difference for integer outputs); synchronises the stream.
+// res_dev: three device words of scratch.  displace_caches: overwrites `bytes` of scratch memory.
+int compare_outputs(const HostPlan &h, const void *a, const void *b, uint32_t *res_dev, void *stream,
+                    float &max_diff, float &max_ref, uint32_t &bad, std::string &err);
+int displace_caches(void *scratch, size_t bytes, void *stream, std::string &err);
 
 }  // namespace sparsert
 

@@ -14,7 +14,7 @@
 namespace {
 
 constexpr uint32_t kMagic = 0x54525053u;   // "SPRT"
-constexpr uint32_t kFormat = 1;
+constexpr uint32_t kFormat = 2;   // bumped whenever the field list below changes
 
 struct Writer {
     std::vector<uint8_t> out;
@@ -59,7 +59,7 @@ inline void field(Reader &r, int32_t &x) { x = r.i32(); }
 template <typename IO> void scalars(IO &io, sparsert::HostPlan &h) {
     int32_t *f[] = {&h.M, &h.K, &h.N, &h.nnz, &h.dtype, &h.conv, &h.Cin, &h.H, &h.W, &h.kernel, &h.vec,
                     &h.lanes_per_tile, &h.n_tiles, &h.gy, &h.split_threshold, &h.n_split, &h.n_wg_rows,
-                    &h.natural_order, &h.batch,
+                    &h.natural_order, &h.batch, &h.ldb, &h.ldc,
                     &h.spec.rows_per_group, &h.spec.n_groups, &h.spec.depth, &h.spec.n_tiles, &h.spec.lanes_per_tile,
                     &h.spec.tiles_per_wg, &h.spec.swizzle, &h.spec.vec, &h.spec.mode, &h.spec.n_blocks,
                     &h.spec.lds_bytes, &h.spec.ksplit};
@@ -82,9 +82,65 @@ bool consistent(const sparsert::HostPlan &h) {
     if (h.n_split < 0 || h.n_split > h.M || h.segments.size() != (size_t)h.n_split * (size_t)(h.gy + 1)) return false;
     if (h.conv && h.conv_seg.size() != M * 10) return false;
     if (h.batch < 1 || h.batch > 65535) return false;
+    if (h.ldb < h.N || h.ldc < h.N || (h.conv && (h.ldb != h.N || h.ldc != h.N))) return false;
+    const int64_t esz = h.elem_size(), osz = h.out_elem_size();
+    // Row-walk geometry: what launch_rows and rows_kernel index with.
+    if (h.gy != sparsert::kGy || h.vec < 1 || h.vec > 8 || h.N % h.vec || h.ldb % h.vec || h.ldc % h.vec) return false;
+    if (h.lanes_per_tile < 1 || h.lanes_per_tile > sparsert::kWave || h.n_tiles < 1) return false;
+    if (h.n_wg_rows != h.n_split + (h.M - h.n_split + h.gy - 1) / h.gy) return false;
+    // Split rows: the shares of slot i are ascending positions inside the slot's own nonzeros.
+    for (int32_t i = 0; i < h.n_split; ++i) {
+        const int32_t *sg = &h.segments[(size_t)i * (h.gy + 1)];
+        if (sg[0] != h.p_row_ptr[i] || sg[h.gy] != h.p_row_ptr[i + 1]) return false;
+        for (int g = 0; g < h.gy; ++g)
+            if (sg[g + 1] < sg[g]) return false;
+    }
+    // The operand words the row-walk kernel turns into addresses.
+    if (!h.conv) {
+        if ((int64_t)h.K * h.ldb * esz >= (1ll << 31) || (int64_t)h.M * h.ldc * osz >= (1ll << 31)) return false;
+        const uint64_t row_bytes = (uint64_t)h.ldb * (uint64_t)esz, limit = (uint64_t)h.K * row_bytes;
+        for (size_t p = 0; p < nnz; ++p) {
+            const uint64_t off = h.stream[2 * p];
+            if (off >= limit || off % row_bytes) return false;
+        }
+    } else {
+        if (h.Cin <= 0 || h.H <= 0 || h.W <= 0 || (int64_t)h.K != 9ll * h.Cin || (int64_t)h.N != (int64_t)h.H * h.W) return false;
+        if (((int64_t)h.Cin * h.H * h.W + h.W + 1) * esz >= (1ll << 27)) return false;
+        for (size_t i = 0; i < M; ++i) {
+            const int32_t *cs = &h.conv_seg[i * 10];
+            if (cs[0] != h.p_row_ptr[i] || cs[9] != h.p_row_ptr[i + 1]) return false;
+            for (int t = 0; t < 9; ++t) {
+                if (cs[t + 1] < cs[t]) return false;
+                for (int32_t p = cs[t]; p < cs[t + 1]; ++p) {
+                    // the word names tap t and a displacement (c*H*W + (r-1)*W + (s-1)) * esz with c < Cin
+                    const uint32_t w = h.stream[2 * (size_t)p];
+                    if ((int)(w >> 28) != t) return false;
+                    const int64_t d = (int32_t)(w << 4) >> 4;
+                    const int64_t rel = d - ((int64_t)(t / 3 - 1) * h.W + (t % 3 - 1)) * esz;
+                    if (rel < 0 || rel % ((int64_t)h.H * h.W * esz) || rel / ((int64_t)h.H * h.W * esz) >= h.Cin) return false;
+                }
+            }
+        }
+    }
     if (h.kernel == SPARSERT_KERNEL_SPEC) {
-        if (h.spec.code.size() < 64 || h.spec.symbol.empty() || h.spec.group_of_slot.size() != M) return false;
-        if (h.spec.n_groups < 1 || h.spec.n_blocks < h.spec.n_groups || h.spec.n_tiles < 1) return false;
+        const sparsert::SpecPlan &sp = h.spec;
+        if (sp.code.size() < 64 || sp.symbol.empty() || sp.group_of_slot.size() != M) return false;
+        if (sp.n_groups < 1 || sp.n_blocks < sp.n_groups || sp.n_tiles < 1) return false;
+        // what launch_spec turns into a grid, and what the generated prologue assumes of it
+        const int tpw = sp.tiles_per_wg;
+        if (tpw < 1 || tpw > 16 || (tpw & (tpw - 1))) return false;
+        if (sp.mode != SPARSERT_SPEC_DIRECT && sp.mode != SPARSERT_SPEC_LDS) return false;
+        if (sp.vec < 1 || h.N % sp.vec || sp.lanes_per_tile < 1 || sp.lanes_per_tile > sparsert::kWave) return false;
+        const int64_t nvc = h.N / sp.vec;
+        if ((int64_t)sp.n_tiles * sp.lanes_per_tile < nvc || (int64_t)(sp.n_tiles - 1) * sp.lanes_per_tile >= nvc) return false;
+        if (sp.rows_per_group < 1 || (int64_t)sp.n_groups * sp.rows_per_group < h.M) return false;
+        if (sp.lds_bytes < 0 || sp.lds_bytes > 160 * 1024) return false;
+        const bool lds = sp.mode == SPARSERT_SPEC_LDS;
+        if (lds && (sp.ksplit != 1 || sp.n_blocks % tpw)) return false;
+        if (!lds && (sp.ksplit < 1 || sp.n_blocks != sp.n_groups * sp.ksplit || (sp.ksplit > 1 && sp.ksplit != tpw))) return false;
+        if (sp.group_columns.size() != (size_t)sp.n_blocks) return false;
+        for (int32_t g : sp.group_of_slot)
+            if (g < 0 || g >= sp.n_groups) return false;
     }
     return true;
 }

@@ -207,6 +207,7 @@ struct Gen {
     const HostPlan &h;
     SpecPlan &sp;
     int N, K, D;
+    int64_t ldb, ldc;    // elements between consecutive rows of B and of C
     bool half = false;   // B, C and the values of A are IEEE half; sums stay fp32
     bool int8 = false;   // B and the values of A are int8, C is int32, sums are exact integers
     int esz = 4;         // bytes of an element of B / X
@@ -222,7 +223,7 @@ struct Gen {
     bool stream_stores = false;      // every wave store of C covers whole 128-byte lines
     int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
     Gen(const HostPlan &hp, SpecPlan &s)
-        : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth), half(hp.dtype == SPARSERT_F16), int8(hp.dtype == SPARSERT_I8),
+        : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth), ldb(hp.ldb), ldc(hp.ldc), half(hp.dtype == SPARSERT_F16), int8(hp.dtype == SPARSERT_I8),
           esz(half ? 2 : int8 ? 1 : 4), osz(half ? 2 : 4) {}
 
     void zero_accs(size_t n) {
@@ -268,7 +269,7 @@ struct Gen {
     }
     void load_b_row(int k, int vdst, int ring_pos) {
         const int sreg = kSgprOffRing + (ring_pos % kOffRing);
-        e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)k * N * esz));
+        e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)k * ldb * esz));
         e.line("\t%s v%d, v%d, s[%d:%d], s%d offen", load_op(), vdst, kVgprOff, kRsrcB, kRsrcB + 3, sreg);
     }
     // (slot of the permuted CSR, first accumulator register of the row) pairs: one row of C each
@@ -277,7 +278,7 @@ struct Gen {
         e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
         for (size_t i = 0; i < rows.size(); ++i) {
             const int sreg = kSgprOffRing + ((int)i % kOffRing), r = rows[i].second;
-            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i].first] * N * osz));
+            e.line("\ts_mov_b32 s%d, 0x%llx", sreg, (unsigned long long)((int64_t)h.perm[rows[i].first] * ldc * osz));
             const char *op = "buffer_store_dword";
             if (half) {   // one rounding to nearest even, at the store
                 for (int j = 0; j < V; ++j) e.line("\tv_cvt_f16_f32_e32 v%d, v%d", r + j, r + j);
@@ -365,7 +366,7 @@ struct Gen {
         // Byte offset of operand row k from the descriptor base (convolution: Section 3.6, operand row
         // k = c*9 + tap is the input plane c displaced by the tap).
         auto offset_of = [&](int32_t k) -> int64_t {
-            if (!h.conv) return (int64_t)k * N * esz;
+            if (!h.conv) return (int64_t)k * ldb * esz;
             const int c = k / 9, tap = k % 9;
             return ((int64_t)c * h.H * h.W + (tap / 3) * h.W + tap % 3) * esz;
         };
@@ -373,7 +374,7 @@ struct Gen {
         // multiples of the row pitch kept in scalar registers, and the lane's address register is
         // advanced when a row falls outside the table's reach: no scalar move per fetch.  Blocks
         // whose rows are far apart would advance at every fetch and keep the move instead.
-        const int64_t unit = h.conv ? (int64_t)h.H * h.W * esz : (int64_t)N * esz;
+        const int64_t unit = h.conv ? (int64_t)h.H * h.W * esz : ldb * esz;
         bool use_tab = false;
         {
             int64_t base = 0;
@@ -631,6 +632,8 @@ struct Gen {
 
 }  // namespace
 
+bool spec_available() { return comgr().ok; }
+
 int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) {
     SpecPlan &sp = h.spec;
     if (h.conv && opt.spec_mode == SPARSERT_SPEC_LDS) {
@@ -653,7 +656,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     const int V = opt.spec_vec ? opt.spec_vec : 1;
     if (!(V == 1 || (V == 2 && half) || (V == 4 && int8))) { err = "spec_vec must be 0/1, 2 for half plans or 4 for int8 plans"; return SPARSERT_EINVAL; }
     if (V > 1 && (h.conv || lds)) { err = "spec_vec > 1 applies to SpMM plans of the DIRECT variant"; return SPARSERT_EINVAL; }
-    if (N % V) { err = "N must be a multiple of spec_vec"; return SPARSERT_EINVAL; }
+    if (N % V || h.ldb % V || h.ldc % V) { err = "N, ldb and ldc must be multiples of spec_vec"; return SPARSERT_EINVAL; }
     sp.vec = V;
     const int32_t nvc = N / V;   // vector columns
     sp.n_tiles = (nvc + max_lanes - 1) / max_lanes;
@@ -748,10 +751,11 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     }
 
     Gen gen(h, sp);
-    gen.stream_stores = ((int64_t)N * osz) % 128 == 0 && ((int64_t)sp.lanes_per_tile * V * osz) % 128 == 0;
+    gen.stream_stores = ((int64_t)h.ldc * osz) % 128 == 0 && ((int64_t)sp.lanes_per_tile * V * osz) % 128 == 0;
     Emitter &e = gen.e;
-    const int64_t b_bytes = h.conv ? ((int64_t)h.Cin * N + 2 * (h.W + 1)) * esz : (int64_t)h.K * N * esz;
-    const int64_t c_bytes = (int64_t)M * N * osz;
+    // descriptor extents: the last row of a matrix ends after its N columns, whatever the pitch
+    const int64_t b_bytes = h.conv ? ((int64_t)h.Cin * N + 2 * (h.W + 1)) * esz : ((int64_t)(h.K - 1) * h.ldb + N) * esz;
+    const int64_t c_bytes = ((int64_t)(M - 1) * h.ldc + N) * osz;
     // conv: pixel -> (oh, ow) by multiplication with ceil(2^32 / W); verified here for every pixel
     uint32_t magic = 0;
     if (h.conv && h.W > 1) {
@@ -899,7 +903,7 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     }
     if (images) {
         // problem z of the batch: the operand and the result advance by one image / matrix each
-        const int64_t strides[2] = {(h.conv ? (int64_t)h.Cin : (int64_t)h.K) * N * esz, (int64_t)M * N * osz};
+        const int64_t strides[2] = {(h.conv ? (int64_t)h.Cin * N : (int64_t)h.K * h.ldb) * esz, (int64_t)M * h.ldc * osz};
         const int bases[2] = {kSgprB, kSgprC};
         for (int i = 0; i < 2; ++i) {
             e.line("\ts_mov_b32 s%d, 0x%llx", kSgprTmp2, (unsigned long long)strides[i]);

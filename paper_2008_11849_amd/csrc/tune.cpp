@@ -20,24 +20,52 @@
 
 namespace {
 
-float time_plan(sparsert_plan *p, bool conv, const void *in, void *out, hipStream_t s,
-                hipEvent_t e0, hipEvent_t e1, int launches, int repeats) {
-    auto run = [&]() { return conv ? sparsert_conv3x3(p, in, out, s) : sparsert_spmm(p, in, out, s); };
-    for (int i = 0; i < 5; ++i)
-        if (run() != SPARSERT_OK) return -1.0f;
-    float best = -1.0f;
-    for (int r = 0; r < repeats; ++r) {
-        if (hipEventRecord(e0, s) != hipSuccess) return -1.0f;
-        for (int i = 0; i < launches; ++i)
-            if (run() != SPARSERT_OK) return -1.0f;
-        if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1.0f;
-        float ms = 0.0f;
-        if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.0f;
-        const float us = ms * 1000.0f / launches;
-        if (best < 0.0f || us < best) best = us;
+// Times plans on one stream.  "Warm": back-to-back launches of the same plan, whose code and
+// operands then sit in the L2 caches.  "Cold": a fill of more scratch memory than the L2 caches
+// hold runs before every launch, as the other layers of a model would displace this one's code
+// and operands; the fill's own time, measured the same way once, is subtracted.
+struct Bench {
+    hipStream_t s = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    void *scratch = nullptr;
+    size_t scratch_bytes = 0;
+    float fill_us = 0.0f;
+    bool conv = false;
+    const void *in = nullptr;
+    void *out = nullptr;
+    int launches = 30, repeats = 3;
+
+    int run(sparsert_plan *p) const { return conv ? sparsert_conv3x3(p, in, out, s) : sparsert_spmm(p, in, out, s); }
+    bool fill() const {
+        std::string err;
+        return sparsert::displace_caches(scratch, scratch_bytes, s, err) == SPARSERT_OK;
     }
-    return best;
-}
+    // best-of-repeats microseconds per iteration of `body`, which returns false on failure
+    template <typename F> float loop(F body) const {
+        float best = -1.0f;
+        for (int r = 0; r < repeats; ++r) {
+            if (hipEventRecord(e0, s) != hipSuccess) return -1.0f;
+            for (int i = 0; i < launches; ++i)
+                if (!body()) return -1.0f;
+            if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1.0f;
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.0f;
+            const float us = ms * 1000.0f / launches;
+            if (best < 0.0f || us < best) best = us;
+        }
+        return best;
+    }
+    float warm(sparsert_plan *p) const {
+        for (int i = 0; i < 5; ++i)
+            if (run(p) != SPARSERT_OK) return -1.0f;
+        return loop([&] { return run(p) == SPARSERT_OK; });
+    }
+    float cold(sparsert_plan *p) const {
+        if (!scratch) return -1.0f;
+        const float both = loop([&] { return fill() && run(p) == SPARSERT_OK; });
+        return both < 0.0f ? -1.0f : std::max(0.01f, both - fill_us);
+    }
+};
 
 }  // namespace
 
@@ -51,6 +79,8 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     if (base) b = *base; else std::memset(&b, 0, sizeof(b));
     b.host_only = 0;
     b.vec = b.split_threshold = b.spec_rows = b.spec_depth = b.spec_tiles = b.spec_mode = b.spec_ksplit = b.spec_lanes = b.spec_swizzle = b.spec_vec = 0;
+    const int32_t tune_warm = b.tune_warm;
+    b.tune_warm = 0;   // a tuner flag, not a property of the plans
     // First candidate: the inspector's own choice.  It also validates every argument.
     sparsert_plan *best = nullptr;
     {
@@ -62,17 +92,42 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         sparsert_plan_destroy(best);
         return sparsert::set_error(SPARSERT_EINVAL, "out is NULL, or a device pointer is NULL or not 16-byte aligned");
     }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
-        if (e0) (void)hipEventDestroy(e0);
+    // Everything the timing needs lives in `bench`; `Cleanup` releases it on every way out.
+    Bench bench;
+    bench.s = static_cast<hipStream_t>(stream);
+    bench.in = in_dev; bench.out = out_dev; bench.conv = b.conv != 0;
+    void *ref_out = nullptr;        // what the first candidate wrote: every other candidate is held against it
+    uint32_t *res_dev = nullptr;
+    struct Cleanup {
+        Bench &bn; void *&ref; uint32_t *&res;
+        ~Cleanup() {
+            if (bn.e0) (void)hipEventDestroy(bn.e0);
+            if (bn.e1) (void)hipEventDestroy(bn.e1);
+            if (bn.scratch) (void)hipFree(bn.scratch);
+            if (ref) (void)hipFree(ref);
+            if (res) (void)hipFree(res);
+        }
+    } cleanup{bench, ref_out, res_dev};
+    const sparsert::HostPlan &h0 = best->host;
+    const size_t out_bytes = (size_t)h0.batch * h0.M * (size_t)(h0.conv ? h0.N : h0.ldc) * h0.out_elem_size();
+    bench.scratch_bytes = (size_t)64 << 20;   // twice what the eight 4 MiB L2 caches hold
+    if (hipEventCreate(&bench.e0) != hipSuccess || hipEventCreate(&bench.e1) != hipSuccess ||
+        hipMalloc(&bench.scratch, bench.scratch_bytes) != hipSuccess || hipMalloc(&ref_out, out_bytes) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&res_dev), 3 * sizeof(uint32_t)) != hipSuccess) {
         sparsert_plan_destroy(best);
-        return sparsert::set_error(SPARSERT_EHIP, "hipEventCreate failed");
+        return sparsert::set_error(SPARSERT_EHIP, "the tuner could not create its events and scratch buffers");
     }
+    for (int i = 0; i < 3; ++i) (void)bench.fill();
+    bench.fill_us = bench.loop([&] { return bench.fill(); });
+    if (bench.fill_us < 0.0f) {
+        sparsert_plan_destroy(best);
+        return sparsert::set_error(SPARSERT_EHIP, "timing the cache-displacing fill failed");
+    }
+    hipStream_t s = bench.s;
     const bool conv = b.conv != 0, f16 = b.dtype == SPARSERT_F16, i8 = b.dtype == SPARSERT_I8;
+    const bool rank_cold = !tune_warm;
     const int family = b.kernel;   // AUTO: both executor families; else only that one
     const int64_t nnz = row_ptr[M];
-    const int launches = 30, repeats = 3;
 
     std::vector<sparsert_options> cands;
     if (!conv) {
@@ -169,8 +224,33 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         cands.insert(cands.end(), spec_family.begin(), spec_family.end());
     }
 
-    float best_us = time_plan(best, conv, in_dev, out_dev, s, e0, e1, launches, repeats);
-    auto log = [&](const sparsert_plan *p, float us) {
+    // One candidate: poison the output, run, hold the result against the first candidate's, time.
+    struct Timing { float warm = -1.0f, cold = -1.0f; int agrees = 0; };
+    const float tol = i8 ? 0.0f : f16 ? 5e-3f : 1e-3f;   // two correct summation orders differ by far less
+    bool have_ref = false;
+    auto measure = [&](sparsert_plan *p) {
+        Timing t;
+        // 0xff bytes: NaN in both floating types, -1 as an integer; an element a plan fails to write shows
+        if (hipMemsetAsync(out_dev, 0xff, out_bytes, s) != hipSuccess || bench.run(p) != SPARSERT_OK) return t;
+        if (!have_ref) {
+            if (hipMemcpyAsync(ref_out, out_dev, out_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess ||
+                hipStreamSynchronize(s) != hipSuccess) return t;
+            have_ref = true;
+            t.agrees = 1;
+        } else {
+            float dmax = 0.0f, rmax = 0.0f;
+            uint32_t bad = 0;
+            std::string err;
+            if (sparsert::compare_outputs(p->host, out_dev, ref_out, res_dev, s, dmax, rmax, bad, err) != SPARSERT_OK) return t;
+            t.agrees = bad == 0 && dmax <= tol * rmax;
+            if (!t.agrees) return t;
+        }
+        t.warm = bench.warm(p);
+        t.cold = t.warm > 0.0f ? bench.cold(p) : -1.0f;
+        return t;
+    };
+    auto key = [&](const Timing &t) { return rank_cold ? t.cold : t.warm; };
+    auto log = [&](const sparsert_plan *p, const Timing &tm) {
         if (!report || report->count >= SPARSERT_TUNE_MAX) return;
         sparsert_tune_entry &t = report->entries[report->count++];
         const sparsert::HostPlan &h = p->host;
@@ -180,9 +260,10 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         t.spec_lanes = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.lanes_per_tile : 0;
         t.spec_swizzle = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.swizzle : 0;
         t.spec_vec = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.vec : 0;
-        t.microseconds = us;
+        t.microseconds = tm.warm; t.cold_microseconds = tm.cold; t.agrees = tm.agrees;
     };
-    log(best, best_us);
+    Timing best_t = measure(best);
+    log(best, best_t);
     // The host half of a candidate (analysis, code generation, assembling: seconds for a large
     // matrix) is independent of every other candidate's, so a few host threads build the plans
     // ahead, in list order and at most `window` beyond the one being timed; this thread uploads
@@ -244,17 +325,17 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
             if (sparsert::upload_plan(p->host, p->dev, err) != SPARSERT_OK) { sparsert_plan_destroy(p); continue; }
             p->on_device = true;
         }
-        const float us = time_plan(p, conv, in_dev, out_dev, s, e0, e1, launches, repeats);
-        log(p, us);
-        if (us > 0.0f && (best_us <= 0.0f || us < best_us)) {
+        const Timing t = measure(p);
+        log(p, t);
+        if (key(t) > 0.0f && (key(best_t) <= 0.0f || key(t) < key(best_t))) {
             sparsert_plan_destroy(best);
-            best = p; best_us = us;
+            best = p; best_t = t;
         } else {
             sparsert_plan_destroy(p);
         }
     }
     // Last candidate: the winner's configuration with its blocks formed by similarity (row swizzle).
-    if (best_us > 0.0f && best->host.kernel == SPARSERT_KERNEL_SPEC && best->host.spec.rows_per_group > 1 &&
+    if (key(best_t) > 0.0f && best->host.kernel == SPARSERT_KERNEL_SPEC && best->host.spec.rows_per_group > 1 &&
         !b.natural_order) {
         const sparsert::SpecPlan &w = best->host.spec;
         sparsert_options o = b;
@@ -262,22 +343,25 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         o.spec_tiles = w.tiles_per_wg; o.spec_ksplit = w.ksplit; o.spec_vec = w.vec; o.spec_swizzle = 1;
         sparsert_plan *p = nullptr;
         if (sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &p) == SPARSERT_OK) {
-            const float us = time_plan(p, conv, in_dev, out_dev, s, e0, e1, launches, repeats);
-            log(p, us);
-            if (us > 0.0f && us < best_us) {
+            const Timing t = measure(p);
+            log(p, t);
+            if (key(t) > 0.0f && key(t) < key(best_t)) {
                 sparsert_plan_destroy(best);
-                best = p; best_us = us;
+                best = p; best_t = t;
             } else {
                 sparsert_plan_destroy(p);
             }
         }
     }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    if (report) report->best_microseconds = best_us;
-    if (best_us <= 0.0f) {
+    if (report) { report->best_microseconds = best_t.warm; report->best_cold_microseconds = best_t.cold; }
+    if (key(best_t) <= 0.0f) {
         sparsert_plan_destroy(best);
         return sparsert::set_error(SPARSERT_EHIP, "no candidate configuration could be launched and timed");
+    }
+    // leave the winner's result in out_dev (the last candidate timed need not be the winner)
+    if (bench.run(best) != SPARSERT_OK || hipStreamSynchronize(s) != hipSuccess) {
+        sparsert_plan_destroy(best);
+        return sparsert::set_error(SPARSERT_EHIP, "the chosen plan failed to launch");
     }
     *out = best;
     return SPARSERT_OK;

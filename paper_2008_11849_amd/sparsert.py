@@ -26,8 +26,9 @@ SPEC_AUTO, SPEC_DIRECT, SPEC_LDS = 0, 1, 2
 INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", "vec",
               "lanes_per_tile", "n_tiles", "gy", "split_threshold", "n_split", "n_wg_rows",
               "n_bins", "spec_rows", "spec_groups", "spec_depth", "spec_code_bytes",
-              "spec_tiles", "spec_mode", "spec_lds_bytes", "spec_ksplit", "natural_order", "spec_lanes", "spec_swizzle", "batch", "spec_vec"]
-INFO_COUNT = 32
+              "spec_tiles", "spec_mode", "spec_lds_bytes", "spec_ksplit", "natural_order", "spec_lanes", "spec_swizzle", "batch", "spec_vec",
+              "ldb", "ldc"]
+INFO_COUNT = 48
 
 EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_plan_export",
             "sparsert_plan_save", "sparsert_plan_load", "sparsert_plan_destroy", "sparsert_last_error",
@@ -43,7 +44,8 @@ class Options(ctypes.Structure):
                 ("spec_tiles", ctypes.c_int32), ("spec_mode", ctypes.c_int32),
                 ("spec_ksplit", ctypes.c_int32), ("natural_order", ctypes.c_int32),
                 ("spec_lanes", ctypes.c_int32), ("spec_swizzle", ctypes.c_int32),
-                ("spec_vec", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
+                ("spec_vec", ctypes.c_int32), ("ldb", ctypes.c_int32), ("ldc", ctypes.c_int32),
+                ("tune_warm", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
 TUNE_MAX = 64
@@ -54,12 +56,13 @@ class TuneEntry(ctypes.Structure):
                 ("spec_mode", ctypes.c_int32), ("spec_rows", ctypes.c_int32),
                 ("spec_tiles", ctypes.c_int32), ("spec_ksplit", ctypes.c_int32),
                 ("spec_lanes", ctypes.c_int32), ("spec_swizzle", ctypes.c_int32),
-                ("spec_vec", ctypes.c_int32), ("microseconds", ctypes.c_float)]
+                ("spec_vec", ctypes.c_int32), ("microseconds", ctypes.c_float),
+                ("cold_microseconds", ctypes.c_float), ("agrees", ctypes.c_int32)]
 
 
 class TuneReport(ctypes.Structure):
     _fields_ = [("count", ctypes.c_int32), ("best_microseconds", ctypes.c_float),
-                ("entries", TuneEntry * TUNE_MAX)]
+                ("best_cold_microseconds", ctypes.c_float), ("entries", TuneEntry * TUNE_MAX)]
 
 
 class SparseRTError(RuntimeError):
@@ -169,7 +172,8 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
             vec: int = 0, split_threshold: int = 0, kernel: int = KERNEL_AUTO,
             spec_rows: int = 0, spec_depth: int = 0, spec_tiles: int = 0,
             spec_mode: int = 0, spec_ksplit: int = 0, natural_order: bool = False,
-            spec_lanes: int = 0, spec_swizzle: bool = False, spec_vec: int = 0) -> Plan:
+            spec_lanes: int = 0, spec_swizzle: bool = False, spec_vec: int = 0,
+            ldb: int = 0, ldc: int = 0) -> Plan:
     """sparsert_inspect.  `vals` must already be float32, float16 or int8; it is not converted."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -184,6 +188,7 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
     opt.spec_rows, opt.spec_depth, opt.spec_tiles = spec_rows, spec_depth, spec_tiles
     opt.spec_mode, opt.spec_ksplit, opt.natural_order = spec_mode, spec_ksplit, int(natural_order)
     opt.spec_lanes, opt.spec_swizzle, opt.spec_vec = spec_lanes, int(spec_swizzle), spec_vec
+    opt.ldb, opt.ldc = ldb, ldc
     if conv is not None:
         opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
     handle = _vp()
@@ -195,9 +200,10 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
 
 def tune(row_ptr, col_idx, vals, M: int, K: int, N: int, in_dev: int, out_dev: int, stream: int = 0, *,
          conv: Optional[Tuple[int, int, int]] = None, batch: int = 0, kernel: int = KERNEL_AUTO,
-         natural_order: bool = False):
+         natural_order: bool = False, ldb: int = 0, ldc: int = 0, tune_warm: bool = False):
     """sparsert_tune: returns (best plan, list of timed candidates as dicts).  `kernel` other
-    than KERNEL_AUTO restricts the search to that executor family."""
+    than KERNEL_AUTO restricts the search to that executor family; tune_warm ranks by
+    back-to-back launches instead of launches with displaced caches."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
     vals = np.ascontiguousarray(vals)
@@ -206,6 +212,7 @@ def tune(row_ptr, col_idx, vals, M: int, K: int, N: int, in_dev: int, out_dev: i
     opt = Options()
     opt.dtype = _DTYPE_OF[vals.dtype]
     opt.kernel, opt.natural_order, opt.batch = kernel, int(natural_order), batch
+    opt.ldb, opt.ldc, opt.tune_warm = ldb, ldc, int(tune_warm)
     if conv is not None:
         opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
     handle, rep = _vp(), TuneReport()

@@ -289,3 +289,62 @@ def sweep_case(M, K, N, sparsity, mask_kind="uniform", dtype=np.float32) -> Case
         raise KeyError(mask_kind)
     name = f"sweep_{M}x{K}x{N}_s{sparsity}_{mask_kind}_{np.dtype(dtype).name}"
     return Case(name, csr, N, B=normal_dense(K, N, s + 1000, dtype), sparsity=sparsity)
+
+
+# ---------------------------------------------------------------- the paper's problem lists
+# Shapes only (Table 1: twenty SpMM problems from ResNet-50, Transformer and MobileNetV1, at 90 %
+# and, for problems 1-11, 95 % sparsity; Table 3: four 3x3 convolutions as (image, Cin, Cout)).
+# The pruned checkpoints behind them are not available; weights are magnitude-pruned N(0,1) draws.
+TABLE1 = [(64, 256, 3136), (256, 64, 3136), (128, 512, 784), (512, 128, 784), (256, 1024, 196),
+          (1024, 256, 196), (512, 2048, 49), (2048, 512, 49), (2048, 512, 256), (512, 2048, 256),
+          (512, 512, 256), (64, 32, 12544), (128, 64, 3136), (128, 128, 3136), (256, 128, 784),
+          (256, 256, 784), (512, 256, 196), (512, 512, 196), (1024, 512, 49), (1024, 1024, 49)]
+TABLE3 = [(56, 64, 64), (28, 128, 128), (14, 256, 256), (7, 512, 512)]
+
+
+def table1_problems():
+    """(tag, index, sparsity) of every Table 1 instance: problems 1-20 at 90 %, 1-11 at 95 %."""
+    out = [(f"t1_p{i + 1}_90", i, 0.90) for i in range(len(TABLE1))]
+    out += [(f"t1_p{i + 1}_95", i, 0.95) for i in range(11)]
+    return out
+
+
+def table1_case(i: int, sparsity: float, dtype=np.float32) -> Case:
+    M, K, N = TABLE1[i]
+    pct = int(round(sparsity * 100))
+    seed = BASE_SEED + 1000 + 100 * i + pct
+    return Case(f"t1_p{i + 1}_{pct}", magnitude_csr(M, K, sparsity, seed, 1.0, dtype), N,
+                B=normal_dense(K, N, seed + 1, dtype), sparsity=sparsity)
+
+
+def table3_case(i: int, sparsity: float, dtype=np.float32, batch: int = 1) -> Case:
+    img, Cin, Cout = TABLE3[i]
+    pct = int(round(sparsity * 100))
+    seed = BASE_SEED + 5000 + 100 * i + pct
+    csr, Wd = conv_weights_csr(Cout, Cin, sparsity, seed, dtype)
+    X = normal_dense(batch * Cin, img * img, seed + 1, dtype).reshape(batch, Cin, img, img)
+    return Case(f"t3_p{i + 1}_{pct}", csr, img * img, X=X, Wdense=Wd, conv=(Cin, img, img), sparsity=sparsity)
+
+
+# ---------------------------------------------------------------- the shape / sparsity sweep
+SWEEP_MK = [256, 512, 1024, 2048, 4096]
+SWEEP_N = [64, 196, 784, 3136, 4096]
+SWEEP_SPARSITY = [0.80, 0.90, 0.95, 0.98]
+# The measured subset of the M x K cross product: the squares and two 4:1 rectangles.
+SWEEP_SHAPES = [(m, m) for m in SWEEP_MK] + [(4096, 1024), (1024, 4096)]
+
+
+def sweep_sample(count: int, seed: int = BASE_SEED + 77):
+    """A seeded sample of the full sweep grid as (M, K, N, sparsity, mask kind, dtype) tuples:
+    independent uniform draws per axis, except that on every axis the first len(axis) positions
+    (in a seeded rotation) run through all of the axis' values, so that each size, each N, each
+    sparsity, both mask kinds and both storage types occur (count >= 5)."""
+    rng = np.random.default_rng(seed)
+    axes = [SWEEP_MK, SWEEP_MK, SWEEP_N, SWEEP_SPARSITY, ["uniform", "skewed"], [np.float32, np.float16]]
+    cols = []
+    for a in axes:
+        idx = rng.integers(0, len(a), size=count)
+        forced = (int(rng.integers(0, count)) + np.arange(len(a))) % count
+        idx[forced] = rng.permutation(len(a))
+        cols.append([a[i] for i in idx])
+    return list(zip(*cols))

@@ -37,6 +37,32 @@ def run_spmm(csr, B, **opts):
     return out, info
 
 
+def run_spmm_strided(csr, B, ldb, ldc, **opts):
+    """B [K, N] (or [batch, K, N]) handed over at a row pitch of ldb elements, C received at a
+    pitch of ldc.  The unused columns of the operand hold NaN (or a large integer) and those of
+    the result a poison value: returns (C [.., M, N], whether the poison columns of the result
+    buffer are untouched, plan info)."""
+    dev = torch.device("cuda:0")
+    N = B.shape[-1]
+    lead = B.shape[:-2]
+    if B.ndim == 3:
+        opts = dict(opts, batch=B.shape[0])
+    plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, N, ldb=ldb, ldc=ldc, **opts)
+    wide = np.full(lead + (csr.K, ldb), 100 if B.dtype == np.int8 else np.nan, dtype=B.dtype)
+    wide[..., :N] = B
+    Bd = torch.from_numpy(wide).to(dev)
+    Cd = _poisoned(lead + (csr.M, ldc), B.dtype, dev)
+    before = Cd.clone()
+    sp.spmm(plan, Bd.data_ptr(), Cd.data_ptr(), torch.cuda.current_stream(dev).cuda_stream)
+    torch.cuda.synchronize()
+    # the poison of the floating types is NaN, which equals nothing: compare the bytes
+    pad_ok = Cd[..., N:].contiguous().cpu().numpy().tobytes() == before[..., N:].contiguous().cpu().numpy().tobytes()
+    out = Cd[..., :N].contiguous().cpu().numpy()
+    info = plan.info()
+    plan.destroy()
+    return out, pad_ok, info
+
+
 def run_conv(csr, X, Cout, **opts):
     dev = torch.device("cuda:0")
     batch, Cin, H, W = X.shape

@@ -65,7 +65,7 @@ def test_options_struct_matches_header_layout():
     want = _header_struct_fields("sparsert_options")
     got = [(n, getattr(t, "_length_", 1)) for n, t in sp.Options._fields_]
     assert got == want
-    assert ctypes.sizeof(sp.Options) == 4 * sum(c for _, c in want) == 20 * 4
+    assert ctypes.sizeof(sp.Options) == 4 * sum(c for _, c in want) == 25 * 4
     assert [n for n, _ in sp.TuneEntry._fields_] == [n for n, _ in _header_struct_fields("sparsert_tune_entry")]
 
 
@@ -111,6 +111,34 @@ def test_plan_overrides(vec, thr):
     plan = _host_plan(csr, 64, vec=vec, split_threshold=thr)
     _assert_plan_equal(plan, plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, 100, 200, 64,
                                            vec=vec, split_threshold=thr))
+
+
+@pytest.mark.parametrize("N,ldb,ldc,dt", [(100, 128, 0, np.float32), (64, 64, 200, np.float32), (96, 98, 102, np.float16),
+                                          (196, 1024, 4096, np.float32), (64, 68, 64, np.int8)])
+def test_leading_dimensions_in_the_plan(N, ldb, ldc, dt):
+    """A wider row pitch of B changes the operand offsets and which vector widths are legal; nothing else."""
+    csr = synth.int8_csr(70, 50, 0.8, 4) if dt == np.int8 else synth.uniform_csr(70, 50, 0.8, 4, dtype=dt)
+    plan = _host_plan(csr, N, ldb=ldb, ldc=ldc)
+    refp = plan_ref.plan(csr.row_ptr, csr.col_idx, csr.vals, 70, 50, N, ldb=ldb, ldc=ldc)
+    _assert_plan_equal(plan, refp)
+    info = plan.info()
+    assert info["ldb"] == (ldb or N) and info["ldc"] == (ldc or N)
+    assert info["ldb"] % info["vec"] == 0 and info["ldc"] % info["vec"] == 0
+    plan.destroy()
+    for bad in (dict(ldb=N - 1), dict(ldc=N - 1), dict(ldb=-4), dict(ldb=N + 1, vec=2), dict(ldc=N + 2, vec=4)):
+        if N % bad.get("vec", 1):
+            continue
+        with pytest.raises(sp.SparseRTError) as e:
+            _host_plan(csr, N, **bad)
+        assert e.value.status == sp.EINVAL, bad
+    ccsr, _ = synth.conv_weights_csr(4, 2, 0.5, 1)
+    with pytest.raises(sp.SparseRTError) as e:
+        sp.inspect(ccsr.row_ptr, ccsr.col_idx, ccsr.vals, 4, 18, 16, conv=(2, 4, 4), host_only=True, ldb=32)
+    assert e.value.status == sp.EINVAL
+    # the 2 GiB limit of the 32-bit operand offsets counts the pitch, not N
+    with pytest.raises(sp.SparseRTError) as e:
+        _host_plan(synth.uniform_csr(4, 1 << 16, 0.999, 1), 64, ldb=1 << 13)
+    assert e.value.status == sp.EUNSUPPORTED
 
 
 @pytest.mark.parametrize("N,conv", [(64, None), (63, None), (100, None), (1024, None), (42, (4, 6, 7))])

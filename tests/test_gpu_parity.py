@@ -17,26 +17,34 @@ if not torch.cuda.is_available():  # pragma: no cover
     pytest.skip("no GPU", allow_module_level=True)
 
 from gpu_util import check, run_conv, run_spmm  # noqa: E402
+from paper_2008_11849_amd import sparsert as sp  # noqa: E402
+
+# Every case runs with the always-available row-walk kernel and with what the inspector picks
+# when the caller leaves the choice to it (the generated kernel for these sizes).
+FAMILIES = [pytest.param(sp.KERNEL_ROWS, id="rows"), pytest.param(sp.KERNEL_AUTO, id="auto")]
 
 
 def _oracle(csr, B):
     return ref.spmm(csr.M, csr.K, B.shape[1], csr.row_ptr, csr.col_idx, csr.vals, B)
 
 
+@pytest.mark.parametrize("family", FAMILIES)
 @pytest.mark.parametrize("dtype", [np.float32, np.float16])
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c3t"])
-def test_spmm_configs(name, dtype):
+def test_spmm_configs(name, dtype, family):
     case = synth.config(name, dtype)
-    got, info = run_spmm(case.csr, case.B)
+    got, info = run_spmm(case.csr, case.B, kernel=family)
+    assert info["kernel"] == (sp.KERNEL_ROWS if family == sp.KERNEL_ROWS else sp.KERNEL_SPEC)
     Cref, S = _oracle(case.csr, case.B)
     m = check(got, Cref, S, dtype, gate_relative=True)
     print(name, np.dtype(dtype).name, info, m)
 
 
+@pytest.mark.parametrize("family", FAMILIES)
 @pytest.mark.parametrize("dtype", [np.float32, np.float16])
-def test_conv_config_c4(dtype):
+def test_conv_config_c4(dtype, family):
     case = synth.config("c4", dtype)
-    got, info = run_conv(case.csr, case.X, 256)
+    got, info = run_conv(case.csr, case.X, 256, kernel=family)
     Yref, S = ref.conv3x3(case.Wdense, case.X)
     m = check(got, Yref, S, dtype, gate_relative=True)
     print("c4", np.dtype(dtype).name, info, m)
@@ -51,8 +59,8 @@ def test_small_integers_are_bit_exact_any_order(N):
     csr = synth.small_int_csr(77, 130, 0.85, N)
     B = synth.small_int_dense(130, N, N + 1)
     Cref, _ = _oracle(csr, B)
-    for opts in ({}, {"vec": 1}, {"split_threshold": 1}, {"split_threshold": 7, "vec": 1}):
-        if "vec" not in opts and N % 2 == 0:
+    for opts in ({}, {"kernel": sp.KERNEL_ROWS}, {"vec": 1}, {"split_threshold": 1}, {"split_threshold": 7, "vec": 1}):
+        if opts and "vec" not in opts and N % 2 == 0:
             for v in (2, 4):
                 if N % v == 0:
                     got, _ = run_spmm(csr, B, vec=v, **opts)
@@ -67,7 +75,7 @@ def test_small_integers_half(N):
     B = synth.small_int_dense(90, N, N + 1, dtype=np.float16, bmax=4)
     Cref, _ = _oracle(csr, B)
     assert np.abs(Cref).max() <= 2048
-    for opts in ({}, {"vec": 1}, {"vec": 8, "split_threshold": 2}, {"vec": 2}):
+    for opts in ({}, {"kernel": sp.KERNEL_ROWS}, {"vec": 1}, {"vec": 8, "split_threshold": 2}, {"vec": 2}):
         got, _ = run_spmm(csr, B, **opts)
         assert np.array_equal(got.astype(np.float64), Cref), (N, opts)
 
@@ -76,13 +84,14 @@ def test_identity_and_permutation_return_B_bit_for_bit():
     K, N = 300, 196
     B = synth.normal_dense(K, N, 3)
     eye = synth.csr_from_mask(np.eye(K, dtype=np.float32), np.eye(K, dtype=bool))
-    got, _ = run_spmm(eye, B)
-    assert got.tobytes() == B.tobytes()
     perm = np.random.default_rng(0).permutation(K)
     P = np.zeros((K, K), dtype=np.float32)
     P[np.arange(K), perm] = 1.0
-    got, _ = run_spmm(synth.csr_from_mask(P, P != 0), B)
-    assert got.tobytes() == B[perm].tobytes()
+    for family in (sp.KERNEL_ROWS, sp.KERNEL_AUTO):
+        got, _ = run_spmm(eye, B, kernel=family)
+        assert got.tobytes() == B.tobytes()
+        got, _ = run_spmm(synth.csr_from_mask(P, P != 0), B, kernel=family)
+        assert got.tobytes() == B[perm].tobytes()
 
 
 def test_empty_rows_empty_matrix_and_dense_row():
@@ -92,16 +101,18 @@ def test_empty_rows_empty_matrix_and_dense_row():
     A[17, 3] = -2.0                     # one single-nonzero row; all others empty
     csr = synth.csr_from_mask(A, A != 0)
     B = synth.small_int_dense(K, N, 9)
-    got, info = run_spmm(csr, B)
     Cref, _ = _oracle(csr, B)
-    assert np.array_equal(got.astype(np.float64), Cref)
-    assert not np.signbit(got[0]).any()  # empty row: +0.0
+    for family in (sp.KERNEL_ROWS, sp.KERNEL_AUTO):
+        got, info = run_spmm(csr, B, kernel=family)
+        assert np.array_equal(got.astype(np.float64), Cref)
+        assert not np.signbit(got[0]).any()  # empty row: +0.0
     for thr in (1, 16):
         got, _ = run_spmm(csr, B, split_threshold=thr)
         assert np.array_equal(got.astype(np.float64), Cref)
     empty = synth.csr_from_mask(np.zeros((M, K), np.float32), np.zeros((M, K), bool))
-    got, _ = run_spmm(empty, B)
-    assert np.array_equal(got, np.zeros((M, N), np.float32)) and not np.signbit(got).any()
+    for family in (sp.KERNEL_ROWS, sp.KERNEL_AUTO):
+        got, _ = run_spmm(empty, B, kernel=family)
+        assert np.array_equal(got, np.zeros((M, N), np.float32)) and not np.signbit(got).any()
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float16])
@@ -109,10 +120,11 @@ def test_skewed_rows_at_98_percent(dtype):
     csr = synth.skewed_csr(512, 2048, 0.98, 13, dtype=dtype)
     assert (np.diff(csr.row_ptr) == 0).any()
     B = synth.normal_dense(2048, 784, 14, dtype=dtype)
-    got, info = run_spmm(csr, B)
-    assert info["n_split"] > 0
     Cref, S = _oracle(csr, B)
-    check(got, Cref, S, dtype)
+    for family in (sp.KERNEL_ROWS, sp.KERNEL_AUTO):
+        got, info = run_spmm(csr, B, kernel=family)
+        assert info["n_split"] > 0
+        check(got, Cref, S, dtype)
 
 
 def test_run_to_run_determinism_and_two_streams():
@@ -147,9 +159,10 @@ def test_conv_shapes(Cin, Cout, H, W):
     for dtype, sparsity in ((np.float32, 0.9), (np.float16, 0.95)):
         csr, Wd = synth.conv_weights_csr(Cout, Cin, sparsity, Cin + H, dtype=dtype)
         X = synth.normal_dense(Cin, H * W, Cout + W, dtype=dtype).reshape(1, Cin, H, W)
-        got, _ = run_conv(csr, X, Cout)
         Yref, S = ref.conv3x3(Wd, X)
-        check(got, Yref, S, dtype)
+        for family in (sp.KERNEL_ROWS, sp.KERNEL_AUTO):
+            got, _ = run_conv(csr, X, Cout, kernel=family)
+            check(got, Yref, S, dtype)
 
 
 def test_conv_integer_taps_bit_exact():
@@ -159,17 +172,18 @@ def test_conv_integer_taps_bit_exact():
     X = rng.integers(-5, 6, size=(1, Cin, H, W)).astype(np.float32)
     csr = synth.csr_from_mask(Wd.reshape(Cout, -1), Wd.reshape(Cout, -1) != 0)
     Yref, _ = ref.conv3x3(Wd, X)
-    for thr in (0, 1, 5):
-        got, _ = run_conv(csr, X, Cout, split_threshold=thr)
+    for opts in ({}, {"kernel": sp.KERNEL_ROWS}, {"split_threshold": 1}, {"split_threshold": 5}):
+        got, _ = run_conv(csr, X, Cout, **opts)
         assert np.array_equal(got.astype(np.float64), Yref)
     # one tap at a time: a zero-filled shift of the input, bit for bit
     for t in range(9):
         W1 = np.zeros((1, 1, 3, 3), dtype=np.float32)
         W1[0, 0, t // 3, t % 3] = 1.0
         X1 = synth.normal_dense(1, H * W, t).reshape(1, 1, H, W)
-        got, _ = run_conv(synth.csr_from_mask(W1.reshape(1, 9), W1.reshape(1, 9) != 0), X1, 1)
         Yr, _ = ref.conv3x3(W1, X1)
-        assert np.array_equal(got.astype(np.float64), Yr)
+        for family in (sp.KERNEL_ROWS, sp.KERNEL_AUTO):
+            got, _ = run_conv(synth.csr_from_mask(W1.reshape(1, 9), W1.reshape(1, 9) != 0), X1, 1, kernel=family)
+            assert np.array_equal(got.astype(np.float64), Yr)
 
 
 SWEEP = [(256, 256, 64, 0.8, "uniform"), (1024, 512, 196, 0.9, "magnitude"),
@@ -181,9 +195,10 @@ SWEEP = [(256, 256, 64, 0.8, "uniform"), (1024, 512, 196, 0.9, "magnitude"),
 @pytest.mark.parametrize("M,K,N,s,kind", SWEEP)
 def test_sweep_subset_full_check(M, K, N, s, kind, dtype):
     case = synth.sweep_case(M, K, N, s, kind, dtype)
-    got, _ = run_spmm(case.csr, case.B)
     Cref, S = _oracle(case.csr, case.B)
-    check(got, Cref, S, dtype)
+    for family in (sp.KERNEL_ROWS, sp.KERNEL_AUTO):
+        got, _ = run_spmm(case.csr, case.B, kernel=family)
+        check(got, Cref, S, dtype)
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float16])

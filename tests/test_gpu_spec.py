@@ -610,3 +610,48 @@ def test_tune_covers_half_and_conv():
     Yref, S = ref.conv3x3(Wd, X)
     check(Yd.cpu().numpy(), Yref, S, np.float16)
     plan.destroy()
+
+
+# ---------------------------------------------------------------- leading dimensions (strided N)
+@pytest.mark.parametrize("opts", [dict(kernel=sp.KERNEL_ROWS), dict(kernel=sp.KERNEL_ROWS, split_threshold=3),
+                                  dict(kernel=sp.KERNEL_SPEC, spec_rows=5), dict(kernel=sp.KERNEL_SPEC, spec_rows=16, spec_ksplit=4),
+                                  dict(kernel=sp.KERNEL_SPEC, spec_rows=7, spec_mode=sp.SPEC_LDS, spec_tiles=4), dict()])
+@pytest.mark.parametrize("N,ldb,ldc", [(1, 5, 3), (64, 64, 80), (65, 130, 65), (196, 1024, 3136), (256, 260, 264), (300, 304, 512)])
+def test_leading_dimensions_small_integers_bit_exact(N, ldb, ldc, opts):
+    """A column slice of wider activation matrices (Section 4.3: more columns make N larger):
+    only the N columns are read and written, at the given pitches; sums are exact integers."""
+    from gpu_util import run_spmm_strided
+    csr = synth.small_int_csr(60, 140, 0.85, N + ldb)
+    B = synth.small_int_dense(140, N, N + ldc)
+    Cref, _ = ref.spmm(csr.M, csr.K, N, csr.row_ptr, csr.col_idx, csr.vals, B)
+    got, pad_ok, info = run_spmm_strided(csr, B, ldb, ldc, **opts)
+    assert np.array_equal(got.astype(np.float64), Cref), info
+    assert pad_ok, "columns beyond N of the result buffer were written"
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16, np.int8])
+def test_leading_dimensions_batch_and_storage_types(dtype):
+    from gpu_util import run_spmm_strided
+    N, ldb, ldc, batch = 200, 208, 256, 3
+    if dtype == np.int8:
+        csr = synth.int8_csr(90, 300, 0.9, 1)
+        B = synth.int8_dense(batch * 300, N, 2).reshape(batch, 300, N)
+    else:
+        csr = synth.small_int_csr(90, 300, 0.9, 1, dtype=dtype, vmax=3)
+        B = synth.small_int_dense(batch * 300, N, 2, dtype=dtype, bmax=4).reshape(batch, 300, N)
+    want = np.stack([ref.spmm(90, 300, N, csr.row_ptr, csr.col_idx, csr.vals, B[i])[0] for i in range(batch)])
+    for opts in (dict(kernel=sp.KERNEL_ROWS), dict(kernel=sp.KERNEL_SPEC, spec_rows=8, spec_ksplit=2),
+                 dict(kernel=sp.KERNEL_SPEC, spec_rows=6, spec_vec=2 if dtype == np.float16 else 4 if dtype == np.int8 else 1)):
+        got, pad_ok, info = run_spmm_strided(csr, B, ldb, ldc, **opts)
+        assert np.array_equal(got.astype(np.float64), want), (opts, info)
+        assert pad_ok
+
+
+def test_leading_dimensions_headline_layer_slice():
+    """c3 on a 1024-column slice of 4096-column activations, in the plan the inspector picks."""
+    from gpu_util import run_spmm_strided
+    case = synth.config("c3")
+    got, pad_ok, info = run_spmm_strided(case.csr, case.B, 4096, 4096)
+    Cref, S = ref.spmm(case.csr.M, case.csr.K, case.N, case.csr.row_ptr, case.csr.col_idx, case.csr.vals, case.B)
+    check(got, Cref, S, np.float32, gate_relative=True)
+    assert pad_ok and info["kernel"] == sp.KERNEL_SPEC
