@@ -121,7 +121,7 @@ def main():
         rows, want, scale = oracle
         got = out.cpu().numpy()
         got = got if rows is None else got[rows]
-        m = ref.error_metrics(got.reshape(want.shape), want, scale)
+        m = ref.error_metrics(got.reshape(want.shape), want, scale, ref.HALF_STORE_ROUNDING if args.dtype == "f16" else 0.0)
         ok = (not np.isnan(got).any()) and m["exact_on_zero_scale"] and m["componentwise"] <= tol and m["normwise"] <= tol
         if not ok:
             print(f"bench_table1.py: {tag} ({what}): the timed plan disagrees with the oracle: {m}", file=sys.stderr)

@@ -257,7 +257,10 @@ typedef enum sparsert_field {
     SPARSERT_FIELD_SPEC_GROUPS = 12, /* SPEC plans, int32[M]: code block (row group) of each slot */
     SPARSERT_FIELD_SPEC_COLUMNS = 13, /* SPEC plans, int32[blocks]: B rows a code block loads per tile
                                          (blocks = groups x K parts; padded in the LDS variant) */
-    SPARSERT_FIELD_SPEC_CODE = 14 /* SPEC plans, bytes: the generated gfx950 code object */
+    SPARSERT_FIELD_SPEC_CODE = 14, /* SPEC plans, bytes: the generated gfx950 code object */
+    SPARSERT_FIELD_KERNEL_NAME = 15 /* bytes (no terminator): the name a kernel trace shows for this plan's
+                                      launches - the generated kernel's symbol, which carries the problem
+                                      shape, or the row-walk kernel's template instance */
 } sparsert_field;
 
 enum {

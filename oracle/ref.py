@@ -80,20 +80,29 @@ def im2col3x3(X) -> np.ndarray:
     return Bcol
 
 
-def error_metrics(got, ref, scale) -> dict:
+HALF_STORE_ROUNDING = 2.0 ** -25   # half of the spacing of binary16 below 2^-14
+
+
+def error_metrics(got, ref, scale, abs_floor=0.0) -> dict:
     """The three error figures the parity gate uses.
+
+    abs_floor: an absolute error every element is allowed before the figures are formed.  Half
+    storage passes HALF_STORE_ROUNDING: binary16 has the fixed spacing 2^-24 below 2^-14, so the
+    one rounding at the store costs up to 2^-25 whatever the size of the sum, which no bound
+    relative to |A|*|B| can express for results that small.
 
     componentwise: max |got-ref| / S   with S = |A|*|B| (Higham-style bound; the
                    gate), entries with S == 0 must match exactly;
     normwise:      max |got-ref| / max |ref|;
     relative:      max |got-ref| / |ref| over entries with |ref| >= 1e-2 * rms(ref)
                    (below that floor cancellation makes |ref| arbitrarily small and even a
-                   correctly rounded fp32 sum exceeds any fixed relative bound).
+                   correctly rounded fp32 sum exceeds any fixed relative bound);
+                   relative_excluded_fraction is the share of entries below the floor.
     """
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     scale = np.asarray(scale, dtype=np.float64)
-    diff = np.abs(got - ref)
+    diff = np.maximum(np.abs(got - ref) - abs_floor, 0.0)
     zero = scale == 0.0
     exact_on_zero = bool(np.all(diff[zero] == 0.0)) if zero.any() else True
     comp = float(np.max(diff[~zero] / scale[~zero])) if (~zero).any() else 0.0
@@ -103,4 +112,5 @@ def error_metrics(got, ref, scale) -> dict:
     big = np.abs(ref) >= 1e-2 * rms
     rel = float(np.max(diff[big] / np.abs(ref[big]))) if (rms > 0 and big.any()) else 0.0
     return {"componentwise": comp, "normwise": normwise, "relative": rel,
+            "relative_excluded_fraction": float(1.0 - np.mean(big)) if ref.size else 0.0,
             "exact_on_zero_scale": exact_on_zero}

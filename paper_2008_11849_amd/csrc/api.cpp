@@ -95,6 +95,7 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
     int32_t info[SPARSERT_INFO_COUNT] = {0};
     const void *src = nullptr;
     size_t bytes = 0;
+    std::string name;
     auto vec32 = [&](const std::vector<int32_t> &v) { src = v.data(); bytes = v.size() * 4; };
     switch (field) {
     case SPARSERT_FIELD_INFO:
@@ -138,6 +139,16 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
     case SPARSERT_FIELD_SPEC_GROUPS: vec32(h.spec.group_of_slot); break;
     case SPARSERT_FIELD_SPEC_COLUMNS: vec32(h.spec.group_columns); break;
     case SPARSERT_FIELD_SPEC_CODE: src = h.spec.code.data(); bytes = h.spec.code.size(); break;
+    case SPARSERT_FIELD_KERNEL_NAME:
+        if (h.kernel == SPARSERT_KERNEL_SPEC) {
+            name = h.spec.symbol;
+        } else {
+            name = std::string("void sparsert::rows_kernel<") +
+                   (h.dtype == SPARSERT_F16 ? "_Float16" : h.dtype == SPARSERT_I8 ? "signed char" : "float") + ", " +
+                   std::to_string(h.vec) + ", " + (h.conv ? "true" : "false") + ">(sparsert::RowsArgs)";
+        }
+        src = name.data(); bytes = name.size();
+        break;
     default: return fail(SPARSERT_EINVAL, "unknown plan field");
     }
     if (need) *need = bytes;

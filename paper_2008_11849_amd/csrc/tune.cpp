@@ -274,7 +274,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     std::condition_variable cv;
     size_t next = 0, consumed = 0;
     bool stop = false;
-    const size_t window = 8;
+    const size_t window = 12;
     auto worker = [&]() {
         for (;;) {
             size_t i;
@@ -307,7 +307,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         }
     } pool{{}, mu, cv, stop, built};
     const unsigned hw = std::thread::hardware_concurrency();
-    const size_t n_threads = std::min<size_t>(cands.size(), std::max(1u, std::min(4u, hw / 2)));
+    const size_t n_threads = std::min<size_t>(cands.size(), std::max(1u, std::min(8u, hw / 2)));
     for (size_t t = 0; t < n_threads; ++t) pool.threads.emplace_back(worker);
     for (size_t i = 0; i < cands.size(); ++i) {
         sparsert_plan *p = nullptr;

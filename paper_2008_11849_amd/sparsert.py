@@ -22,7 +22,7 @@ KERNEL_AUTO, KERNEL_ROWS, KERNEL_SPEC = 0, 1, 2
 SPEC_AUTO, SPEC_DIRECT, SPEC_LDS = 0, 1, 2
 (FIELD_INFO, FIELD_ROW_NNZ, FIELD_HIST, FIELD_PERM, FIELD_INV_PERM, FIELD_P_ROW_PTR,
  FIELD_P_COL_IDX, FIELD_P_VALS, FIELD_BINS, FIELD_STREAM, FIELD_CONV_SEG,
- FIELD_SEGMENTS, FIELD_SPEC_GROUPS, FIELD_SPEC_COLUMNS, FIELD_SPEC_CODE) = range(15)
+ FIELD_SEGMENTS, FIELD_SPEC_GROUPS, FIELD_SPEC_COLUMNS, FIELD_SPEC_CODE, FIELD_KERNEL_NAME) = range(16)
 INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", "vec",
               "lanes_per_tile", "n_tiles", "gy", "split_threshold", "n_split", "n_wg_rows",
               "n_bins", "spec_rows", "spec_groups", "spec_depth", "spec_code_bytes",
@@ -121,7 +121,7 @@ def _check(rc: int):
         raise SparseRTError(rc, last_error())
 
 
-_FIELD_DTYPE = {FIELD_STREAM: np.uint32, FIELD_SPEC_CODE: np.uint8}
+_FIELD_DTYPE = {FIELD_STREAM: np.uint32, FIELD_SPEC_CODE: np.uint8, FIELD_KERNEL_NAME: np.uint8}
 
 
 class Plan:
@@ -146,6 +146,10 @@ class Plan:
     def info(self) -> dict:
         raw = self.export(FIELD_INFO)
         return {k: int(raw[i]) for i, k in enumerate(INFO_NAMES)}
+
+    def kernel_name(self) -> str:
+        """The name a kernel trace shows for this plan's launches."""
+        return self.export(FIELD_KERNEL_NAME).tobytes().decode()
 
     def save(self) -> bytes:
         """sparsert_plan_save: the whole plan (with its generated code, if any) as bytes."""

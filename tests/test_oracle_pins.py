@@ -240,3 +240,19 @@ def test_error_metric_flags_a_planted_mistake():
     bad = good.copy()
     bad[3, 10] -= np.float32(c.csr.vals[p]) * c.B[c.csr.col_idx[p], 10]
     assert ref.error_metrics(bad, C, S)["componentwise"] > 1e-4 or abs(c.B[c.csr.col_idx[p], 10]) < 1e-3
+
+
+def test_half_store_rounding_floor_of_the_error_metrics():
+    """binary16 is spaced 2^-24 below 2^-14: rounding a tiny sum to half costs up to 2^-25 in
+    absolute terms.  The floor forgives exactly that and nothing more."""
+    want = np.array([[8.0e-8, 1.0, -2.5e-6]])
+    scale = np.abs(want)
+    got = want.astype(np.float16).astype(np.float64)          # one round-to-nearest-even
+    assert np.abs(got - want).max() <= ref.HALF_STORE_ROUNDING
+    assert ref.error_metrics(got, want, scale)["componentwise"] > 2e-2            # 8.0e-8 -> 2^-24 = 5.96e-8 is 25 % off ...
+    m = ref.error_metrics(got, want, scale, ref.HALF_STORE_ROUNDING)
+    assert m["componentwise"] <= 2.0 ** -11 and m["normwise"] <= 2.0 ** -11      # ... and within the format's rounding
+    off = got.copy()
+    off[0, 1] += 2.0 ** -9                                                        # a real error of two ulp of 1.0
+    assert ref.error_metrics(off, want, scale, ref.HALF_STORE_ROUNDING)["componentwise"] > 1.9e-3
+    assert ref.HALF_STORE_ROUNDING == 2.0 ** -25 == np.float64(np.nextafter(np.float16(0), np.float16(1))) / 2
