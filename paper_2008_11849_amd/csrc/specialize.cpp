@@ -38,6 +38,7 @@
 #include <map>
 #include <mutex>
 #include <stdexcept>
+#include <string>
 
 #include "plan.h"
 
@@ -46,7 +47,10 @@ namespace sparsert {
 namespace {
 
 // ---------------------------------------------------------------- code object manager
-// Loaded at run time so the library itself has no link-time dependency on it.
+// Loaded at run time so the library itself has no link-time dependency on it.  The entry points
+// and the enumerator values below are those of interface version 3 of the code object manager
+// (amd_comgr.h); a library that reports another major version is not used.
+constexpr size_t kComgrMajor = 3;
 typedef struct { uint64_t handle; } comgr_handle;
 enum { COMGR_SUCCESS = 0, COMGR_KIND_SOURCE = 1, COMGR_KIND_RELOCATABLE = 7, COMGR_KIND_EXECUTABLE = 8,
        COMGR_KIND_LOG = 5, COMGR_ACTION_LINK_RELOC_TO_EXE = 7, COMGR_ACTION_ASSEMBLE = 8 };
@@ -68,6 +72,8 @@ struct Comgr {
     int (*set_isa_name)(comgr_handle, const char *) = nullptr;
     int (*set_logging)(comgr_handle, bool) = nullptr;
     int (*do_action)(int, comgr_handle, comgr_handle, comgr_handle) = nullptr;
+    void (*get_version)(size_t *, size_t *) = nullptr;
+    size_t major = 0, minor = 0;
     bool ok = false;
 };
 
@@ -98,8 +104,10 @@ Comgr &comgr() {
         COMGR_SYM(set_isa_name, "amd_comgr_action_info_set_isa_name");
         COMGR_SYM(set_logging, "amd_comgr_action_info_set_logging");
         COMGR_SYM(do_action, "amd_comgr_do_action");
+        COMGR_SYM(get_version, "amd_comgr_get_version");
 #undef COMGR_SYM
-        c.ok = all;
+        if (all) c.get_version(&c.major, &c.minor);
+        c.ok = all && c.major == kComgrMajor;
     });
     return c;
 }
@@ -124,7 +132,13 @@ std::string fetch_log(Comgr &c, comgr_handle set) {
 
 int assemble(const std::string &text, std::vector<char> &code, std::string &err) {
     Comgr &c = comgr();
-    if (!c.ok) { err = "code object manager (libamd_comgr) is not available"; return SPARSERT_ECOMPILE; }
+    if (!c.ok) {
+        err = c.lib && c.major != kComgrMajor
+                  ? "code object manager (libamd_comgr) has interface version " + std::to_string(c.major) + "." +
+                        std::to_string(c.minor) + ", this library was written against version 3"
+                  : std::string("code object manager (libamd_comgr) is not available");
+        return SPARSERT_ECOMPILE;
+    }
     comgr_handle src{0}, in{0}, rel{0}, exe{0}, info{0}, out{0};
     int rc = SPARSERT_ECOMPILE;
     bool have_src = false, have_in = false, have_rel = false, have_exe = false, have_info = false;
@@ -634,14 +648,20 @@ struct Gen {
 
 bool spec_available() { return comgr().ok; }
 
-int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) {
-    SpecPlan &sp = h.spec;
+// What the stages below hand to each other besides the SpecPlan itself.
+struct Shape {
+    bool lds = false;   // LDS-staged variant
+    int max_lanes = kWave, V = 1, nvc = 0, KS = 1, W = 4, wshift = 2;
+};
+
+// Stage 1, launch policy: variant, column tiling, columns per lane, rows per block, K split,
+// waves per workgroup, fetch depth, number of code blocks.
+static int choose_launch_shape(const HostPlan &h, const sparsert_options &opt, SpecPlan &sp, Shape &sh, std::string &err) {
     if (h.conv && opt.spec_mode == SPARSERT_SPEC_LDS) {
         err = "convolution plans use the DIRECT variant of the generated kernel";
         return SPARSERT_EUNSUPPORTED;
     }
     const bool half = h.dtype == SPARSERT_F16, int8 = h.dtype == SPARSERT_I8;
-    const int esz = half ? 2 : int8 ? 1 : 4, osz = half ? 2 : 4;
     if ((half || int8) && opt.spec_mode == SPARSERT_SPEC_LDS) {
         err = "half and int8 plans use the DIRECT variant of the generated kernel";
         return SPARSERT_EUNSUPPORTED;
@@ -695,17 +715,24 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     sp.n_groups = (M + R - 1) / R;
     sp.depth = opt.spec_depth ? opt.spec_depth : (lds ? 6 : 16);
     if (lds && sp.depth > 12) sp.depth = 12;
-    // Block-level balance (Section 3.4, strategy b): slots are in descending-nnz order; deal
-    // them to the groups in serpentine order so every group gets nearly the same nonzero count.
     const int G = sp.n_groups;
     // LDS mode: a workgroup runs W consecutive blocks and every one of them takes part in the
     // staging and the barriers, so the block list is padded with empty blocks.
-    KS = sp.ksplit;
-    const int n_blocks = lds ? (G + W - 1) / W * W : G * KS;
-    sp.n_blocks = n_blocks;
+    sp.n_blocks = lds ? (G + W - 1) / W * W : G * sp.ksplit;
+    sh.lds = lds; sh.max_lanes = max_lanes; sh.V = V; sh.nvc = nvc; sh.KS = sp.ksplit; sh.W = W; sh.wshift = wshift;
+    return SPARSERT_OK;
+}
+
+// Stage 2, block formation: which slots (rows of the permuted CSR) share a code block.
+static void form_blocks(const HostPlan &h, const sparsert_options &opt, SpecPlan &sp,
+                        std::vector<std::vector<int32_t>> &members) {
+    const int32_t M = h.M;
+    const int R = sp.rows_per_group, G = sp.n_groups;
+    // Block-level balance (Section 3.4, strategy b): slots are in descending-nnz order; deal
+    // them to the groups in serpentine order so every group gets nearly the same nonzero count.
+    members.assign(sp.n_blocks, {});
     sp.group_of_slot.resize(M);
     sp.swizzle = opt.spec_swizzle && !h.natural_order;
-    std::vector<std::vector<int32_t>> members(n_blocks);
     if (!sp.swizzle) {
         for (int32_t i = 0; i < M; ++i) {
             const int32_t round = i / G, pos = i % G;
@@ -750,14 +777,23 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
         }
     }
 
-    Gen gen(h, sp);
+}
+
+// Stage 3, register and LDS plan: where accumulators, the operand ring, staging registers and the
+// exchange area sit; the descriptor extents; the convolution's pixel-index constant.
+struct Extents { int64_t b_bytes = 0, c_bytes = 0; uint32_t magic = 0; };
+
+static int plan_registers(const HostPlan &h, SpecPlan &sp, const Shape &sh, const std::vector<std::vector<int32_t>> &members,
+                          Gen &gen, Extents &ex, std::string &err) {
+    const bool half = gen.half, int8 = gen.int8, lds = sh.lds;
+    const int esz = gen.esz, osz = gen.osz, V = sh.V, KS = sh.KS, W = sh.W, max_lanes = sh.max_lanes;
+    const int32_t M = h.M, N = h.N;
     gen.stream_stores = ((int64_t)h.ldc * osz) % 128 == 0 && ((int64_t)sp.lanes_per_tile * V * osz) % 128 == 0;
-    Emitter &e = gen.e;
     // descriptor extents: the last row of a matrix ends after its N columns, whatever the pitch
-    const int64_t b_bytes = h.conv ? ((int64_t)h.Cin * N + 2 * (h.W + 1)) * esz : ((int64_t)(h.K - 1) * h.ldb + N) * esz;
-    const int64_t c_bytes = ((int64_t)(M - 1) * h.ldc + N) * osz;
+    ex.b_bytes = h.conv ? ((int64_t)h.Cin * N + 2 * (h.W + 1)) * esz : ((int64_t)(h.K - 1) * h.ldb + N) * esz;
+    ex.c_bytes = ((int64_t)(M - 1) * h.ldc + N) * osz;
     // conv: pixel -> (oh, ow) by multiplication with ceil(2^32 / W); verified here for every pixel
-    uint32_t magic = 0;
+    uint32_t &magic = ex.magic;
     if (h.conv && h.W > 1) {
         magic = (uint32_t)(((1ull << 32) + h.W - 1) / h.W);
         for (int64_t p = 0; p < N; ++p)
@@ -791,10 +827,23 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
             if (gen.lds_bytes == 0) gen.lds_bytes = 256;
         }
     }
-    const int n_vgpr = gen.n_vgpr;
-    if (n_vgpr > 256) { err = "spec_rows too large for the register file"; return SPARSERT_EINVAL; }
+    if (gen.n_vgpr > 256) { err = "spec_rows too large for the register file"; return SPARSERT_EINVAL; }
     sp.lds_bytes = gen.lds_bytes;
 
+    return SPARSERT_OK;
+}
+
+// Stage 4a, emission of everything before the blocks: directives, the prologue that turns the
+// workgroup and lane ids into a block, a column and two buffer descriptors, and the jump table.
+static void emit_prologue(Gen &gen, const Shape &sh, const Extents &ex) {
+    const HostPlan &h = gen.h;
+    SpecPlan &sp = gen.sp;
+    Emitter &e = gen.e;
+    const bool half = gen.half, int8 = gen.int8, lds = sh.lds;
+    const int esz = gen.esz, osz = gen.osz, V = sh.V, KS = sh.KS, wshift = sh.wshift, nvc = sh.nvc, n_blocks = sp.n_blocks;
+    const int32_t M = h.M, N = h.N;
+    const int64_t b_bytes = ex.b_bytes, c_bytes = ex.c_bytes;
+    const uint32_t magic = ex.magic;
     e.line("\t.amdgcn_target \"amdgcn-amd-amdhsa--gfx950\"");
     e.line("\t.amdhsa_code_object_version 6");
     e.line("\t.text");
@@ -931,13 +980,16 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line(".Ltable:");
     for (int g = 0; g < n_blocks; ++g) e.line("\t.long .Lg%d-.Ltable", g);
 
-    sp.group_columns.assign(n_blocks, 0);
-    for (int g = 0; g < n_blocks; ++g) {
-        e.line("\t.p2align 2");
-        e.line(".Lg%d:", g);
-        sp.group_columns[g] = lds ? gen.block_lds(members[g], g % W, W)
-                                  : gen.block_direct(members[g / KS], g % KS, KS);
-    }
+}
+
+// Stage 4b, emission of what follows the blocks: the kernel descriptor and the code object metadata.
+static void emit_kernel_descriptor(Gen &gen, const Shape &sh) {
+    const HostPlan &h = gen.h;
+    SpecPlan &sp = gen.sp;
+    Emitter &e = gen.e;
+    const char *sym = sp.symbol.c_str();
+    const bool images = h.batch > 1;
+    const int n_vgpr = gen.n_vgpr, W = sh.W;
     e.line(".Lfunc_end:");
     e.line("\t.size\t%s, .Lfunc_end-%s", sym, sym);
     e.line("\t.section\t.rodata,\"a\",@progbits");
@@ -1011,6 +1063,28 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     e.line("...");
     e.line("");
     e.line("\t.end_amdgpu_metadata");
+
+}
+
+int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) {
+    SpecPlan &sp = h.spec;
+    Shape sh;
+    if (int rc = choose_launch_shape(h, opt, sp, sh, err)) return rc;
+    std::vector<std::vector<int32_t>> members;
+    form_blocks(h, opt, sp, members);
+    Gen gen(h, sp);
+    Extents ex;
+    if (int rc = plan_registers(h, sp, sh, members, gen, ex, err)) return rc;
+    emit_prologue(gen, sh, ex);
+    Emitter &e = gen.e;
+    sp.group_columns.assign(sp.n_blocks, 0);
+    for (int g = 0; g < sp.n_blocks; ++g) {
+        e.line("\t.p2align 2");
+        e.line(".Lg%d:", g);
+        sp.group_columns[g] = sh.lds ? gen.block_lds(members[g], g % sh.W, sh.W)
+                                     : gen.block_direct(members[g / sh.KS], g % sh.KS, sh.KS);
+    }
+    emit_kernel_descriptor(gen, sh);
 
     if (const char *dump = getenv("SPARSERT_DUMP_ASM")) {
         if (FILE *f = fopen(dump, "w")) { fwrite(e.s.data(), 1, e.s.size(), f); fclose(f); }
