@@ -69,7 +69,8 @@ typedef enum sparsert_spec_mode {
     SPARSERT_SPEC_DIRECT = 1, /* a workgroup's waves run one code block on adjacent column tiles;
                                  B rows are read straight from L2/L1 */
     SPARSERT_SPEC_LDS = 2     /* a workgroup's waves run adjacent code blocks on one column tile;
-                                 the tile's B rows are staged once through LDS */
+                                 the tile's B rows are staged once through LDS (SpMM plans of every
+                                 storage type; half and int8 operands are widened to 32 bits on the way in) */
 } sparsert_spec_mode;
 
 /* Zero-initialise, then set what you need.  All-zero = fp32 SpMM, automatic tiling. */

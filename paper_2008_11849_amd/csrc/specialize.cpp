@@ -21,7 +21,8 @@
 //   DIRECT with K split: workgroup = KS waves sharing one block and one tile, each walking
 //           a contiguous range of the block's columns with an equal share of its nonzeros
 //           (Section 3.4); the partial sums meet in LDS after the walk (Section 3.3).
-//   LDS   : workgroup = W waves running W adjacent blocks on the same tile.  The tile's
+//   LDS   : workgroup = W waves running W adjacent blocks on the same tile (SpMM; fp32, and half
+//           and int8 widened to 32 bits on their way into LDS).  The tile's
 //           B rows are staged once per workgroup through LDS in chunks of up to 128 rows
 //           (double buffered, one barrier per chunk; each wave fetches a 1/W share) and
 //           every wave reads its b values from LDS with compile-time offsets.  Measured
@@ -235,6 +236,7 @@ struct Gen {
     int slot_bytes = 256;            // K split: bytes of one row's partial sums in the exchange area
     int xchg_rows = 0;               // K split: rows exchanged per phase (all of them if they fit the LDS)
     bool stream_stores = false;      // every wave store of C covers whole 128-byte lines
+    bool staged = false;             // LDS variant: operands reach the multiply-adds through LDS, already widened to 32 bits
     int chunk_rows = kMaxChunkRows;  // LDS mode: 32 rows per wave of the workgroup, at most 128
     Gen(const HostPlan &hp, SpecPlan &s)
         : h(hp), sp(s), N(hp.N), K(hp.K), D(s.depth), ldb(hp.ldb), ldc(hp.ldc), half(hp.dtype == SPARSERT_F16), int8(hp.dtype == SPARSERT_I8),
@@ -252,7 +254,7 @@ struct Gen {
         if (terms.empty()) return;
         if (int8 && V == 4)   // the four packed operands, sign-extended once per fetched row of B
             for (int j = 0; j < 4; ++j) e.line("\tv_bfe_i32 v%d, v%d, %d, 8", vgpr_unpack0 + j, vb, 8 * j);
-        if (half) {
+        if (half && !staged) {
             if (V == 2)   // the high half of the dword is the next column
                 e.line("\tv_cvt_f32_f16_sdwa v%d, v%d dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1", vgpr_unpack0, vb);
             e.line("\tv_cvt_f32_f16_e32 v%d, v%d", vb, vb);
@@ -575,6 +577,10 @@ struct Gen {
             for (int q = w; q < quads_per_chunk; q += W, ++t) {
                 if (c * kChunkRows + 4 * q >= K) break;
                 const int v = vgpr_stage0 + (c & 1) * 4 * quads_per_wave + 4 * t;
+                // half storage: widened once here (exact), so the staged tile and everything after
+                // it is the fp32 code; int8 arrives sign-extended by the load itself
+                if (half)
+                    for (int j = 0; j < 4 && c * kChunkRows + 4 * q + j < K; ++j) e.line("\tv_cvt_f32_f16_e32 v%d, v%d", v + j, v + j);
                 e.line("\tds_write_b128 v%d, v[%d:%d] offset:%d", kVgprLds, v, v + 3, (c & 1) * buf_bytes + q * 1024);
             }
         };
@@ -662,10 +668,6 @@ static int choose_launch_shape(const HostPlan &h, const sparsert_options &opt, S
         return SPARSERT_EUNSUPPORTED;
     }
     const bool half = h.dtype == SPARSERT_F16, int8 = h.dtype == SPARSERT_I8;
-    if ((half || int8) && opt.spec_mode == SPARSERT_SPEC_LDS) {
-        err = "half and int8 plans use the DIRECT variant of the generated kernel";
-        return SPARSERT_EUNSUPPORTED;
-    }
     const int32_t M = h.M, N = h.N;
     sp.mode = opt.spec_mode ? opt.spec_mode : SPARSERT_SPEC_DIRECT;
     const bool lds = sp.mode == SPARSERT_SPEC_LDS;
@@ -806,6 +808,7 @@ static int plan_registers(const HostPlan &h, SpecPlan &sp, const Shape &sh, cons
     for (auto &m : members) max_rows = std::max<int>(max_rows, (int)m.size());
     const int D = sp.depth;
     if (lds) {
+        gen.staged = true;
         gen.chunk_rows = std::min(kMaxChunkRows, 32 * W);
         const int kChunkRows = gen.chunk_rows;
         const int quads_per_wave = (kChunkRows / 4 + W - 1) / W;

@@ -160,7 +160,7 @@ def test_int8_plan_is_bit_exact(N, conv):
     if not conv:
         assert np.array_equal(stream[:, 1].view(np.int32), plan.export(sp.FIELD_P_VALS).astype(np.int32))
     plan.destroy()
-    for bad in ({"vec": 2}, {"kernel": sp.KERNEL_SPEC, "spec_mode": sp.SPEC_LDS}):
+    for bad in ({"vec": 2},) + (({"kernel": sp.KERNEL_SPEC, "spec_mode": sp.SPEC_LDS},) if conv else ()):
         with pytest.raises(sp.SparseRTError):
             _host_plan(csr, 64 if not conv else N, conv=conv, **bad)
 

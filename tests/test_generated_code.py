@@ -59,10 +59,11 @@ def test_packed_columns_stay_in_bounds(N, vec, dtype, ks, tmp_path):
     _clean(_csr(dtype, 100, 200, 0.85, 5), N, tmp_path, spec_rows=12, spec_vec=vec, spec_ksplit=ks)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float16, np.int8])
 @pytest.mark.parametrize("waves", [1, 2, 4, 8, 16])
 @pytest.mark.parametrize("K", [5, 128, 129, 515])
-def test_lds_staged_blocks_stay_in_bounds(waves, K, tmp_path):
-    csr = synth.uniform_csr(90, K, 0.8, K)
+def test_lds_staged_blocks_stay_in_bounds(waves, K, dtype, tmp_path):
+    csr = _csr(dtype, 90, K, 0.8, K)
     info, stats = _clean(csr, 130, tmp_path, spec_rows=6, spec_mode=sp.SPEC_LDS, spec_tiles=waves)
     assert stats["lds"] > 0 and stats["max_lds_end"] <= info["spec_lds_bytes"]
 
@@ -140,8 +141,6 @@ def test_random_generated_kernels_are_clean(M, K, N, sparsity, rows, ks, mode, d
     opts = dict(spec_rows=rows, spec_ksplit=ks, spec_mode=mode, spec_swizzle=swizzle)
     if mode == sp.SPEC_LDS:
         opts["spec_ksplit"] = 0
-        if dtype != np.float32:
-            opts["spec_mode"] = sp.SPEC_DIRECT
     try:
         text, info = _generated(csr, N, tmp_path, **opts)
     except sp.SparseRTError as e:

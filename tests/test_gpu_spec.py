@@ -568,11 +568,39 @@ def test_spec_conv_integer_taps_bit_exact():
 
 
 def test_spec_rejects_what_it_does_not_cover():
-    csr = synth.uniform_csr(16, 18, 0.5, 1, dtype=np.float16)
-    with pytest.raises(sp.SparseRTError) as e:
-        sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 16, 18, 8, kernel=sp.KERNEL_SPEC, host_only=True,
+    ccsr, _ = synth.conv_weights_csr(4, 2, 0.5, 1)
+    with pytest.raises(sp.SparseRTError) as e:   # the LDS-staged variant is for SpMM plans
+        sp.inspect(ccsr.row_ptr, ccsr.col_idx, ccsr.vals, 4, 18, 16, conv=(2, 4, 4), kernel=sp.KERNEL_SPEC, host_only=True,
                    spec_mode=sp.SPEC_LDS)
     assert e.value.status == sp.EUNSUPPORTED
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.int8])
+@pytest.mark.parametrize("N,waves", [(1, 1), (65, 4), (196, 8), (300, 16)])
+def test_lds_staged_variant_half_and_int8_bit_exact(N, waves, dtype):
+    """Operands of the narrow storage types are widened to 32 bits on their way into LDS."""
+    if dtype == np.int8:
+        csr, B = synth.int8_csr(70, 270, 0.85, N), synth.int8_dense(270, N, N + 1)
+    else:
+        csr = synth.small_int_csr(70, 270, 0.85, N, dtype=np.float16, vmax=3)
+        B = synth.small_int_dense(270, N, N + 1, dtype=np.float16, bmax=4)
+    Cref, _ = _oracle(csr, B)
+    for rows in (1, 5, 24):
+        got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_mode=sp.SPEC_LDS, spec_rows=rows, spec_tiles=waves)
+        assert info["spec_mode"] == sp.SPEC_LDS
+        assert np.array_equal(got.astype(np.float64), Cref), (rows, info)
+
+
+def test_lds_staged_variant_half_config_and_batch():
+    case = synth.config("c2", np.float16)
+    got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_mode=sp.SPEC_LDS, spec_rows=12, spec_tiles=8)
+    Cref, S = _oracle(case.csr, case.B)
+    check(got, Cref, S, np.float16, gate_relative=True)
+    B3 = np.stack([case.B, case.B[::-1].copy(), case.B * np.float16(0.5)])
+    got, _ = run_spmm(case.csr, B3, kernel=sp.KERNEL_SPEC, spec_mode=sp.SPEC_LDS, spec_rows=12, spec_tiles=4)
+    for i in range(3):
+        Cref, S = _oracle(case.csr, B3[i])
+        check(got[i], Cref, S, np.float16)
 
 
 def test_tune_returns_a_correct_plan_and_a_report():
