@@ -233,6 +233,25 @@ int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, const void *va
                   const void *in_dev, void *out_dev, void *stream,
                   sparsert_plan **out, sparsert_tune_report *report);
 
+/*
+ * Comparison of two results of one plan: what the autotuner does with every candidate (Section 3.7
+ * searches configurations that must all compute the same product), callable on its own to hold a
+ * new plan's output against a trusted one on live operands.
+ *
+ *   a_dev, b_dev  DEVICE, two outputs of `plan` ([batch, M, ldc] / [batch, Cout, H, W], the plan's
+ *                 result type), 16-byte aligned, read only; only the N valid columns are looked at
+ *   result_dev    DEVICE, four 32-bit words, 16-byte aligned, written: the bits of the float
+ *                 max |a - b| and of the float max |b| over elements finite in both (0 for int8 plans),
+ *                 the number of elements that differ in kind (finite against not finite, NaN against
+ *                 not NaN; for int8 plans: that differ at all), and the number of blocks used
+ *
+ * Deterministic (no atomics).  Allocates its partial results for the call and frees them before it
+ * returns, so it synchronises `stream`.  Errors: EINVAL (null / misaligned pointer, host-only plan,
+ * other device), ENOMEM, EHIP.
+ */
+int sparsert_compare_outputs(const sparsert_plan *plan, const void *a_dev, const void *b_dev,
+                             void *result_dev, void *stream);
+
 /* Arrays of the plan that sparsert_plan_export can copy out (HOST side). */
 typedef enum sparsert_field {
     SPARSERT_FIELD_INFO = 0,      /* int32[SPARSERT_INFO_COUNT], see below */

@@ -158,6 +158,17 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
     return SPARSERT_OK;
 }
 
+int sparsert_compare_outputs(const sparsert_plan *plan, const void *a_dev, const void *b_dev, void *result_dev, void *stream) {
+    if (!plan) return fail(SPARSERT_EINVAL, "plan is NULL");
+    if (!a_dev || !b_dev || !result_dev) return fail(SPARSERT_EINVAL, "device pointer is NULL");
+    if (((uintptr_t)a_dev | (uintptr_t)b_dev | (uintptr_t)result_dev) & 15u) return fail(SPARSERT_EINVAL, "device pointers must be 16-byte aligned");
+    if (!plan->on_device) return fail(SPARSERT_EINVAL, "plan was made with host_only");
+    if (!sparsert::on_plan_device(plan->dev)) return fail(SPARSERT_EINVAL, "the plan's arrays live on another HIP device than the current one");
+    std::string err;
+    int rc = sparsert::compare_with_own_partials(plan->host, a_dev, b_dev, static_cast<uint32_t *>(result_dev), stream, err);
+    return rc == SPARSERT_OK ? rc : fail(rc, err);
+}
+
 void sparsert_plan_destroy(sparsert_plan *plan) {
     if (!plan) return;
     sparsert::free_device_plan(plan->dev);

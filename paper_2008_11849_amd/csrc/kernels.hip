@@ -16,6 +16,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <type_traits>
 
 #include "plan.h"
@@ -387,53 +388,105 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *in, void *ou
     }
 }
 
-// ---------------------------------------------------------------- helpers of the autotuner
-// Largest |a - b| and largest |b| over the N valid columns of every output row (bits of the
-// non-negative floats, so an unsigned integer maximum orders them), and the number of elements
-// that are not finite in one buffer only or differ at all for integer outputs.
+// ---------------------------------------------------------------- comparing two results of a plan
+// Two passes and no atomics: block b of the first kernel leaves the largest |a - b|, the
+// largest |b| (both over the N valid columns of its share of the output rows, as the bits of
+// non-negative floats, which order like unsigned integers) and the number of elements that
+// differ in kind in slot b of a partials array; one block of the second kernel folds the slots
+// into the caller's four result words.  Every slot that is read has been written by the same
+// call, so the partials never need clearing.
+constexpr int kCmpThreads = 256;
+constexpr int64_t kCmpPerBlock = 64 * kCmpThreads;   // output elements per block of the first pass
+
 template <typename T>
-__global__ __launch_bounds__(256) void diff_kernel(const T *a, const T *b, int64_t rows, int32_t N, int32_t ld,
-                                                    uint32_t *res) {
+__global__ __launch_bounds__(kCmpThreads) void diff_kernel(const T *a, const T *b, int64_t total, int32_t N, int32_t ld,
+                                                            uint32_t *partials) {
     float dmax = 0.0f, bmax = 0.0f;
     uint32_t bad = 0;
-    const int64_t total = rows * N;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t first = (int64_t)blockIdx.x * kCmpPerBlock, last = min(total, first + kCmpPerBlock);
+    for (int64_t i = first + threadIdx.x; i < last; i += kCmpThreads) {
         const int64_t r = i / N, c = i - r * N;
-        const float x = (float)a[r * ld + c], y = (float)b[r * ld + c];
         if constexpr (std::is_integral<T>::value) {
             bad += a[r * ld + c] != b[r * ld + c];
         } else {
+            const float x = (float)a[r * ld + c], y = (float)b[r * ld + c];
             const bool fx = __builtin_isfinite(x), fy = __builtin_isfinite(y);
             if (fx && fy) { dmax = fmaxf(dmax, fabsf(x - y)); bmax = fmaxf(bmax, fabsf(y)); }
             else if (fx != fy || (__builtin_isnan(x) != __builtin_isnan(y)) || (!__builtin_isnan(x) && x != y)) ++bad;
         }
     }
-    atomicMax(&res[0], __float_as_uint(dmax));
-    atomicMax(&res[1], __float_as_uint(bmax));
-    if (bad) atomicAdd(&res[2], bad);
+    __shared__ uint32_t sd[kCmpThreads], sb[kCmpThreads], sc[kCmpThreads];
+    sd[threadIdx.x] = __float_as_uint(dmax); sb[threadIdx.x] = __float_as_uint(bmax); sc[threadIdx.x] = bad;
+    __syncthreads();
+    for (int w = kCmpThreads / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            sd[threadIdx.x] = max(sd[threadIdx.x], sd[threadIdx.x + w]);
+            sb[threadIdx.x] = max(sb[threadIdx.x], sb[threadIdx.x + w]);
+            sc[threadIdx.x] += sc[threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        partials[4 * (size_t)blockIdx.x + 0] = sd[0];
+        partials[4 * (size_t)blockIdx.x + 1] = sb[0];
+        partials[4 * (size_t)blockIdx.x + 2] = sc[0];
+        partials[4 * (size_t)blockIdx.x + 3] = 0;
+    }
 }
 
-int compare_outputs(const HostPlan &h, const void *a, const void *b, uint32_t *res_dev, void *stream,
-                    float &max_diff, float &max_ref, uint32_t &bad, std::string &err) {
+__global__ __launch_bounds__(kCmpThreads) void fold_kernel(const uint32_t *partials, int32_t n_blocks, uint32_t *result) {
+    uint32_t d = 0, b = 0, c = 0;
+    for (int i = threadIdx.x; i < n_blocks; i += kCmpThreads) {
+        d = max(d, partials[4 * (size_t)i]); b = max(b, partials[4 * (size_t)i + 1]); c += partials[4 * (size_t)i + 2];
+    }
+    __shared__ uint32_t sd[kCmpThreads], sb[kCmpThreads], sc[kCmpThreads];
+    sd[threadIdx.x] = d; sb[threadIdx.x] = b; sc[threadIdx.x] = c;
+    __syncthreads();
+    for (int w = kCmpThreads / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            sd[threadIdx.x] = max(sd[threadIdx.x], sd[threadIdx.x + w]);
+            sb[threadIdx.x] = max(sb[threadIdx.x], sb[threadIdx.x + w]);
+            sc[threadIdx.x] += sc[threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) { result[0] = sd[0]; result[1] = sb[0]; result[2] = sc[0]; result[3] = (uint32_t)n_blocks; }
+}
+
+int64_t compare_blocks(const HostPlan &h) {
+    const int64_t total = (int64_t)h.batch * h.M * h.N;
+    return (total + kCmpPerBlock - 1) / kCmpPerBlock;
+}
+
+int launch_compare(const HostPlan &h, const void *a, const void *b, uint32_t *partials_dev, uint32_t *result_dev,
+                   void *stream, std::string &err) {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    HIP_TRY(hipMemsetAsync(res_dev, 0, 3 * sizeof(uint32_t), s));
-    const int64_t rows = (int64_t)h.batch * h.M;
-    const int32_t ld = h.conv ? h.N : h.ldc;
-    const unsigned grid = (unsigned)std::min<int64_t>(2048, (rows * h.N + 255) / 256);
+    const int64_t total = (int64_t)h.batch * h.M * h.N, blocks = compare_blocks(h);
+    const int32_t ld = h.conv ? h.N : h.ldc;   // the batch's results follow each other at the same pitch
+    if (blocks < 1 || blocks > (1ll << 30)) { err = "output too large to compare"; return SPARSERT_EUNSUPPORTED; }
+    const dim3 grid((unsigned)blocks), wg(kCmpThreads);
     if (h.dtype == SPARSERT_I8)
-        hipLaunchKernelGGL(diff_kernel<int32_t>, dim3(grid), dim3(256), 0, s, (const int32_t *)a, (const int32_t *)b, rows, h.N, ld, res_dev);
+        hipLaunchKernelGGL(diff_kernel<int32_t>, grid, wg, 0, s, (const int32_t *)a, (const int32_t *)b, total, h.N, ld, partials_dev);
     else if (h.dtype == SPARSERT_F16)
-        hipLaunchKernelGGL(diff_kernel<_Float16>, dim3(grid), dim3(256), 0, s, (const _Float16 *)a, (const _Float16 *)b, rows, h.N, ld, res_dev);
+        hipLaunchKernelGGL(diff_kernel<_Float16>, grid, wg, 0, s, (const _Float16 *)a, (const _Float16 *)b, total, h.N, ld, partials_dev);
     else
-        hipLaunchKernelGGL(diff_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)a, (const float *)b, rows, h.N, ld, res_dev);
+        hipLaunchKernelGGL(diff_kernel<float>, grid, wg, 0, s, (const float *)a, (const float *)b, total, h.N, ld, partials_dev);
     HIP_TRY(hipGetLastError());
-    uint32_t host[3] = {0, 0, 0};
-    HIP_TRY(hipMemcpyAsync(host, res_dev, sizeof(host), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    std::memcpy(&max_diff, &host[0], 4);
-    std::memcpy(&max_ref, &host[1], 4);
-    bad = host[2];
+    hipLaunchKernelGGL(fold_kernel, dim3(1), wg, 0, s, partials_dev, (int32_t)blocks, result_dev);
+    HIP_TRY(hipGetLastError());
     return SPARSERT_OK;
+}
+
+// The partials live in memory allocated for this call and released before it returns, which is
+// why this form synchronises the stream.
+int compare_with_own_partials(const HostPlan &h, const void *a, const void *b, uint32_t *result_dev, void *stream, std::string &err) {
+    uint32_t *partials = nullptr;
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(&partials), (size_t)compare_blocks(h) * 4 * sizeof(uint32_t)));
+    int rc = launch_compare(h, a, b, partials, result_dev, stream, err);
+    const hipError_t e1 = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    (void)hipFree(partials);
+    if (rc == SPARSERT_OK && e1 != hipSuccess) { err = std::string("hipStreamSynchronize: ") + hipGetErrorString(e1); rc = SPARSERT_EHIP; }
+    return rc;
 }
 
 // Writes `bytes` of scratch memory: more than the eight L2 caches hold, so whatever a plan left

@@ -102,12 +102,13 @@ int launch_rows(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
                 void *stream, std::string &err);
 int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
                 void *stream, std::string &err);
-// Autotuner helpers (kernels.hip).  compare_outputs: largest |a - b| and |b| over the valid
-// columns of two output buffers of plan `h`, and the count of elements that differ in kind
-// (finite against not finite; any difference for integer outputs); synchronises the stream.
-// res_dev: three device words of scratch.  displace_caches: overwrites `bytes` of scratch memory.
-int compare_outputs(const HostPlan &h, const void *a, const void *b, uint32_t *res_dev, void *stream,
-                    float &max_diff, float &max_ref, uint32_t &bad, std::string &err);
+// Comparison of two results of a plan (kernels.hip).  launch_compare: two kernels on `stream`,
+// partials_dev must hold 4 words per block of compare_blocks(h), result_dev receives 4 words.
+int64_t compare_blocks(const HostPlan &h);
+int launch_compare(const HostPlan &h, const void *a, const void *b, uint32_t *partials_dev, uint32_t *result_dev,
+                   void *stream, std::string &err);
+int compare_with_own_partials(const HostPlan &h, const void *a, const void *b, uint32_t *result_dev, void *stream, std::string &err);
+// Autotuner helper: overwrites `bytes` of scratch memory so that the L2 caches hold nothing of a plan.
 int displace_caches(void *scratch, size_t bytes, void *stream, std::string &err);
 
 }  // namespace sparsert

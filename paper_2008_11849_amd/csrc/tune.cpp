@@ -97,7 +97,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     bench.s = static_cast<hipStream_t>(stream);
     bench.in = in_dev; bench.out = out_dev; bench.conv = b.conv != 0;
     void *ref_out = nullptr;        // what the first candidate wrote: every other candidate is held against it
-    uint32_t *res_dev = nullptr;
+    uint32_t *res_dev = nullptr;    // partial and final words of the output comparison
     struct Cleanup {
         Bench &bn; void *&ref; uint32_t *&res;
         ~Cleanup() {
@@ -113,7 +113,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     bench.scratch_bytes = (size_t)64 << 20;   // twice what the eight 4 MiB L2 caches hold
     if (hipEventCreate(&bench.e0) != hipSuccess || hipEventCreate(&bench.e1) != hipSuccess ||
         hipMalloc(&bench.scratch, bench.scratch_bytes) != hipSuccess || hipMalloc(&ref_out, out_bytes) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void **>(&res_dev), 3 * sizeof(uint32_t)) != hipSuccess) {
+        hipMalloc(reinterpret_cast<void **>(&res_dev), (size_t)(4 * sparsert::compare_blocks(h0) + 4) * sizeof(uint32_t)) != hipSuccess) {
         sparsert_plan_destroy(best);
         return sparsert::set_error(SPARSERT_EHIP, "the tuner could not create its events and scratch buffers");
     }
@@ -168,7 +168,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
                 }
             }
             if (K >= 512) {   // long reduction axis: split it over the waves of a workgroup
-                const int rk[][2] = {{1, 8}, {2, 8}, {4, 8}, {8, 8}, {16, 8}, {24, 8}, {32, 8}, {48, 8}, {64, 8},
+                const int rk[][2] = {{1, 8}, {2, 8}, {4, 8}, {8, 8}, {16, 8}, {24, 8}, {32, 8}, {48, 8}, {64, 8}, {96, 8}, {128, 8},
                                      {1, 4}, {2, 4}, {4, 4}, {8, 4}, {16, 4}, {32, 4}, {48, 4}, {64, 4}, {96, 4},
                                      {64, 2}, {96, 2}};
                 for (auto &c : rk) {
@@ -238,11 +238,16 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
             have_ref = true;
             t.agrees = 1;
         } else {
-            float dmax = 0.0f, rmax = 0.0f;
-            uint32_t bad = 0;
+            uint32_t words[4] = {0, 0, 1, 0};
             std::string err;
-            if (sparsert::compare_outputs(p->host, out_dev, ref_out, res_dev, s, dmax, rmax, bad, err) != SPARSERT_OK) return t;
-            t.agrees = bad == 0 && dmax <= tol * rmax;
+            uint32_t *final_dev = res_dev + 4 * sparsert::compare_blocks(p->host);
+            if (sparsert::launch_compare(p->host, out_dev, ref_out, res_dev, final_dev, s, err) != SPARSERT_OK ||
+                hipMemcpyAsync(words, final_dev, sizeof(words), hipMemcpyDeviceToHost, s) != hipSuccess ||
+                hipStreamSynchronize(s) != hipSuccess) return t;
+            float dmax, rmax;
+            std::memcpy(&dmax, &words[0], 4);
+            std::memcpy(&rmax, &words[1], 4);
+            t.agrees = words[2] == 0 && dmax <= tol * rmax;
             if (!t.agrees) return t;
         }
         t.warm = bench.warm(p);

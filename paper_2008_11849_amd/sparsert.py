@@ -30,7 +30,7 @@ INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", 
               "ldb", "ldc"]
 INFO_COUNT = 48
 
-EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_plan_export",
+EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_compare_outputs", "sparsert_plan_export",
             "sparsert_plan_save", "sparsert_plan_load", "sparsert_plan_destroy", "sparsert_last_error",
             "sparsert_version"]
 
@@ -95,6 +95,8 @@ _lib.sparsert_spmm.argtypes = [_vp, _vp, _vp, _vp]
 _lib.sparsert_spmm.restype = ctypes.c_int
 _lib.sparsert_conv3x3.argtypes = [_vp, _vp, _vp, _vp]
 _lib.sparsert_conv3x3.restype = ctypes.c_int
+_lib.sparsert_compare_outputs.argtypes = [_vp, _vp, _vp, _vp, _vp]
+_lib.sparsert_compare_outputs.restype = ctypes.c_int
 _lib.sparsert_plan_export.argtypes = [_vp, _i32, _vp, ctypes.c_size_t,
                                       ctypes.POINTER(ctypes.c_size_t)]
 _lib.sparsert_plan_export.restype = ctypes.c_int
@@ -245,6 +247,11 @@ def spmm(plan: Plan, B_dev: int, C_dev: int, stream: int = 0):
 def conv3x3(plan: Plan, X_dev: int, Y_dev: int, stream: int = 0):
     """sparsert_conv3x3: device addresses and a hipStream_t as integers."""
     _check(_lib.sparsert_conv3x3(plan.handle, X_dev, Y_dev, stream))
+
+
+def compare_outputs(plan: Plan, a_dev: int, b_dev: int, result_dev: int, stream: int = 0):
+    """sparsert_compare_outputs: result_dev receives four 32-bit words (see the header)."""
+    _check(_lib.sparsert_compare_outputs(plan.handle, a_dev, b_dev, result_dev, stream))
 
 
 # Raw entry points for callers that time launches without Python argument handling.

@@ -11,4 +11,6 @@ bool on_plan_device(const DevicePlan &) { return false; }
 int launch_rows(const HostPlan &, const DevicePlan &, const void *, void *, void *, std::string &err) { err = "host build: no device"; return SPARSERT_EHIP; }
 int launch_spec(const HostPlan &, const DevicePlan &, const void *, void *, void *, std::string &err) { err = "host build: no device"; return SPARSERT_EHIP; }
 
+int compare_with_own_partials(const HostPlan &, const void *, const void *, uint32_t *, void *, std::string &err) { err = "host build: no device"; return SPARSERT_EHIP; }
+
 }  // namespace sparsert
