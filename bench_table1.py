@@ -54,6 +54,15 @@ def graph_us(torch, fn, replays=20):
     return e0.elapsed_time(e1) * 1e3 / (replays * INNER)
 
 
+def dense_gemm_candidates(torch, Ad, B):
+    """Dense baselines of the same product, all on operands prepared ahead of time (the paper took
+    the vendor library's best algorithm with the weight stored transposed, Section 4): A @ B,
+    the transposed product B^T @ A^T, and A kept column-major.  The fastest one is the baseline."""
+    At, Bt = Ad.t().contiguous(), B.t().contiguous()
+    return {"A@B": lambda: torch.matmul(Ad, B), "(B^T@A^T)": lambda: torch.matmul(Bt, At),
+            "A(col-major)@B": lambda: torch.matmul(At.t(), B)}
+
+
 def geomean(xs):
     return math.exp(sum(math.log(x) for x in xs) / len(xs)) if xs else None
 
@@ -173,19 +182,23 @@ def main():
                 extra[key] = round(t_abl, 3)
         use_auto = args.sweep and (args.plans == "auto" or (args.plans == "mixed" and csr.nnz > 150000))
         plan, t_sparse, err = tuned(auto=use_auto)
-        try:
-            t_dense, dense_how = graph_us(torch, dense_fn), "graph"
-        except Exception:  # a library call that cannot be captured: plain event loop instead
-            torch.cuda.synchronize()
-            for _ in range(5):
-                dense_fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(100):
-                dense_fn()
-            e1.record()
-            torch.cuda.synchronize()
-            t_dense, dense_how = e0.elapsed_time(e1) * 10.0, "event loop"
+        t_dense, dense_how = None, None
+        for name, fn_d in (dense_fn.items() if isinstance(dense_fn, dict) else [("library call", dense_fn)]):
+            try:
+                t, how = graph_us(torch, fn_d), "graph"
+            except Exception:  # a library call that cannot be captured: plain event loop instead
+                torch.cuda.synchronize()
+                for _ in range(5):
+                    fn_d()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(100):
+                    fn_d()
+                e1.record()
+                torch.cuda.synchronize()
+                t, how = e0.elapsed_time(e1) * 10.0, "event loop"
+            if t_dense is None or t < t_dense:
+                t_dense, dense_how = t, f"{how}, {name}"
         info = plan.info()
         plan.destroy()
         return {"tag": tag, "sparse_us": round(t_sparse, 3), "dense_us": round(t_dense, 3),
@@ -204,7 +217,7 @@ def main():
         B = torch.from_numpy(case.B).to(dev)
         C = torch.empty((M, N), dtype=tdt, device=dev)
         Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
-        r = run(tag, case, B, C, lambda: torch.matmul(Ad, B))
+        r = run(tag, case, B, C, dense_gemm_candidates(torch, Ad, B))
         r.update(M=M, K=K, N=N, sparsity=sparsity, paper_speedup_t4=PAPER_T1[sparsity][i])
         rows.append(r)
         print(json.dumps(r), file=sys.stderr, flush=True)
@@ -238,7 +251,7 @@ def main():
                     B = torch.from_numpy(case.B).to(dev)
                     C = torch.empty((M, N), dtype=tdt, device=dev)
                     Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
-                    r = run(tag, case, B, C, lambda: torch.matmul(Ad, B))
+                    r = run(tag, case, B, C, dense_gemm_candidates(torch, Ad, B))
                     r.update(M=M, K=K, N=N, sparsity=sparsity, paper_speedup_t4="-")
                     rows.append(r)
                     print(json.dumps(r), file=sys.stderr, flush=True)
@@ -256,7 +269,7 @@ def main():
             B = torch.from_numpy(case.B).to(dev)
             C = torch.empty((M, N), dtype=tdt, device=dev)
             Ad = torch.from_numpy(csr.todense(np.float32)).to(dev).to(tdt)
-            r = run(tag, case, B, C, lambda: torch.matmul(Ad, B))
+            r = run(tag, case, B, C, dense_gemm_candidates(torch, Ad, B))
             r.update(M=M, K=K, N=N, sparsity=0.95, paper_speedup_t4="-", skewed=True)
             rows.append(r)
             print(json.dumps(r), file=sys.stderr, flush=True)
