@@ -499,7 +499,13 @@ def main():
                           "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
                                                           "spec_tiles", "spec_ksplit", "spec_swizzle", "spec_vec",
                                                           "spec_code_bytes")},
-                          "tuned_candidates": len(L.tuned) if L.tuned else 0})
+                          "tuned_candidates": len(L.tuned) if L.tuned else 0,
+                          # the tuner's six fastest candidates (ranked with displaced caches), for the record
+                          "tuned_top": sorted(({k: (round(v, 2) if isinstance(v, float) else v) for k, v in e.items()
+                                                if k in ("kernel", "vec", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit",
+                                                         "spec_swizzle", "spec_vec", "microseconds", "cold_microseconds", "agrees")}
+                                               for e in (L.tuned or []) if e["cold_microseconds"] > 0),
+                                              key=lambda e: e["cold_microseconds"])[:6]})
     # ---- every layer's launch duration inside the step.  The HIP events around the timed region
     # give the time of a whole step (kernels and the gaps between them); it is apportioned to the
     # layers in the ratio of their back-to-back durations.  (Event pairs around single launches
