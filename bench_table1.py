@@ -182,6 +182,16 @@ def main():
                 extra[key] = round(t_abl, 3)
         use_auto = args.sweep and (args.plans == "auto" or (args.plans == "mixed" and csr.nnz > 150000))
         plan, t_sparse, err = tuned(auto=use_auto)
+        plan_from = "inspect defaults" if use_auto else "sparsert_tune"
+        if use_auto and args.plans == "mixed" and plan.info()["kernel"] != sp.KERNEL_SPEC and csr.nnz <= (4 << 20):
+            # beyond 524288 nonzeros the inspector hands out the row-walk kernel unless asked; the
+            # generated kernel with its defaults (one assembling run, no timing runs) is tried as well
+            p2, t2, e2 = tuned(untuned=True, what="generated, defaults")
+            if t2 < t_sparse:
+                plan.destroy()
+                plan, t_sparse, err, plan_from = p2, t2, e2, "inspect, kernel = generated"
+            else:
+                p2.destroy()
         t_dense, dense_how = None, None
         for name, fn_d in (dense_fn.items() if isinstance(dense_fn, dict) else [("library call", dense_fn)]):
             try:
@@ -205,7 +215,7 @@ def main():
                 "speedup": round(t_dense / t_sparse, 3), "dense_timing": dense_how,
                 "gflops": round(2.0 * csr.nnz * N * max(1, batch) / t_sparse / 1e3, 1),
                 "oracle_componentwise_error": err, "oracle_rows_checked": "all" if oracle[0] is None else len(oracle[0]),
-                "plan_from": "inspect defaults" if use_auto else "sparsert_tune",
+                "plan_from": plan_from,
                 "plan": {k: info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit", "spec_swizzle", "spec_vec")},
                 **extra}
 
@@ -313,7 +323,7 @@ def write_sweep_markdown(path, res, command):
              "Benchmark table (not a rocprofv3 summary), builder-run.  Outputs checked against the oracle: yes - "
              f"{oc['timed_plans_checked']} timed plans, every element (64 sampled rows for the largest cases), "
              f"worst componentwise error {oc['worst_componentwise_error']:.2e} against {oc['tolerance']:g}.", "",
-             f"command: `{command}` (one MI355X; `plan`: tune = sparsert_tune, auto = sparsert_inspect without options;",
+             f"command: `{command}` (one MI355X; `plan`: tune = sparsert_tune, auto = sparsert_inspect without options, gen = sparsert_inspect with kernel = generated and nothing else;",
              f"sparse and dense both timed as {INNER} launches per HIP graph, 20 replays, HIP events; effective GFLOP/s = 2 nnz N / t).", "",
              "| M | K | N | sparsity | sparse us | dense us | speedup | effective GFLOP/s | kernel | R | KS | swizzle | plan | oracle err |",
              "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
@@ -321,7 +331,7 @@ def write_sweep_markdown(path, res, command):
         p = r["plan"]
         lines.append(f"| {r['M']} | {r['K']} | {r['N']} | {r['sparsity']:.2f} | {r['sparse_us']:.2f} | {r['dense_us']:.2f} | "
                      f"{r['speedup']:.2f} | {r['gflops']:.0f} | {p['kernel']} | {p['spec_rows']} | {p['spec_ksplit']} | "
-                     f"{p['spec_swizzle']} | {'auto' if r['plan_from'].startswith('inspect') else 'tune'} | {r['oracle_componentwise_error']:.1e} |")
+                     f"{p['spec_swizzle']} | {'tune' if r['plan_from'] == 'sparsert_tune' else 'auto' if r['plan_from'] == 'inspect defaults' else 'gen'} | {r['oracle_componentwise_error']:.1e} |")
     with open(path, "w") as f:
         f.write("\n".join(lines) + "\n")
 
