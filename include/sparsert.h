@@ -252,6 +252,20 @@ int sparsert_tune(const int32_t *row_ptr, const int32_t *col_idx, const void *va
 int sparsert_compare_outputs(const sparsert_plan *plan, const void *a_dev, const void *b_dev,
                              void *result_dev, void *stream);
 
+/*
+ * sparsert_compare_outputs for callers that cannot allocate device memory: code under HIP graph
+ * capture, serving loops and harnesses that forbid hipMalloc.  Same arguments and result words;
+ * the partial results live in a static device array of the library (32 KiB on every GPU the
+ * library runs on, held until the process ends) instead of memory allocated for the call.
+ * Allocates nothing, does not synchronise: two kernels on `stream`.
+ * Limit: outputs of at most 33 554 432 elements (batch * M * N); larger ones give EUNSUPPORTED.
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+ * host threads) race and may return each other's figures; calls on one stream are ordered.
+ * Nothing has to be cleared between calls: a call reads only the slots it has written itself.
+ */
+int sparsert_compare_outputs_static(const sparsert_plan *plan, const void *a_dev, const void *b_dev,
+                                    void *result_dev, void *stream);
+
 /* Arrays of the plan that sparsert_plan_export can copy out (HOST side). */
 typedef enum sparsert_field {
     SPARSERT_FIELD_INFO = 0,      /* int32[SPARSERT_INFO_COUNT], see below */

@@ -169,6 +169,22 @@ int sparsert_compare_outputs(const sparsert_plan *plan, const void *a_dev, const
     return rc == SPARSERT_OK ? rc : fail(rc, err);
 }
 
+int sparsert_compare_outputs_static(const sparsert_plan *plan, const void *a_dev, const void *b_dev, void *result_dev, void *stream) {
+    if (!plan) return fail(SPARSERT_EINVAL, "plan is NULL");
+    if (!a_dev || !b_dev || !result_dev) return fail(SPARSERT_EINVAL, "device pointer is NULL");
+    if (((uintptr_t)a_dev | (uintptr_t)b_dev | (uintptr_t)result_dev) & 15u) return fail(SPARSERT_EINVAL, "device pointers must be 16-byte aligned");
+    if (!plan->on_device) return fail(SPARSERT_EINVAL, "plan was made with host_only");
+    if (!sparsert::on_plan_device(plan->dev)) return fail(SPARSERT_EINVAL, "the plan's arrays live on another HIP device than the current one");
+    const sparsert::HostPlan &h = plan->host;
+    if ((int64_t)h.batch * h.M * h.N > sparsert::static_compare_max_elements())
+        return fail(SPARSERT_EUNSUPPORTED, "output has more than 33554432 elements: beyond the static partials array, use sparsert_compare_outputs");
+    std::string err;
+    uint32_t *partials = nullptr;
+    int rc = sparsert::static_compare_scratch(&partials, err);
+    if (rc == SPARSERT_OK) rc = sparsert::launch_compare(h, a_dev, b_dev, partials, static_cast<uint32_t *>(result_dev), stream, err);
+    return rc == SPARSERT_OK ? rc : fail(rc, err);
+}
+
 void sparsert_plan_destroy(sparsert_plan *plan) {
     if (!plan) return;
     sparsert::free_device_plan(plan->dev);

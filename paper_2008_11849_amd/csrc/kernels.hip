@@ -477,6 +477,31 @@ int launch_compare(const HostPlan &h, const void *a, const void *b, uint32_t *pa
     return SPARSERT_OK;
 }
 
+// The variant for callers that cannot allocate keeps its partials in this array: one copy per
+// GPU, held until the process ends.  On the host the array's name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returns for the current device.
+constexpr int kStaticCmpBlocks = 2048;   // 2048 x 16384 = 33 554 432 output elements
+static __device__ __align__(256) uint32_t scratch[4 * kStaticCmpBlocks];
+
+int64_t static_compare_max_elements() { return (int64_t)kStaticCmpBlocks * kCmpPerBlock; }
+
+int static_compare_scratch(uint32_t **out, std::string &err) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static uint32_t *per_device[kMaxDevices] = {nullptr};
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { err = "device ordinal out of range"; return SPARSERT_EUNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        per_device[dev] = static_cast<uint32_t *>(ptr);
+    }
+    *out = per_device[dev];
+    return SPARSERT_OK;
+}
+
 // The partials live in memory allocated for this call and released before it returns, which is
 // why this form synchronises the stream.
 int compare_with_own_partials(const HostPlan &h, const void *a, const void *b, uint32_t *result_dev, void *stream, std::string &err) {

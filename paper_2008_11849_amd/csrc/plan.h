@@ -108,6 +108,10 @@ int64_t compare_blocks(const HostPlan &h);
 int launch_compare(const HostPlan &h, const void *a, const void *b, uint32_t *partials_dev, uint32_t *result_dev,
                    void *stream, std::string &err);
 int compare_with_own_partials(const HostPlan &h, const void *a, const void *b, uint32_t *result_dev, void *stream, std::string &err);
+// The library's static partials array: its address on the current device (looked up once per
+// device) and the number of output elements it covers.
+int static_compare_scratch(uint32_t **out, std::string &err);
+int64_t static_compare_max_elements();
 // Autotuner helper: overwrites `bytes` of scratch memory so that the L2 caches hold nothing of a plan.
 int displace_caches(void *scratch, size_t bytes, void *stream, std::string &err);
 

@@ -30,7 +30,7 @@ INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", 
               "ldb", "ldc"]
 INFO_COUNT = 48
 
-EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_compare_outputs", "sparsert_plan_export",
+EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_compare_outputs", "sparsert_compare_outputs_static", "sparsert_plan_export",
             "sparsert_plan_save", "sparsert_plan_load", "sparsert_plan_destroy", "sparsert_last_error",
             "sparsert_version"]
 
@@ -97,6 +97,8 @@ _lib.sparsert_conv3x3.argtypes = [_vp, _vp, _vp, _vp]
 _lib.sparsert_conv3x3.restype = ctypes.c_int
 _lib.sparsert_compare_outputs.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.sparsert_compare_outputs.restype = ctypes.c_int
+_lib.sparsert_compare_outputs_static.argtypes = [_vp, _vp, _vp, _vp, _vp]
+_lib.sparsert_compare_outputs_static.restype = ctypes.c_int
 _lib.sparsert_plan_export.argtypes = [_vp, _i32, _vp, ctypes.c_size_t,
                                       ctypes.POINTER(ctypes.c_size_t)]
 _lib.sparsert_plan_export.restype = ctypes.c_int
@@ -252,6 +254,11 @@ def conv3x3(plan: Plan, X_dev: int, Y_dev: int, stream: int = 0):
 def compare_outputs(plan: Plan, a_dev: int, b_dev: int, result_dev: int, stream: int = 0):
     """sparsert_compare_outputs: result_dev receives four 32-bit words (see the header)."""
     _check(_lib.sparsert_compare_outputs(plan.handle, a_dev, b_dev, result_dev, stream))
+
+
+def compare_outputs_static(plan: Plan, a_dev: int, b_dev: int, result_dev: int, stream: int = 0):
+    """sparsert_compare_outputs_static: the same comparison without any allocation (static scratch, no synchronisation)."""
+    _check(_lib.sparsert_compare_outputs_static(plan.handle, a_dev, b_dev, result_dev, stream))
 
 
 # Raw entry points for callers that time launches without Python argument handling.
