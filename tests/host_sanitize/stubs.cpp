@@ -13,4 +13,8 @@ int launch_spec(const HostPlan &, const DevicePlan &, const void *, void *, void
 
 int compare_with_own_partials(const HostPlan &, const void *, const void *, uint32_t *, void *, std::string &err) { err = "host build: no device"; return SPARSERT_EHIP; }
 
+int launch_compare(const HostPlan &, const void *, const void *, uint32_t *, uint32_t *, void *, std::string &err) { err = "host build: no device"; return SPARSERT_EHIP; }
+int static_compare_scratch(uint32_t **, std::string &err) { err = "host build: no device"; return SPARSERT_EHIP; }
+int64_t static_compare_max_elements() { return 0; }
+
 }  // namespace sparsert
