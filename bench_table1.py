@@ -184,8 +184,8 @@ def main():
         plan, t_sparse, err = tuned(auto=use_auto)
         plan_from = "inspect defaults" if use_auto else "sparsert_tune"
         if use_auto and args.plans == "mixed" and plan.info()["kernel"] != sp.KERNEL_SPEC and csr.nnz <= (4 << 20):
-            # beyond 524288 nonzeros the inspector hands out the row-walk kernel unless asked; the
-            # generated kernel with its defaults (one assembling run, no timing runs) is tried as well
+            # where the inspector hands out the row-walk kernel (more than 4194304 nonzeros, or no code
+            # object manager), the generated kernel with its defaults is tried as well
             p2, t2, e2 = tuned(untuned=True, what="generated, defaults")
             if t2 < t_sparse:
                 plan.destroy()

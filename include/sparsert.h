@@ -54,7 +54,7 @@ typedef enum sparsert_dtype { SPARSERT_F32 = 0, SPARSERT_F16 = 1, SPARSERT_I8 = 
 typedef enum sparsert_kernel {
     SPARSERT_KERNEL_AUTO = 0,  /* the inspector chooses: the generated kernel with its shape-dependent
                                   defaults when the code object manager (libamd_comgr) can be loaded, A has
-                                  at most 524288 nonzeros (a few seconds of assembling; the inspector is off
+                                  at most 4194304 nonzeros (about 4 s of assembling per million; the inspector is off
                                   the latency path, Section 2.3) and neither vec nor split_threshold is set;
                                   the row-walk kernel otherwise, and also when the generator declines the
                                   problem (EUNSUPPORTED / ECOMPILE) */

@@ -26,7 +26,7 @@ Specification
                 stably reordered by tap; conv_seg[slot] holds the ten stream positions where
                 the taps start/end
   kernel      = executor family when the caller leaves the choice to the inspector: 2 (per-matrix
-                generated code) if nnz <= 524288 and neither vec nor split_threshold is given,
+                generated code) if nnz <= 4194304 and neither vec nor split_threshold is given,
                 else 1 (row-walk).  (Stated for a process that can load the code object manager.)
 """
 from __future__ import annotations
@@ -36,7 +36,7 @@ import numpy as np
 GY = 4
 WAVE = 64
 FULL_TASKS = 2048
-AUTO_SPEC_NNZ = 512 * 1024
+AUTO_SPEC_NNZ = 4 * 1024 * 1024
 
 
 def _bin(x: np.ndarray) -> np.ndarray:

@@ -13,7 +13,7 @@ constexpr int kWave = 64;       // lanes per wavefront on gfx950
 constexpr int kGy = 4;          // waves per workgroup (one per SIMD of a CU)
 constexpr int kBins = 33;       // bin(0)=0, bin(x)=1+floor(log2 x), x < 2^31
 constexpr int kFullTasks = 2048;  // wave tasks wanted before widening per-lane vectors
-constexpr int32_t kAutoSpecNnz = 512 << 10;   // SPARSERT_KERNEL_AUTO generates code up to this many nonzeros (about 6 s of assembling)
+constexpr int32_t kAutoSpecNnz = 4 << 20;   // SPARSERT_KERNEL_AUTO generates code up to this many nonzeros (about 4 s of assembling per million)
 
 // Per-matrix generated kernel (kernel == SPARSERT_KERNEL_SPEC).
 // IEEE binary16 -> binary32, exact for every input (subnormals, inf, NaN payload kept).
@@ -89,6 +89,12 @@ int build_host_plan(const int32_t *row_ptr, const int32_t *col_idx, const void *
 
 // Generated-kernel path (specialize.cpp): fills h.spec, including the assembled code object.
 int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err);
+// Rows per code block, among lo..hi, for which the busiest compute unit has the least work on a
+// large launch: workgroups(R) = ceil(ceil(M / R) / groups_per_wg) * wg_columns are dealt to 256
+// compute units, a workgroup's work grows with R, so the cost is ceil(workgroups / 256) * R;
+// ties go to the larger R (fewer fetches of B).  Only counts that leave no compute unit without a
+// workgroup are considered; if there is none, lo is returned.
+int rows_for_whole_rounds(int32_t M, int groups_per_wg, int64_t wg_columns, int lo, int hi);
 bool spec_available();   // can generated kernels be assembled in this process (is the code object manager loadable)?
 
 // Records the thread-local error message behind sparsert_last_error (api.cpp); returns `code`.

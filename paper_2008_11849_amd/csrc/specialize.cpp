@@ -31,6 +31,7 @@
 // All global addresses are "descriptor base + row offset literal + lane column offset"
 // with the column clamped to the tile, so every access is in bounds by construction.
 #include <algorithm>
+#include <climits>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -653,6 +654,22 @@ struct Gen {
 }  // namespace
 
 bool spec_available() { return comgr().ok; }
+
+int rows_for_whole_rounds(int32_t M, int groups_per_wg, int64_t wg_columns, int lo, int hi) {
+    constexpr int64_t kComputeUnits = 256;
+    lo = std::max(1, std::min<int>(lo, M));
+    hi = std::max(lo, std::min<int>(hi, M));
+    int best = -1;
+    int64_t best_cost = INT64_MAX;
+    for (int r = lo; r <= hi; ++r) {
+        const int64_t groups = ((int64_t)M + r - 1) / r;
+        const int64_t wgs = (groups + groups_per_wg - 1) / groups_per_wg * wg_columns;
+        if (wgs < kComputeUnits) continue;   // the model holds while every compute unit has a workgroup
+        const int64_t cost = (wgs + kComputeUnits - 1) / kComputeUnits * r;
+        if (cost < best_cost || (cost == best_cost && r > best)) { best = r; best_cost = cost; }
+    }
+    return best > 0 ? best : lo;   // too small a launch for any count in range: the most workgroups
+}
 
 // What the stages below hand to each other besides the SpecPlan itself.
 struct Shape {

@@ -94,7 +94,7 @@ def _rows_sample(csr, rows):
 @pytest.mark.parametrize("M,K,N,sparsity,kind,dtype", SAMPLE,
                          ids=[f"{m}x{k}x{n}_{int(s * 100)}_{kind}_{np.dtype(dt).name}" for m, k, n, s, kind, dt in SAMPLE])
 def test_sweep_sample(M, K, N, sparsity, kind, dtype):
-    """The plan a caller gets without options (the generated kernel up to 524288 nonzeros, the
+    """The plan a caller gets without options (the generated kernel up to 4194304 nonzeros, the
     row-walk kernel beyond) and, for the smaller matrices, the tuned plan."""
     case = synth.sweep_case(M, K, N, sparsity, kind, dtype)
     csr = case.csr
@@ -107,7 +107,7 @@ def test_sweep_sample(M, K, N, sparsity, kind, dtype):
         sub_ptr, cols, vals = _rows_sample(csr, rows)
         Cref, S = ref.spmm(len(rows), K, N, sub_ptr, cols, vals, case.B)
     got, info = run_spmm(csr, case.B)
-    assert info["kernel"] == (sp.KERNEL_SPEC if csr.nnz <= 524288 else sp.KERNEL_ROWS)
+    assert info["kernel"] == (sp.KERNEL_SPEC if csr.nnz <= 4194304 else sp.KERNEL_ROWS)
     check(got[rows], Cref, S, dtype)
     if csr.nnz <= 120000:
         got, info, entries = _tuned_run(case, dtype)
