@@ -122,7 +122,12 @@ typedef struct sparsert_options {
     int32_t tune_warm;       /* sparsert_tune only.  0: candidates are ranked by their time when every launch
                                 finds its code and operands displaced from the L2 caches, as inside a model
                                 where other layers run in between; 1: by back-to-back launches of the same plan */
-    int32_t reserved[3];     /* must be zero */
+    int32_t spec_prefetch;   /* SPARSERT_KERNEL_SPEC: 1 = every wave touches the code of its block with a few
+                                loads before it runs into it, so that the L2 misses of straight-line code
+                                that other layers have displaced overlap instead of following each other
+                                (costs about 0.5 us when the code is still in the L2, gains more than that
+                                when it is not; the tuner tries it on its winner); 0 = off */
+    int32_t reserved[2];     /* must be zero */
 } sparsert_options;
 
 /*
@@ -221,6 +226,7 @@ typedef struct sparsert_tune_entry {
     int32_t agrees;          /* 1: the candidate's output matches the first candidate's within the storage type's
                                 tolerance (bit for bit for int8 plans); 0: it does not, and the candidate was
                                 not considered */
+    int32_t spec_prefetch;   /* SPEC plans: 1 if the waves prefetch the code of their block */
 } sparsert_tune_entry;
 typedef struct sparsert_tune_report {
     int32_t count;
@@ -324,6 +330,7 @@ enum {
     SPARSERT_INFO_SPEC_VEC,       /* SPEC plans: columns per lane */
     SPARSERT_INFO_LDB,            /* elements between consecutive rows of B (N unless options.ldb) */
     SPARSERT_INFO_LDC,            /* elements between consecutive rows of C (N unless options.ldc) */
+    SPARSERT_INFO_SPEC_PREFETCH,  /* SPEC plans: 128-byte lines of its block's code every lane touches ahead (0 = no prefetch) */
     SPARSERT_INFO_COUNT = 48      /* remaining entries are zero */
 };
 

@@ -121,6 +121,7 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
         info[SPARSERT_INFO_BATCH] = h.batch;
         info[SPARSERT_INFO_SPEC_VEC] = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.vec : 0;
         info[SPARSERT_INFO_LDB] = h.ldb; info[SPARSERT_INFO_LDC] = h.ldc;
+        info[SPARSERT_INFO_SPEC_PREFETCH] = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.prefetch_lines : 0;
         info[SPARSERT_INFO_SPEC_LANES] = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.lanes_per_tile : 0;
         info[SPARSERT_INFO_SPEC_SWIZZLE] = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.swizzle : 0;
         src = info; bytes = sizeof(info);

@@ -26,7 +26,8 @@ static int validate(const int32_t *row_ptr, const int32_t *col_idx, const void *
     if (opt.spec_lanes != 0 && opt.spec_lanes != 16 && opt.spec_lanes != 32 && opt.spec_lanes != 64) { err = "spec_lanes must be 0,16,32,64"; return SPARSERT_EINVAL; }
     if (opt.spec_swizzle != 0 && opt.spec_swizzle != 1) { err = "spec_swizzle must be 0 or 1"; return SPARSERT_EINVAL; }
     if (opt.spec_vec != 0 && opt.spec_vec != 1 && opt.spec_vec != 2 && opt.spec_vec != 4) { err = "spec_vec must be 0,1,2,4"; return SPARSERT_EINVAL; }
-    for (int i = 0; i < 3; ++i)
+    if (opt.spec_prefetch != 0 && opt.spec_prefetch != 1) { err = "spec_prefetch must be 0 or 1"; return SPARSERT_EINVAL; }
+    for (int i = 0; i < 2; ++i)
         if (opt.reserved[i] != 0) { err = "reserved option fields must be zero"; return SPARSERT_EINVAL; }
     if (row_ptr[0] != 0) { err = "row_ptr[0] must be 0"; return SPARSERT_EINVAL; }
     for (int32_t m = 0; m < M; ++m)

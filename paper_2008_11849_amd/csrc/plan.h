@@ -43,6 +43,7 @@ struct SpecPlan {
     int32_t n_blocks = 0;       // code blocks (n_groups, padded to a multiple of the waves in LDS mode)
     int32_t lds_bytes = 0;
     int32_t ksplit = 1;         // DIRECT: waves of a workgroup that split the K range of one block
+    int32_t prefetch_lines = 0; // 128-byte lines of its block's code every lane touches before the block runs
     int64_t asm_bytes = 0;
     std::vector<int32_t> group_of_slot;   // [M]
     std::vector<int32_t> group_columns;   // [n_groups] B rows each group loads per column tile

@@ -14,7 +14,7 @@
 namespace {
 
 constexpr uint32_t kMagic = 0x54525053u;   // "SPRT"
-constexpr uint32_t kFormat = 2;   // bumped whenever the field list below changes
+constexpr uint32_t kFormat = 3;   // bumped whenever the field list below changes
 
 struct Writer {
     std::vector<uint8_t> out;
@@ -62,7 +62,7 @@ template <typename IO> void scalars(IO &io, sparsert::HostPlan &h) {
                     &h.natural_order, &h.batch, &h.ldb, &h.ldc,
                     &h.spec.rows_per_group, &h.spec.n_groups, &h.spec.depth, &h.spec.n_tiles, &h.spec.lanes_per_tile,
                     &h.spec.tiles_per_wg, &h.spec.swizzle, &h.spec.vec, &h.spec.mode, &h.spec.n_blocks,
-                    &h.spec.lds_bytes, &h.spec.ksplit};
+                    &h.spec.lds_bytes, &h.spec.ksplit, &h.spec.prefetch_lines};
     for (int32_t *x : f) field(io, *x);
 }
 

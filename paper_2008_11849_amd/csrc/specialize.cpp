@@ -183,6 +183,7 @@ int assemble(const std::string &text, std::vector<char> &code, std::string &err)
 // ---------------------------------------------------------------- assembly text
 struct Emitter {
     std::string s;
+    int64_t lines = 0;
     char buf[256];
     void line(const char *fmt, ...) __attribute__((format(printf, 2, 3))) {
         va_list ap;
@@ -191,6 +192,7 @@ struct Emitter {
         va_end(ap);
         s.append(buf, (size_t)n);
         s.push_back('\n');
+        ++lines;
     }
 };
 
@@ -203,7 +205,8 @@ constexpr int kSgprOffRing = 24, kOffRing = 8; // s[24:31] row-offset literals i
 constexpr int kSgprTap0 = 32;                  // conv: s[32:49] = lane masks of the 9 filter taps
 constexpr int kSgprFull = 50;                  // conv: s[50:51] = all lanes
 constexpr int kSgprImage = 52;                 // batch > 1: workgroup id z = image / matrix of the batch
-constexpr int kSgprJump = 53;                  // offset of the block's code from the table
+constexpr int kSgprJump = 53;                  // byte offset of the block's entry in the table
+constexpr int kSgprEntry = 54;                 // prologue only, s[54:55]: the block's table entry and the next one's (offsets of their code from the table)
 constexpr int kSgprValRing = 54, kValRing = 8; // half / int8 plans: s[54:61] values of A on their way into the multiply-add
 constexpr int kSgprTab = 62, kTab = 32;        // DIRECT: s[62:93] = i * (bytes between consecutive operand rows), i < 32
 constexpr int kNextFreeSgpr = 94;
@@ -848,6 +851,11 @@ static int plan_registers(const HostPlan &h, SpecPlan &sp, const Shape &sh, cons
         }
     }
     if (gen.n_vgpr > 256) { err = "spec_rows too large for the register file"; return SPARSERT_EINVAL; }
+    // The symbol carries the problem shape so that kernel traces tell the plans of a model apart.
+    char sym[96];
+    snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d%s", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N,
+             half ? (V == 2 ? "_f16x2" : "_f16") : int8 ? (V == 4 ? "_i8x4" : "_i8") : "");
+    sp.symbol = sym;
     sp.lds_bytes = gen.lds_bytes;
 
     return SPARSERT_OK;
@@ -855,11 +863,10 @@ static int plan_registers(const HostPlan &h, SpecPlan &sp, const Shape &sh, cons
 
 // Stage 4a, emission of everything before the blocks: directives, the prologue that turns the
 // workgroup and lane ids into a block, a column and two buffer descriptors, and the jump table.
-static void emit_prologue(Gen &gen, const Shape &sh, const Extents &ex) {
+static void emit_prologue(Gen &gen, Emitter &e, const Shape &sh, const Extents &ex, int prefetch_lines) {
     const HostPlan &h = gen.h;
     SpecPlan &sp = gen.sp;
-    Emitter &e = gen.e;
-    const bool half = gen.half, int8 = gen.int8, lds = sh.lds;
+    const bool lds = sh.lds;
     const int esz = gen.esz, osz = gen.osz, V = sh.V, KS = sh.KS, wshift = sh.wshift, nvc = sh.nvc, n_blocks = sp.n_blocks;
     const int32_t M = h.M, N = h.N;
     const int64_t b_bytes = ex.b_bytes, c_bytes = ex.c_bytes;
@@ -867,11 +874,7 @@ static void emit_prologue(Gen &gen, const Shape &sh, const Extents &ex) {
     e.line("\t.amdgcn_target \"amdgcn-amd-amdhsa--gfx950\"");
     e.line("\t.amdhsa_code_object_version 6");
     e.line("\t.text");
-    // The symbol carries the problem shape so that kernel traces tell the plans of a model apart.
-    char sym[96];
-    snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d%s", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N,
-             half ? (V == 2 ? "_f16x2" : "_f16") : int8 ? (V == 4 ? "_i8x4" : "_i8") : "");
-    sp.symbol = sym;
+    const char *sym = sp.symbol.c_str();
     e.line("\t.protected\t%s", sym);
     e.line("\t.globl\t%s", sym);
     e.line("\t.p2align\t8");
@@ -914,7 +917,8 @@ static void emit_prologue(Gen &gen, const Shape &sh, const Extents &ex) {
     e.line("\ts_add_u32 s%d, s%d, .Ltable-.Lpc", kSgprPc, kSgprPc);
     e.line("\ts_addc_u32 s%d, s%d, 0", kSgprPc + 1, kSgprPc + 1);
     e.line("\ts_lshl_b32 s%d, s%d, 2", kSgprJump, kSgprBlock);
-    e.line("\ts_load_dword s%d, s[%d:%d], s%d", kSgprJump, kSgprPc, kSgprPc + 1, kSgprJump);
+    // this block's entry and the next one's: where the code starts and how long it is
+    e.line("\ts_load_dwordx2 s[%d:%d], s[%d:%d], s%d", kSgprEntry, kSgprEntry + 1, kSgprPc, kSgprPc + 1, kSgprJump);
     e.line("\ts_mul_i32 s%d, s%d, %d", kSgprTmp, kSgprTile, sp.lanes_per_tile);  // first column of the tile
     e.line("\tv_add_u32_e32 v%d, s%d, v%d", kVgprT1, kSgprTmp, kVgprOff);        // this lane's column
     e.line("\ts_mov_b32 s%d, %d", kSgprTmp2, nvc);
@@ -991,14 +995,36 @@ static void emit_prologue(Gen &gen, const Shape &sh, const Extents &ex) {
     e.line("\ts_mov_b32 s%d, 0x%llx", kRsrcC + 2, (unsigned long long)c_bytes);
     e.line("\ts_mov_b32 s%d, 0x%x", kRsrcC + 3, kRsrcWord3);
     // jump to the code of this block (the table entry arrived with the kernel arguments)
-    e.line("\ts_add_u32 s%d, s%d, s%d", kSgprPc, kSgprPc, kSgprJump);
+    e.line("\ts_add_u32 s%d, s%d, s%d", kSgprPc, kSgprPc, kSgprEntry);
     e.line("\ts_addc_u32 s%d, s%d, 0", kSgprPc + 1, kSgprPc + 1);
+    if (prefetch_lines > 0) {
+        // The block's code is straight-line and read once, so inside a model, where other layers
+        // have displaced it from the L2 cache, the wave would take one L2 miss after the other
+        // while it runs.  Instead every lane touches `prefetch_lines` 128-byte lines of the block
+        // right now, with ordinary loads whose result is never used (lanes past the end of the
+        // block are masked off, so nothing outside this block's code is read): the misses overlap
+        // each other and the first fetches of B.  The destination register is one no block uses.
+        const int stride = 128 * prefetch_lines;
+        e.line("\ts_sub_u32 s%d, s%d, s%d", kSgprEntry + 1, kSgprEntry + 1, kSgprEntry);   // bytes of code in this block
+        e.line("\ts_mov_b64 exec, -1");
+        e.line("\tv_mbcnt_lo_u32_b32 v%d, -1, 0", kVgprAcc0);
+        e.line("\tv_mbcnt_hi_u32_b32 v%d, -1, v%d", kVgprAcc0, kVgprAcc0);              // lane id
+        e.line("\tv_mul_u32_u24_e32 v%d, 0x%x, v%d", kVgprAcc0, stride, kVgprAcc0);    // first byte this lane touches
+        for (int j = 0; j < prefetch_lines; ++j) {
+            // lanes whose line starts inside the block stay active (the set only shrinks with j)
+            e.line("\tv_cmpx_gt_i32_e32 vcc, s%d, v%d", kSgprEntry + 1, kVgprAcc0);
+            e.line("\tglobal_load_dword v%d, v%d, s[%d:%d] offset:%d", kVgprT1, kVgprAcc0, kSgprPc, kSgprPc + 1, 128 * j);
+            if (j + 1 < prefetch_lines) e.line("\ts_sub_u32 s%d, s%d, 128", kSgprEntry + 1, kSgprEntry + 1);
+        }
+        e.line("\ts_mov_b64 exec, s[%d:%d]", kSgprOwns, kSgprOwns + 1);
+    }
     e.line("\ts_setpc_b64 s[%d:%d]", kSgprPc, kSgprPc + 1);
     e.line(".Lend:");
     e.line("\ts_endpgm");
     e.line("\t.p2align 2");
     e.line(".Ltable:");
     for (int g = 0; g < n_blocks; ++g) e.line("\t.long .Lg%d-.Ltable", g);
+    e.line("\t.long .Lfunc_end-.Ltable");   // end of the last block
 
 }
 
@@ -1095,16 +1121,26 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err) 
     Gen gen(h, sp);
     Extents ex;
     if (int rc = plan_registers(h, sp, sh, members, gen, ex, err)) return rc;
-    emit_prologue(gen, sh, ex);
+    // The blocks are emitted first: the prologue wants to know how long the longest one is.
     Emitter &e = gen.e;
     sp.group_columns.assign(sp.n_blocks, 0);
+    int64_t longest = 0;   // instructions of the longest block
     for (int g = 0; g < sp.n_blocks; ++g) {
+        const int64_t before = e.lines;
         e.line("\t.p2align 2");
         e.line(".Lg%d:", g);
         sp.group_columns[g] = sh.lds ? gen.block_lds(members[g], g % sh.W, sh.W)
                                      : gen.block_direct(members[g / sh.KS], g % sh.KS, sh.KS);
+        longest = std::max(longest, e.lines - before);
     }
     emit_kernel_descriptor(gen, sh);
+    // an instruction is at most 8 bytes; 64 lanes touch one 128-byte line each per prefetch
+    // instruction, at most 32 of them (their offsets must fit the load's immediate field)
+    const int prefetch_lines = !opt.spec_prefetch ? 0 : (int)std::min<int64_t>(32, (longest * 8 + 64 * 128 - 1) / (64 * 128));
+    sp.prefetch_lines = prefetch_lines;
+    Emitter head;
+    emit_prologue(gen, head, sh, ex, prefetch_lines);
+    e.s.insert(0, head.s);
 
     if (const char *dump = getenv("SPARSERT_DUMP_ASM")) {
         if (FILE *f = fopen(dump, "w")) { fwrite(e.s.data(), 1, e.s.size(), f); fclose(f); }

@@ -80,6 +80,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
     b.host_only = 0;
     b.vec = b.split_threshold = b.spec_rows = b.spec_depth = b.spec_tiles = b.spec_mode = b.spec_ksplit = b.spec_lanes = b.spec_swizzle = b.spec_vec = 0;
     const int32_t tune_warm = b.tune_warm;
+    b.spec_prefetch = 0;   // tried on the winner at the end
     b.tune_warm = 0;   // a tuner flag, not a property of the plans
     // First candidate: the inspector's own choice.  It also validates every argument.
     sparsert_plan *best = nullptr;
@@ -278,6 +279,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         t.spec_swizzle = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.swizzle : 0;
         t.spec_vec = h.kernel == SPARSERT_KERNEL_SPEC ? h.spec.vec : 0;
         t.microseconds = tm.warm; t.cold_microseconds = tm.cold; t.agrees = tm.agrees;
+        t.spec_prefetch = h.kernel == SPARSERT_KERNEL_SPEC && h.spec.prefetch_lines > 0;
     };
     Timing best_t = measure(best);
     log(best, best_t);
@@ -363,6 +365,26 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
             const Timing t = measure(p);
             log(p, t);
             if (key(t) > 0.0f && key(t) < key(best_t)) {
+                sparsert_plan_destroy(best);
+                best = p; best_t = t;
+            } else {
+                sparsert_plan_destroy(p);
+            }
+        }
+    }
+    // ... and the winner with its waves prefetching their code: kept if it is worth at least 2 %
+    // under the condition the ranking uses (it costs time while the code is still in the L2)
+    if (key(best_t) > 0.0f && best->host.kernel == SPARSERT_KERNEL_SPEC) {
+        const sparsert::SpecPlan &w = best->host.spec;
+        sparsert_options o = b;
+        o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = w.mode; o.spec_rows = w.rows_per_group;
+        o.spec_tiles = w.tiles_per_wg; o.spec_ksplit = w.ksplit; o.spec_vec = w.vec; o.spec_swizzle = w.swizzle;
+        o.spec_prefetch = 1;
+        sparsert_plan *p = nullptr;
+        if (sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &p) == SPARSERT_OK) {
+            const Timing t = measure(p);
+            log(p, t);
+            if (key(t) > 0.0f && key(t) < 0.98f * key(best_t)) {
                 sparsert_plan_destroy(best);
                 best = p; best_t = t;
             } else {

@@ -27,7 +27,7 @@ INFO_NAMES = ["M", "K", "N", "nnz", "dtype", "conv", "Cin", "H", "W", "kernel", 
               "lanes_per_tile", "n_tiles", "gy", "split_threshold", "n_split", "n_wg_rows",
               "n_bins", "spec_rows", "spec_groups", "spec_depth", "spec_code_bytes",
               "spec_tiles", "spec_mode", "spec_lds_bytes", "spec_ksplit", "natural_order", "spec_lanes", "spec_swizzle", "batch", "spec_vec",
-              "ldb", "ldc"]
+              "ldb", "ldc", "spec_prefetch"]
 INFO_COUNT = 48
 
 EXPORTED = ["sparsert_inspect", "sparsert_tune", "sparsert_spmm", "sparsert_conv3x3", "sparsert_compare_outputs", "sparsert_compare_outputs_static", "sparsert_plan_export",
@@ -45,7 +45,7 @@ class Options(ctypes.Structure):
                 ("spec_ksplit", ctypes.c_int32), ("natural_order", ctypes.c_int32),
                 ("spec_lanes", ctypes.c_int32), ("spec_swizzle", ctypes.c_int32),
                 ("spec_vec", ctypes.c_int32), ("ldb", ctypes.c_int32), ("ldc", ctypes.c_int32),
-                ("tune_warm", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("tune_warm", ctypes.c_int32), ("spec_prefetch", ctypes.c_int32), ("reserved", ctypes.c_int32 * 2)]
 
 
 TUNE_MAX = 64
@@ -57,7 +57,7 @@ class TuneEntry(ctypes.Structure):
                 ("spec_tiles", ctypes.c_int32), ("spec_ksplit", ctypes.c_int32),
                 ("spec_lanes", ctypes.c_int32), ("spec_swizzle", ctypes.c_int32),
                 ("spec_vec", ctypes.c_int32), ("microseconds", ctypes.c_float),
-                ("cold_microseconds", ctypes.c_float), ("agrees", ctypes.c_int32)]
+                ("cold_microseconds", ctypes.c_float), ("agrees", ctypes.c_int32), ("spec_prefetch", ctypes.c_int32)]
 
 
 class TuneReport(ctypes.Structure):
@@ -181,7 +181,7 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
             spec_rows: int = 0, spec_depth: int = 0, spec_tiles: int = 0,
             spec_mode: int = 0, spec_ksplit: int = 0, natural_order: bool = False,
             spec_lanes: int = 0, spec_swizzle: bool = False, spec_vec: int = 0,
-            ldb: int = 0, ldc: int = 0) -> Plan:
+            ldb: int = 0, ldc: int = 0, spec_prefetch: int = 0) -> Plan:
     """sparsert_inspect.  `vals` must already be float32, float16 or int8; it is not converted."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -196,7 +196,7 @@ def inspect(row_ptr, col_idx, vals, M: int, K: int, N: int, *, dtype: Optional[i
     opt.spec_rows, opt.spec_depth, opt.spec_tiles = spec_rows, spec_depth, spec_tiles
     opt.spec_mode, opt.spec_ksplit, opt.natural_order = spec_mode, spec_ksplit, int(natural_order)
     opt.spec_lanes, opt.spec_swizzle, opt.spec_vec = spec_lanes, int(spec_swizzle), spec_vec
-    opt.ldb, opt.ldc = ldb, ldc
+    opt.ldb, opt.ldc, opt.spec_prefetch = ldb, ldc, spec_prefetch
     if conv is not None:
         opt.conv, (opt.Cin, opt.H, opt.W) = 1, conv
     handle = _vp()

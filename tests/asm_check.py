@@ -89,6 +89,31 @@ def check(text: str, info: dict, esz: int, osz: int):
         m = re.match(r"v_lshlrev_b32_e32 v1, (\d+), v0$", l)
         if m:
             lds_class[1] = (1 << int(m.group(1)), 0)
+    # the code prefetch of the prologue: lane i touches byte i * stride + 128 j of its block, j = 0, 1, ...,
+    # under a mask `length - 128 j > i * stride`; the loads must come in that order, each right after its
+    # mask, their offsets must equal what has been subtracted from the length so far, and the
+    # lines of one lane must not run into the next lane's
+    pf_sub, pf_stride, pf_masked, pf_loads = 0, None, False, 0
+    for l in body[:first_block]:
+        m = re.match(r"v_mul_u32_u24_e32 v4, (0x[0-9a-f]+|\d+), v4$", l)
+        if m:
+            pf_stride = _imm(m.group(1))
+        if re.match(r"v_cmpx_gt_i32_e32 vcc, s55, v4$", l):
+            pf_masked = True
+        elif re.match(r"s_sub_u32 s55, s55, 128$", l):
+            pf_sub += 128
+        elif l.startswith("global_load_dword"):
+            m = re.match(r"global_load_dword v2, v4, s\[18:19\] offset:(\d+)$", l)
+            if not m:
+                problems.append(f"prologue: unexpected form of the code prefetch: `{l}`")
+            elif not pf_masked or int(m.group(1)) != pf_sub or int(m.group(1)) > 4095:
+                problems.append(f"prologue: code prefetch at offset {m.group(1)} is not covered by its length mask")
+            pf_masked = False
+            pf_loads += 1
+        elif "exec" in l and pf_loads and not l.startswith("s_mov_b64 exec, s[22:23]"):
+            problems.append(f"prologue: exec changed inside the code prefetch: `{l}`")
+    if pf_loads and (pf_stride is None or pf_stride < 128 * pf_loads):
+        problems.append("prologue: the prefetch lines of neighbouring lanes overlap")
     table = [l for l in body[:first_block] if l.startswith(".long .Lg")]
     n_blocks = sum(1 for l in body if re.match(r"\.Lg\d+:$", l))
     if len(table) != n_blocks:
@@ -97,7 +122,8 @@ def check(text: str, info: dict, esz: int, osz: int):
         problems.append("descriptor extents not found in the prologue")
         return problems, {}
 
-    stats = {"blocks": n_blocks, "loads": 0, "stores": 0, "lds": 0, "max_in_end": 0, "max_out_end": 0, "max_lds_end": 0}
+    stats = {"blocks": n_blocks, "loads": 0, "stores": 0, "lds": 0, "max_in_end": 0, "max_out_end": 0, "max_lds_end": 0,
+             "prefetch_loads": pf_loads}
 
     # ---- blocks
     i = first_block
@@ -124,6 +150,8 @@ def check(text: str, info: dict, esz: int, osz: int):
 
         def touch(regs, what):
             for r in regs:
+                if r == 2 and pf_loads:
+                    bad("v2 is where the prologue's code prefetch lands, at any time: no block may use it")
                 if r >= n_vgpr:
                     bad(f"v{r} is beyond next_free_vgpr {n_vgpr}")
                 if r in pend_vm and pend_vm[r] >= vm_done:

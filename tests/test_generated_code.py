@@ -53,6 +53,19 @@ def test_direct_and_k_split_blocks_stay_in_bounds(dtype, opts, N, tmp_path):
     assert stats["max_in_end"] <= 333 * N * esz and stats["loads"] > 0 and stats["stores"] >= 210
 
 
+
+def test_code_prefetch_is_checked(tmp_path):
+    csr = synth.uniform_csr(300, 500, 0.8, 2)
+    text, info = _generated(csr, 130, tmp_path, spec_rows=96, spec_ksplit=2, spec_prefetch=1)
+    problems, stats = asm_check.check(text, info, 4, 4)
+    assert not problems and stats["prefetch_loads"] >= 2 and info["spec_prefetch"] == stats["prefetch_loads"]   # blocks of more than 8 KiB
+    off, info2 = _generated(csr, 130, tmp_path, spec_rows=96, spec_ksplit=2)
+    assert asm_check.check(off, info2, 4, 4) == ([], dict(stats, prefetch_loads=0)) and info2["spec_prefetch"] == 0
+    # a prefetch whose offset runs ahead of its mask would read past the block: the checker sees it
+    bad = text.replace("global_load_dword v2, v4, s[18:19] offset:128", "global_load_dword v2, v4, s[18:19] offset:256", 1)
+    assert any("not covered by its length mask" in p for p in asm_check.check(bad, info, 4, 4)[0])
+
+
 @pytest.mark.parametrize("N,vec,dtype", [(64, 2, np.float16), (130, 2, np.float16), (64, 4, np.int8), (260, 4, np.int8)])
 @pytest.mark.parametrize("ks", [1, 4])
 def test_packed_columns_stay_in_bounds(N, vec, dtype, ks, tmp_path):
@@ -135,10 +148,10 @@ def test_the_checker_catches_planted_mistakes(tmp_path):
 @settings(max_examples=60, deadline=None, suppress_health_check=[HealthCheck.function_scoped_fixture])
 @given(M=st.integers(1, 130), K=st.integers(1, 400), N=st.integers(1, 330), sparsity=st.sampled_from([0.0, 0.5, 0.9, 0.99]),
        rows=st.sampled_from([0, 1, 3, 8, 31, 96]), ks=st.sampled_from([0, 1, 2, 4, 8]), mode=st.sampled_from([1, 1, 2]),
-       dtype=st.sampled_from([np.float32, np.float16, np.int8]), swizzle=st.booleans(), seed=st.integers(0, 99))
-def test_random_generated_kernels_are_clean(M, K, N, sparsity, rows, ks, mode, dtype, swizzle, seed, tmp_path):
+       dtype=st.sampled_from([np.float32, np.float16, np.int8]), swizzle=st.booleans(), seed=st.integers(0, 99), prefetch=st.booleans())
+def test_random_generated_kernels_are_clean(M, K, N, sparsity, rows, ks, mode, dtype, swizzle, seed, prefetch, tmp_path):
     csr = _csr(dtype, M, K, sparsity, seed)
-    opts = dict(spec_rows=rows, spec_ksplit=ks, spec_mode=mode, spec_swizzle=swizzle)
+    opts = dict(spec_rows=rows, spec_ksplit=ks, spec_mode=mode, spec_swizzle=swizzle, spec_prefetch=int(prefetch))
     if mode == sp.SPEC_LDS:
         opts["spec_ksplit"] = 0
     try:

@@ -683,3 +683,38 @@ def test_leading_dimensions_headline_layer_slice():
     Cref, S = ref.spmm(case.csr.M, case.csr.K, case.N, case.csr.row_ptr, case.csr.col_idx, case.csr.vals, case.B)
     check(got, Cref, S, np.float32, gate_relative=True)
     assert pad_ok and info["kernel"] == sp.KERNEL_SPEC
+
+
+# ---------------------------------------------------------------- code prefetch
+@pytest.mark.parametrize("opts", [dict(spec_rows=1), dict(spec_rows=96, spec_ksplit=2), dict(spec_rows=24, spec_ksplit=8),
+                                  dict(spec_rows=200, spec_ksplit=8), dict(spec_rows=12, spec_mode=sp.SPEC_LDS, spec_tiles=8)])
+@pytest.mark.parametrize("N", [1, 65, 196])
+def test_code_prefetch_changes_no_result(N, opts):
+    """Waves that touch their block's code ahead (blocks from a few hundred bytes to several
+    prefetch lines per lane) compute exactly what they compute without."""
+    csr = synth.small_int_csr(300, 500, 0.8, N)
+    B = synth.small_int_dense(500, N, N + 1)
+    Cref, _ = _oracle(csr, B)
+    got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_prefetch=1, **opts)
+    assert info["spec_prefetch"] >= 1
+    assert np.array_equal(got.astype(np.float64), Cref), info
+
+
+def test_code_prefetch_headline_layers_half_int8_and_conv():
+    for name, opts in (("c3", dict(spec_rows=96, spec_ksplit=4, spec_swizzle=True)), ("c3t", dict(spec_rows=48, spec_ksplit=8))):
+        case = synth.config(name)
+        got, info = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_prefetch=1, **opts)
+        Cref, S = _oracle(case.csr, case.B)
+        check(got, Cref, S, np.float32, gate_relative=True)
+    case = synth.config("c2", np.float16)
+    got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_prefetch=1, spec_vec=2, spec_rows=8)
+    Cref, S = _oracle(case.csr, case.B)
+    check(got, Cref, S, np.float16, gate_relative=True)
+    case = synth.config("c1", np.int8)
+    got, _ = run_spmm(case.csr, case.B, kernel=sp.KERNEL_SPEC, spec_prefetch=1, spec_vec=4, spec_rows=8, spec_ksplit=2)
+    Cref, _ = _oracle(case.csr, case.B)
+    assert np.array_equal(got.astype(np.float64), Cref)
+    case = synth.config("c4")
+    got, _ = run_conv(case.csr, case.X, 256, kernel=sp.KERNEL_SPEC, spec_prefetch=1)
+    Yref, S = ref.conv3x3(case.Wdense, case.X)
+    check(got, Yref, S, np.float32, gate_relative=True)
