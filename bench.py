@@ -57,7 +57,7 @@ class Layer:
     """One sparse layer resident on the GPU: plan, input, output and its dense twin."""
 
     PLAN_KEYS = ("kernel", "vec", "split_threshold", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit",
-                 "spec_swizzle", "spec_vec")
+                 "spec_swizzle", "spec_vec", "spec_prefetch")
 
     def __init__(self, case, torch, sp, kernel="tune", fixed=None):
         import numpy as np
@@ -96,6 +96,7 @@ class Layer:
                     pass
         self.tuned = None
         if fixed is not None:
+            fixed = dict(fixed, spec_prefetch=1 if fixed.get("spec_prefetch") else 0)   # the plan reports lines, the option is a switch
             self.plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, csr.M, csr.K, case.N, conv=case.conv, **fixed)
         elif kernel == "tune":
             # offline, once per matrix (Section 3.7); not part of the timed region
@@ -498,12 +499,12 @@ def main():
                           "dense_timing": dense_how,
                           "plan": {k: L.info[k] for k in ("kernel", "vec", "n_split", "spec_mode", "spec_rows",
                                                           "spec_tiles", "spec_ksplit", "spec_swizzle", "spec_vec",
-                                                          "spec_code_bytes")},
+                                                          "spec_prefetch", "spec_code_bytes")},
                           "tuned_candidates": len(L.tuned) if L.tuned else 0,
                           # the tuner's six fastest candidates (ranked with displaced caches), for the record
                           "tuned_top": sorted(({k: (round(v, 2) if isinstance(v, float) else v) for k, v in e.items()
                                                 if k in ("kernel", "vec", "spec_mode", "spec_rows", "spec_tiles", "spec_ksplit",
-                                                         "spec_swizzle", "spec_vec", "microseconds", "cold_microseconds", "agrees")}
+                                                         "spec_swizzle", "spec_vec", "spec_prefetch", "microseconds", "cold_microseconds", "agrees")}
                                                for e in (L.tuned or []) if e["cold_microseconds"] > 0),
                                               key=lambda e: e["cold_microseconds"])[:6]})
     # ---- every layer's launch duration inside the step.  The HIP events around the timed region
