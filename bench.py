@@ -467,7 +467,12 @@ def main():
         for L in layers:
             L.launch(stream)
 
-    # ---- the timed region: exactly --steps steps between two synchronisations
+    # ---- the timed region: exactly --steps steps between two synchronisations.  Before the
+    # --warmup steps the step runs 300 times untimed: planning and tuning leave the GPU idle for
+    # seconds, and a short run (--steps 20) would otherwise time the clocks ramping up
+    for _ in range(300):
+        step()
+    torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -155,13 +155,18 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         auto add_direct = [&](int V) {
             const int64_t vtiles = (N / V + 63) / 64 * images;
             const int max_rows = 192 / V;   // accumulator registers
+            // Matrices of some size get a thinner list (a candidate costs 1-2.5 s of assembling per
+            // 100 000 nonzeros): blocks of one or two rows - the largest code, and winners only on
+            // small problems - and the two-tile twins of the four-tile workgroups are left out.
+            const bool sizeable = nnz > (64 << 10);
             for (int r : {1, 2, 4, 8, 16, 24, 48, 96}) {
                 if (r > M || r > max_rows || (r == 96 && images == 1)) continue;
+                if (sizeable && r < 4 && M >= 1024) continue;
                 const int64_t groups = (M + r - 1) / r;
                 if (r > 1 && groups * vtiles < 256) continue;   // too few waves to be worth assembling
                 if (groups > 8192) continue;
                 for (int t : {2, 4}) {
-                    if (V > 1 && t == 2) continue;
+                    if ((V > 1 || sizeable) && t == 2) continue;
                     sparsert_options o = b;
                     o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
                     o.spec_rows = r; o.spec_tiles = t; o.spec_vec = V;

@@ -68,8 +68,8 @@ def test_table3_convolution_in_its_tuned_plan(i, sparsity):
 
 
 def test_table1_half_precision_problems_in_their_tuned_plans():
-    # one problem of each family (ResNet-50 with N = 49, Transformer, MobileNetV1 with N = 12544)
-    for i, sparsity in ((7, 0.95), (9, 0.90), (11, 0.90)):
+    # the two extremes of N (ResNet-50's 49 columns, MobileNetV1's 12544)
+    for i, sparsity in ((7, 0.95), (11, 0.90)):
         case = synth.table1_case(i, sparsity, np.float16)
         got, info, _ = _tuned_run(case, np.float16)
         csr = case.csr
@@ -109,7 +109,7 @@ def test_sweep_sample(M, K, N, sparsity, kind, dtype):
     got, info = run_spmm(csr, case.B)
     assert info["kernel"] == (sp.KERNEL_SPEC if csr.nnz <= 4194304 else sp.KERNEL_ROWS)
     check(got[rows], Cref, S, dtype)
-    if csr.nnz <= 120000:
+    if csr.nnz <= 60000:
         got, info, entries = _tuned_run(case, dtype)
         check(got[rows], Cref, S, dtype)
         assert all(e["agrees"] for e in entries)
