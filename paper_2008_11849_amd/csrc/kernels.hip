@@ -546,6 +546,8 @@ int launch_spec(const HostPlan &h, const DevicePlan &d, const void *B, void *C,
     if (sp.ksplit > 1 && (lds || sp.ksplit != tpw || sp.n_blocks != sp.n_groups * sp.ksplit)) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     const unsigned gx = (lds || sp.ksplit > 1) ? (unsigned)sp.n_tiles : (unsigned)((sp.n_tiles + tpw - 1) / tpw);
     const unsigned gy = lds ? (unsigned)(sp.n_blocks / tpw) : (unsigned)sp.n_groups;
+    // (that the workgroup's registers fit a compute unit was checked when the plan was generated;
+    // a loaded plan carries the symbol's own register count in its code object and is checked by the loader)
     const unsigned gz = (unsigned)h.batch;   // the generated prologue offsets the operand and the result by problem
     if (gz < 1 || gz > 65535) { err = "plan geometry is inconsistent"; return SPARSERT_EINVAL; }
     HIP_TRY(hipModuleLaunchKernel(static_cast<hipFunction_t>(d.spec_function), gx, gy, gz, tpw * kWave, 1, 1,

@@ -851,6 +851,13 @@ static int plan_registers(const HostPlan &h, SpecPlan &sp, const Shape &sh, cons
         }
     }
     if (gen.n_vgpr > 256) { err = "spec_rows too large for the register file"; return SPARSERT_EINVAL; }
+    // A workgroup must fit a compute unit at once: its waves are spread over the four SIMDs, and a
+    // SIMD has 512 registers per lane, handed out in granules of eight.  (A dispatch that does not
+    // fit is rejected by the hardware queue, which aborts the process.)
+    if ((W + 3) / 4 * ((gen.n_vgpr + 7) / 8 * 8) > 512) {
+        err = "spec_rows too large for this many waves per workgroup: the workgroup's registers do not fit a compute unit";
+        return SPARSERT_EINVAL;
+    }
     // The symbol carries the problem shape so that kernel traces tell the plans of a model apart.
     char sym[96];
     snprintf(sym, sizeof(sym), "sparsert_spec_%s%dx%dx%d%s", h.conv ? "conv_" : "", (int)M, (int)h.K, (int)N,

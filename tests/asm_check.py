@@ -15,7 +15,8 @@ has not arrived.  For every block this walks the instructions in order and check
     in flight: the s_waitcnt before it must have retired that load (vmcnt counts loads and
     stores on this target, LDS reads return in order under lgkmcnt), and no load is issued
     into a register whose previous load was never consumed;
-  * every VGPR index is below next_free_vgpr, every SGPR index below next_free_sgpr;
+  * every VGPR index is below next_free_vgpr, every SGPR index below next_free_sgpr; a
+    workgroup's registers and its group segment fit one compute unit;
   * the jump table has one entry per block and every block ends the program.
 
 `check(text, info)` returns a list of problems (empty = clean) and a few statistics.
@@ -70,6 +71,14 @@ def check(text: str, info: dict, esz: int, osz: int):
         if m:
             meta[m.group(1)] = int(m.group(2))
     lds_bytes, n_vgpr, n_sgpr = meta["group_segment_fixed_size"], meta["next_free_vgpr"], meta["next_free_sgpr"]
+    m = re.search(r"\.max_flat_workgroup_size:\s*(\d+)", text)
+    waves = int(m.group(1)) // 64 if m else 0
+    if waves < 1 or waves > 16:
+        problems.append(f"workgroup of {waves} waves")
+    if (waves + 3) // 4 * ((n_vgpr + 7) // 8 * 8) > 512:
+        problems.append(f"a workgroup of {waves} waves with {n_vgpr} registers each does not fit a compute unit")
+    if lds_bytes > 160 * 1024:
+        problems.append(f"group segment of {lds_bytes} bytes exceeds a compute unit's LDS")
     V = max(1, info["spec_vec"])
     nvc = info["N"] // V
     lanes = info["spec_lanes"]

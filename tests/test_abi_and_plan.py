@@ -424,6 +424,23 @@ def test_generated_kernel_ksplit_lds_budget():
     plan.destroy()
 
 
+def test_workgroups_whose_registers_do_not_fit_a_compute_unit_are_refused():
+    """Sixteen waves are four per SIMD: at most 128 registers each.  The hardware queue rejects a
+    dispatch that does not fit (and the process with it), so the inspector must."""
+    csr = synth.uniform_csr(480, 600, 0.9, 1)
+    args = (csr.row_ptr, csr.col_idx, csr.vals, 480, 600, 130)
+    for kw in (dict(spec_mode=sp.SPEC_LDS, spec_rows=103, spec_tiles=16), dict(spec_rows=120, spec_tiles=16),
+               dict(spec_mode=sp.SPEC_LDS, spec_rows=128, spec_tiles=16)):
+        with pytest.raises(sp.SparseRTError) as e:
+            sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, **kw)
+        assert e.value.status == sp.EINVAL and "fit a compute unit" in str(e.value), kw
+    for kw in (dict(spec_mode=sp.SPEC_LDS, spec_rows=60, spec_tiles=16), dict(spec_rows=96, spec_tiles=16),
+               dict(spec_rows=200, spec_ksplit=8), dict(spec_mode=sp.SPEC_LDS, spec_rows=128, spec_tiles=8)):
+        plan = sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, **kw)
+        info = plan.info()
+        plan.destroy()
+
+
 def test_generated_kernel_option_errors():
     csr = synth.uniform_csr(16, 18, 0.5, 1)
     args = (csr.row_ptr, csr.col_idx, csr.vals, 16, 18, 8)
