@@ -96,6 +96,14 @@ int build_spec_plan(HostPlan &h, const sparsert_options &opt, std::string &err);
 // ties go to the larger R (fewer fetches of B).  Only counts that leave no compute unit without a
 // workgroup are considered; if there is none, lo is returned.
 int rows_for_whole_rounds(int32_t M, int groups_per_wg, int64_t wg_columns, int lo, int hi);
+// The smallest number of rows per code block for which the launch is at most `rounds` workgroups
+// per compute unit (workgroups counted as above); 0 if more than `hi` rows would be needed.
+int rows_for_rounds(int32_t M, int groups_per_wg, int64_t wg_columns, int rounds, int hi);
+// A launch a little over a whole number of workgroups per compute unit leaves a few compute units
+// with one workgroup more than the rest, and they set the time.  Where the last round is less
+// than a quarter full and at most 15 % more rows per block remove it, this returns that row
+// count; else R.
+int rows_without_thin_round(int32_t M, int R, int groups_per_wg, int64_t wg_columns, int hi);
 bool spec_available();   // can generated kernels be assembled in this process (is the code object manager loadable)?
 
 // Records the thread-local error message behind sparsert_last_error (api.cpp); returns `code`.

@@ -674,6 +674,31 @@ int rows_for_whole_rounds(int32_t M, int groups_per_wg, int64_t wg_columns, int 
     return best > 0 ? best : lo;   // too small a launch for any count in range: the most workgroups
 }
 
+static int64_t workgroups_for(int32_t M, int r, int groups_per_wg, int64_t wg_columns) {
+    const int64_t groups = ((int64_t)M + r - 1) / r;
+    return (groups + groups_per_wg - 1) / groups_per_wg * wg_columns;
+}
+
+int rows_for_rounds(int32_t M, int groups_per_wg, int64_t wg_columns, int rounds, int hi) {
+    constexpr int64_t kComputeUnits = 256;
+    for (int r = 1; r <= std::min<int>(hi, M); ++r)
+        if (workgroups_for(M, r, groups_per_wg, wg_columns) <= kComputeUnits * rounds) return r;
+    return 0;
+}
+
+int rows_without_thin_round(int32_t M, int R, int groups_per_wg, int64_t wg_columns, int hi) {
+    constexpr int64_t kComputeUnits = 256;
+    const int64_t wgs = workgroups_for(M, R, groups_per_wg, wg_columns);
+    const int64_t rounds = (wgs + kComputeUnits - 1) / kComputeUnits;
+    // (blocks of a few rows make small workgroups, several of which share a compute unit: no rounds there)
+    if (R < 8 || rounds < 2 || rounds > 16 || wgs - kComputeUnits * (rounds - 1) > kComputeUnits / 4) return R;
+    const int top = std::min<int>(std::min<int>(hi, M), R + (R * 15 + 99) / 100);
+    for (int r = R + 1; r <= top; ++r)
+        if (workgroups_for(M, r, groups_per_wg, wg_columns) <= kComputeUnits * (rounds - 1))
+            return (rounds - 1) * r < rounds * R ? r : R;
+    return R;
+}
+
 // What the stages below hand to each other besides the SpecPlan itself.
 struct Shape {
     bool lds = false;   // LDS-staged variant
@@ -723,6 +748,11 @@ static int choose_launch_shape(const HostPlan &h, const sparsert_options &opt, S
         R = (int)std::max<int64_t>(1, std::min<int64_t>(96 / V, (int64_t)M * tiles_all * KS / target));
         if (opt.spec_ksplit == 0)   // fewer parts where the rows alone already supply the waves
             while (KS > 1 && ((int64_t)M + R - 1) / R * tiles_all * (KS / 2) >= 2048) KS /= 2;
+        // 1024 rows in blocks of 52 on 13 column tiles are 260 workgroups, four more than compute
+        // units: 34.8 us; in blocks of 54 they are 247: 21.3 us (4096 columns of A at 95 %)
+        const int T = opt.spec_tiles ? opt.spec_tiles : 4;
+        const int64_t wg_columns = KS > 1 ? tiles_all : (sp.n_tiles + T - 1) / T * std::max(1, h.batch);
+        R = rows_without_thin_round(M, R, 1, wg_columns, 128 / V);
     }
     sp.ksplit = KS;
     if (sp.ksplit != 1 && sp.ksplit != 2 && sp.ksplit != 4 && sp.ksplit != 8) { err = "spec_ksplit must be 0,1,2,4,8"; return SPARSERT_EINVAL; }

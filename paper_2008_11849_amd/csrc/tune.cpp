@@ -169,7 +169,9 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
                     if ((V > 1 || sizeable) && t == 2) continue;
                     sparsert_options o = b;
                     o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
-                    o.spec_rows = r; o.spec_tiles = t; o.spec_vec = V;
+                    // (a few more rows where that spares a last round of workgroups on a few compute units)
+                    o.spec_rows = sparsert::rows_without_thin_round(M, r, 1, (vtiles / images + t - 1) / t * images, max_rows);
+                    o.spec_tiles = t; o.spec_vec = V;
                     cands.push_back(o);
                 }
             }
@@ -177,15 +179,34 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
                 const int rk[][2] = {{1, 8}, {2, 8}, {4, 8}, {8, 8}, {16, 8}, {24, 8}, {32, 8}, {48, 8}, {64, 8}, {96, 8}, {128, 8},
                                      {1, 4}, {2, 4}, {4, 4}, {8, 4}, {16, 4}, {32, 4}, {48, 4}, {64, 4}, {96, 4},
                                      {64, 2}, {96, 2}};
+                std::vector<std::pair<int, int>> listed;
+                auto add = [&](int r, int ks) {
+                    if (std::find(listed.begin(), listed.end(), std::make_pair(r, ks)) != listed.end()) return;
+                    listed.push_back({r, ks});
+                    sparsert_options o = b;
+                    o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
+                    o.spec_rows = r; o.spec_ksplit = ks; o.spec_vec = V;
+                    cands.push_back(o);
+                };
                 for (auto &c : rk) {
                     // worth timing with at least two waves for every SIMD of the chip, but not with
                     // more than sixteen (the blocks are then too small to reuse a fetched row)
                     const int64_t waves = (int64_t)((M + c[0] - 1) / c[0]) * vtiles * c[1];
                     if (c[0] > M || c[0] > max_rows || waves < 2048 || waves > 16384) continue;
-                    sparsert_options o = b;
-                    o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_DIRECT;
-                    o.spec_rows = c[0]; o.spec_ksplit = c[1]; o.spec_vec = V;
-                    cands.push_back(o);
+                    // never a last round of workgroups that only a few compute units take part in
+                    add(sparsert::rows_without_thin_round(M, c[0], 1, vtiles, max_rows), c[1]);
+                }
+                // ... and the row counts that make the launch exactly one, two or four workgroups
+                // per compute unit with two or four waves per SIMD: the fewest fetches of B a
+                // launch that still fills the chip can have (1024 x 4096 at 95 %, 784 columns:
+                // 54 rows x 8 parts = 247 workgroups, 21.3 us; the listed 48 rows = 286: 43.7 us)
+                const int whole[][2] = {{8, 1}, {8, 2}, {4, 2}, {4, 4}, {2, 4}};   // parts, workgroups per compute unit
+                for (auto &c : whole) {
+                    const int r = sparsert::rows_for_rounds(M, 1, vtiles, c[1], max_rows);
+                    if (r < 4) continue;
+                    const int64_t wgs = (int64_t)((M + r - 1) / r) * vtiles;
+                    if (wgs * 4 < (int64_t)256 * c[1] * 3) continue;   // under three quarters of the chip
+                    add(r, c[0]);
                 }
             }
         };
@@ -198,7 +219,8 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
                     if (((int64_t)M + r - 1) / r < w) continue;
                     sparsert_options o = b;
                     o.kernel = SPARSERT_KERNEL_SPEC; o.spec_mode = SPARSERT_SPEC_LDS;
-                    o.spec_rows = r; o.spec_tiles = w;
+                    o.spec_rows = sparsert::rows_without_thin_round(M, r, w, tiles, 128);
+                    o.spec_tiles = w;
                     cands.push_back(o);
                 }
         }
