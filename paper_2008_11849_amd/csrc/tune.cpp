@@ -210,6 +210,11 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
                 }
             }
         };
+        {   // what the inspector picks when nothing is set is always in the race
+            sparsert_options o = b;
+            o.kernel = SPARSERT_KERNEL_SPEC;
+            cands.push_back(o);
+        }
         add_direct(1);
         if (!conv && f16 && N % 2 == 0) add_direct(2);
         if (!conv && i8 && N % 4 == 0) add_direct(4);

@@ -718,3 +718,15 @@ def test_code_prefetch_headline_layers_half_int8_and_conv():
     got, _ = run_conv(case.csr, case.X, 256, kernel=sp.KERNEL_SPEC, spec_prefetch=1)
     Yref, S = ref.conv3x3(case.Wdense, case.X)
     check(got, Yref, S, np.float32, gate_relative=True)
+
+
+@pytest.mark.parametrize("M,K,N,rows", [(1024, 512, 784, 54), (256, 128, 3136, 14), (1024, 600, 3136, 103)])
+def test_default_rows_that_avoid_a_thin_last_round(M, K, N, rows):
+    """Shapes whose default row count is raised so that the workgroups fit a whole number of
+    rounds over the compute units (54 rows: 19 blocks x 13 tiles = 247 workgroups, not 260)."""
+    csr = synth.small_int_csr(M, K, 0.95, N)
+    B = synth.small_int_dense(K, N, N + 1)
+    Cref, _ = _oracle(csr, B)
+    got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC)
+    assert info["spec_rows"] == rows, info
+    assert np.array_equal(got.astype(np.float64), Cref)
