@@ -87,8 +87,11 @@ typedef struct sparsert_options {
     int32_t split_threshold; /* rows with at least this many nonzeros are split over the
                                 waves of a workgroup; 0 = automatic */
     int32_t spec_rows;       /* SPARSERT_KERNEL_SPEC: rows of A per generated code block
-                                (accumulator registers per wave); 0 = automatic: as many as leave
-                                the launch about two waves per SIMD of the chip, at most 96 */
+                                (accumulator registers per wave), 1 ... 232 as far as the registers
+                                of the workgroup's waves fit a compute unit; 0 = automatic: as many
+                                as leave the launch about two waves per SIMD of the chip, at most 96,
+                                then up to 15 % more (at most 128) where that spares the launch a
+                                last round of workgroups that only a few compute units take part in */
     int32_t spec_depth;      /* SPARSERT_KERNEL_SPEC: B rows a wave keeps in flight; 0 = automatic */
     int32_t spec_tiles;      /* SPARSERT_KERNEL_SPEC: waves per workgroup (adjacent column tiles in
                                 DIRECT mode, adjacent code blocks in LDS mode): 1,2,4,8,16;

@@ -761,7 +761,7 @@ static int choose_launch_shape(const HostPlan &h, const sparsert_options &opt, S
     const int W = sp.tiles_per_wg;
     int wshift = 0;
     while ((1 << wshift) < W) ++wshift;
-    if (R < 1 || R > 200) { err = "spec_rows must be in 1..200"; return SPARSERT_EINVAL; }
+    if (R < 1 || R > 232) { err = "spec_rows must be in 1..232"; return SPARSERT_EINVAL; }
     R = std::min(R, M);
     sp.rows_per_group = R;
     sp.n_groups = (M + R - 1) / R;

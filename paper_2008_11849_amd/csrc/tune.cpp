@@ -202,7 +202,9 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
                 // 54 rows x 8 parts = 247 workgroups, 21.3 us; the listed 48 rows = 286: 43.7 us)
                 const int whole[][2] = {{8, 1}, {8, 2}, {4, 2}, {4, 4}, {2, 4}};   // parts, workgroups per compute unit
                 for (auto &c : whole) {
-                    const int r = sparsert::rows_for_rounds(M, 1, vtiles, c[1], max_rows);
+                    // (eight parts are two waves per SIMD, which leaves each 256 registers: blocks of up to 224 rows;
+                    // 1024 x 4096 x 3136 at 95 %: 205 rows, one workgroup per compute unit, 45 us; 103 rows, two: 61 us)
+                    const int r = sparsert::rows_for_rounds(M, 1, vtiles, c[1], c[0] == 8 && c[1] == 1 ? 224 / V : max_rows);
                     if (r < 4) continue;
                     const int64_t wgs = (int64_t)((M + r - 1) / r) * vtiles;
                     if (wgs * 4 < (int64_t)256 * c[1] * 3) continue;   // under three quarters of the chip

@@ -444,6 +444,14 @@ def test_workgroups_whose_registers_do_not_fit_a_compute_unit_are_refused():
         plan = sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, **kw)
         info = plan.info()
         plan.destroy()
+    # eight waves are two per SIMD, 256 registers each: two blocks of 232 rows, the fetch ring of 20 and 4 more
+    csr = synth.uniform_csr(464, 300, 0.9, 1)
+    args = (csr.row_ptr, csr.col_idx, csr.vals, 464, 300, 130)
+    sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, spec_rows=232, spec_ksplit=8).destroy()
+    for kw in (dict(spec_rows=233, spec_ksplit=8), dict(spec_rows=232, spec_ksplit=8, spec_depth=32)):
+        with pytest.raises(sp.SparseRTError) as e:
+            sp.inspect(*args, host_only=True, kernel=sp.KERNEL_SPEC, **kw)
+        assert e.value.status == sp.EINVAL, kw
 
 
 def test_generated_kernel_option_errors():

@@ -41,7 +41,7 @@ def _csr(dtype, M, K, sparsity, seed):
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float16, np.int8])
 @pytest.mark.parametrize("opts", [dict(spec_rows=1), dict(spec_rows=7, spec_tiles=2), dict(spec_rows=16, spec_ksplit=2),
-                                  dict(spec_rows=24, spec_ksplit=8), dict(spec_rows=200, spec_ksplit=8), dict(spec_rows=9, spec_depth=3),
+                                  dict(spec_rows=24, spec_ksplit=8), dict(spec_rows=200, spec_ksplit=8), dict(spec_rows=210, spec_ksplit=8), dict(spec_rows=9, spec_depth=3),
                                   dict(spec_rows=5, spec_swizzle=True), dict(spec_rows=8, spec_lanes=16, spec_ksplit=4), dict()])
 @pytest.mark.parametrize("N", [1, 49, 64, 196, 300])
 def test_direct_and_k_split_blocks_stay_in_bounds(dtype, opts, N, tmp_path):

@@ -730,3 +730,15 @@ def test_default_rows_that_avoid_a_thin_last_round(M, K, N, rows):
     got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC)
     assert info["spec_rows"] == rows, info
     assert np.array_equal(got.astype(np.float64), Cref)
+
+
+@pytest.mark.parametrize("N", [49, 130])
+def test_blocks_of_the_most_rows_the_registers_hold(N):
+    """232 rows per block with the reduction axis split over eight waves: the partial sums are
+    exchanged in several phases through all of the LDS."""
+    csr = synth.small_int_csr(464, 300, 0.9, N)
+    B = synth.small_int_dense(300, N, N + 1)
+    Cref, _ = _oracle(csr, B)
+    got, info = run_spmm(csr, B, kernel=sp.KERNEL_SPEC, spec_rows=232, spec_ksplit=8)
+    assert info["spec_rows"] == 232 and info["spec_lds_bytes"] > 150 * 1024
+    assert np.array_equal(got.astype(np.float64), Cref)
