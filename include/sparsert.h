@@ -215,7 +215,8 @@ int sparsert_conv3x3(const sparsert_plan *plan, const void *X_dev, void *Y_dev, 
  *                     out_dev is overwritten many times
  *   stream            launches and timing events go to this stream; the call synchronises it
  *   out               receives the best plan
- *   report            may be NULL; receives one entry per timed candidate
+ *   report            may be NULL; receives one entry per timed candidate (the first SPARSERT_TUNE_MAX of
+ *                     them; later candidates are still timed and may be the one returned)
  *
  * Errors: as sparsert_inspect; EHIP if timing fails.  Allocates (plans, events): not for the
  * inference path.
