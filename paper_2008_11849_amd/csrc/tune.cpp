@@ -302,6 +302,14 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         return t;
     };
     auto key = [&](const Timing &t) { return rank_cold ? t.cold : t.warm; };
+    // `a` beats `b`: by the ranking figure; cold figures within 1 % of each other are a tie (that is
+    // what they scatter by), which the back-to-back figure breaks
+    auto beats = [&](const Timing &a, const Timing &b) {
+        if (key(a) <= 0.0f) return false;
+        if (key(b) <= 0.0f) return true;
+        if (rank_cold && a.warm > 0.0f && b.warm > 0.0f && key(a) < 1.01f * key(b) && key(b) < 1.01f * key(a)) return a.warm < b.warm;
+        return key(a) < key(b);
+    };
     auto log = [&](const sparsert_plan *p, const Timing &tm) {
         if (!report || report->count >= SPARSERT_TUNE_MAX) return;
         sparsert_tune_entry &t = report->entries[report->count++];
@@ -380,7 +388,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         }
         const Timing t = measure(p);
         log(p, t);
-        if (key(t) > 0.0f && (key(best_t) <= 0.0f || key(t) < key(best_t))) {
+        if (beats(t, best_t)) {
             sparsert_plan_destroy(best);
             best = p; best_t = t;
         } else {
@@ -398,7 +406,7 @@ static int tune_impl(const int32_t *row_ptr, const int32_t *col_idx, const void 
         if (sparsert_inspect(row_ptr, col_idx, vals, M, K, N, &o, &p) == SPARSERT_OK) {
             const Timing t = measure(p);
             log(p, t);
-            if (key(t) > 0.0f && key(t) < key(best_t)) {
+            if (beats(t, best_t)) {
                 sparsert_plan_destroy(best);
                 best = p; best_t = t;
             } else {
