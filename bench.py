@@ -305,8 +305,15 @@ def measure_traffic(args, layers, plan_path):
             kib = {c: sum(vals[c][0][-10:]) / len(vals[c][0][-10:]) for c in counted}   # the last launches: steady state
             fetch, write = kib["FETCH_SIZE"] * 1024.0, kib["WRITE_SIZE"] * 1024.0
             code = 8.0 * L.info["spec_code_bytes"]
-            refined = (code + max(0.0, fetch - code) * factor["FETCH_SIZE"]) if fetch > code else fetch * factor["FETCH_SIZE"]
+            # waves that prefetch their code bring most of it in through data requests, which the counter
+            # halves like any other: there the plain scaling is the estimate (an upper one: what still
+            # arrives as instruction fetches is counted in full)
+            split = fetch > code and not L.info.get("spec_prefetch")
+            refined = (code + (fetch - code) * factor["FETCH_SIZE"]) if split else fetch * factor["FETCH_SIZE"]
             res["layers"].append({"layer": L.case.name, "kernel": name,
+                                  "refined_how": "instruction fetches (8 x code, counted in full) taken out before scaling" if split
+                                                 else "scaled plainly",
+
                                   "fetch_counted_bytes": fetch, "write_counted_bytes": write,
                                   "plain_scaled_bytes": fetch * factor["FETCH_SIZE"] + write * factor["WRITE_SIZE"],
                                   "refined_bytes": refined + write * factor["WRITE_SIZE"]})
