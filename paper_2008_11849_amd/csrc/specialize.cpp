@@ -715,6 +715,19 @@ static int choose_launch_shape(const HostPlan &h, const sparsert_options &opt, S
     const bool half = h.dtype == SPARSERT_F16, int8 = h.dtype == SPARSERT_I8;
     const int32_t M = h.M, N = h.N;
     sp.mode = opt.spec_mode ? opt.spec_mode : SPARSERT_SPEC_DIRECT;
+    // With nothing set, large and very sparse products take the LDS-staged variant with eight waves:
+    // every wave fetches a row of B for few multiply-adds there, and staging lets eight blocks share
+    // each fetch.  Over the shape sweep it is what the tuner picks from 95 % sparsity on once a
+    // compute unit has 512 rows x tiles of C to itself (4096 x 4096 x 4096 at 98 %: 73 us against
+    // 156 us for the DIRECT default; 2048 x 2048 x 3136, 392 per compute unit, is better off with
+    // DIRECT); below 95 % the multiply-adds dominate and DIRECT is as fast.
+    bool auto_staged = false;
+    if (!opt.spec_mode && !opt.spec_rows && !opt.spec_ksplit && !opt.spec_tiles && !opt.spec_lanes && opt.spec_vec <= 1 &&
+        h.dtype == SPARSERT_F32 && !h.conv && h.K >= 1024 && (int64_t)h.nnz * 18 <= (int64_t)M * h.K &&
+        (int64_t)M * ((N + kWave - 1) / kWave) * std::max(1, h.batch) >= 131072) {
+        sp.mode = SPARSERT_SPEC_LDS;
+        auto_staged = true;
+    }
     const bool lds = sp.mode == SPARSERT_SPEC_LDS;
     // Column tiling with one column per lane, balanced tails (same rule as the row-walk plan at V = 1).
     const int max_lanes = opt.spec_lanes ? opt.spec_lanes : kWave;
@@ -728,7 +741,7 @@ static int choose_launch_shape(const HostPlan &h, const sparsert_options &opt, S
     const int32_t nvc = N / V;   // vector columns
     sp.n_tiles = (nvc + max_lanes - 1) / max_lanes;
     sp.lanes_per_tile = (nvc + sp.n_tiles - 1) / sp.n_tiles;
-    sp.tiles_per_wg = opt.spec_tiles ? opt.spec_tiles : 4;
+    sp.tiles_per_wg = opt.spec_tiles ? opt.spec_tiles : auto_staged ? 8 : 4;
     // Rows per block and K split.  Left at 0 they follow what the tuner's winners have in common
     // on this chip: a launch of about two waves per SIMD (2048 waves), with as many rows per
     // block as that allows, because rows per block is what saves fetches of B, and with the
@@ -736,7 +749,9 @@ static int choose_launch_shape(const HostPlan &h, const sparsert_options &opt, S
     int R = opt.spec_rows;
     int KS = opt.spec_ksplit;
     if (KS == 0) KS = (!lds && R == 0 && h.K >= 512) ? 8 : 1;
-    if (R == 0 && lds) {
+    if (auto_staged) {
+        R = rows_for_whole_rounds(M, 8, (int64_t)sp.n_tiles * std::max(1, h.batch), 32, 128);
+    } else if (R == 0 && lds) {
         // LDS variant: R1 fills 1024 SIMDs with one wave each, R2 gives a wave about 400 multiply-adds
         const int64_t r1 = (int64_t)M * sp.n_tiles / 1024;
         const int64_t avg = std::max<int64_t>(1, h.nnz / M);

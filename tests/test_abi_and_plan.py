@@ -351,7 +351,8 @@ def test_inspect_from_several_threads_at_once():
     (1024, 4096, 784, 1, 54, 8),     # 52 rows would make 20 blocks x 13 tiles = 260 workgroups for 256 compute units; 54 make 247
     (256, 256, 3136, 1, 14, 1),      # 12 rows: 22 x 13 = 286 workgroups of four tiles; 14 rows: 19 x 13 = 247
     (1024, 1024, 3136, 1, 103, 4),   # 96 rows: 11 blocks x 49 tiles = 539 workgroups, a thin third round; 103 rows: 10 x 49 = 490
-    (2048, 2048, 4096, 1, 96, 2),    # 22 x 64 = 1408 workgroups: the last round is half full, nothing to gain
+    (2048, 1000, 4096, 1, 96, 2),    # 22 x 64 = 1408 workgroups: the last round is half full, nothing to gain
+    (2048, 2048, 4096, 1, 64, 1),    # large and 98 % sparse with a long reduction axis: the LDS-staged variant, eight waves of 64 rows
     (64, 256, 3136, 1, 3, 1),        # blocks of a few rows are left alone
 ])
 def test_untuned_defaults_of_the_generated_kernel(M, K, N, batch, rows, ksplit):
