@@ -538,3 +538,23 @@ def test_load_rejects_damaged_blobs():
     h = ctypes.c_void_p()
     assert sp.raw.sparsert_plan_load(None, 100, 1, ctypes.byref(h)) == sp.EINVAL
     assert sp.raw.sparsert_plan_save(None, None, 0, None) == sp.EINVAL
+
+
+def test_staged_default_for_large_and_very_sparse_products():
+    """With no tiling option set, a large fp32 SpMM with a long reduction axis and at least 94.5 %
+    zeros takes the LDS-staged variant with eight waves; anything else keeps DIRECT."""
+    def default_mode(M, K, N, sparsity, dtype=np.float32, **kw):
+        csr = synth.uniform_csr(M, K, sparsity, 5, dtype=dtype)
+        plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, M, K, N, host_only=True, kernel=sp.KERNEL_SPEC, **kw)
+        info = plan.info()
+        plan.destroy()
+        return info["spec_mode"], info["spec_tiles"], info["spec_rows"]
+    assert default_mode(2048, 1024, 4096, 0.97) == (sp.SPEC_LDS, 8, 64)      # 2048 x 64 tiles = 131072
+    assert default_mode(4096, 1024, 3136, 0.96)[:2] == (sp.SPEC_LDS, 8)
+    assert default_mode(2048, 1024, 4096, 0.90)[0] == sp.SPEC_DIRECT          # too dense: the multiply-adds dominate
+    assert default_mode(2048, 512, 4096, 0.97)[0] == sp.SPEC_DIRECT           # short reduction axis
+    assert default_mode(2048, 1024, 3136, 0.97)[0] == sp.SPEC_DIRECT          # 2048 x 49 tiles: under 512 per compute unit
+    assert default_mode(2048, 1024, 4096, 0.97, dtype=np.float16)[0] == sp.SPEC_DIRECT
+    assert default_mode(2048, 1024, 4096, 0.97, spec_rows=48)[0] == sp.SPEC_DIRECT   # any tiling option: the caller's call
+    assert default_mode(2048, 1024, 4096, 0.97, spec_mode=sp.SPEC_DIRECT)[0] == sp.SPEC_DIRECT
+    assert default_mode(512, 1024, 4096, 0.97, batch=4)[:2] == (sp.SPEC_LDS, 8)       # the problems of a batch count
