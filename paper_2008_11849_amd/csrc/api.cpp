@@ -143,9 +143,11 @@ int sparsert_plan_export(const sparsert_plan *plan, int32_t field, void *buf, si
     case SPARSERT_FIELD_KERNEL_NAME:
         if (h.kernel == SPARSERT_KERNEL_SPEC) {
             name = h.spec.symbol;
+        } else if (h.dtype == SPARSERT_F16) {
+            // the profiler's demangler does not know the half type and shows the symbol as it is
+            name = "_ZN8sparsert11rows_kernelIDF16_Li" + std::to_string(h.vec) + "ELb" + (h.conv ? "1" : "0") + "EEEvNS_8RowsArgsE";
         } else {
-            name = std::string("void sparsert::rows_kernel<") +
-                   (h.dtype == SPARSERT_F16 ? "_Float16" : h.dtype == SPARSERT_I8 ? "signed char" : "float") + ", " +
+            name = std::string("void sparsert::rows_kernel<") + (h.dtype == SPARSERT_I8 ? "signed char" : "float") + ", " +
                    std::to_string(h.vec) + ", " + (h.conv ? "true" : "false") + ">(sparsert::RowsArgs)";
         }
         src = name.data(); bytes = name.size();

@@ -558,3 +558,30 @@ def test_staged_default_for_large_and_very_sparse_products():
     assert default_mode(2048, 1024, 4096, 0.97, spec_rows=48)[0] == sp.SPEC_DIRECT   # any tiling option: the caller's call
     assert default_mode(2048, 1024, 4096, 0.97, spec_mode=sp.SPEC_DIRECT)[0] == sp.SPEC_DIRECT
     assert default_mode(512, 1024, 4096, 0.97, batch=4)[:2] == (sp.SPEC_LDS, 8)       # the problems of a batch count
+
+
+def test_kernel_name_of_row_walk_plans_is_a_symbol_of_the_library():
+    """SPARSERT_FIELD_KERNEL_NAME is what a kernel trace shows: the demangled instantiation of
+    rows_kernel, or - for half storage, whose type the profiler's demangler does not know - the
+    symbol itself.  Either way it must name a kernel this library holds."""
+    import shutil
+    import subprocess
+    if shutil.which("nm") is None:
+        pytest.skip("nm is not installed")
+    lib = os.path.join(os.path.dirname(sp.__file__), "libsparsert.so")
+    mangled = {l.split()[-1] for l in subprocess.run(["nm", "-D", lib], capture_output=True, text=True, check=True).stdout.splitlines() if l.split()}
+    demangled = {l.split(None, 2)[-1] for l in subprocess.run(["nm", "-D", "-C", lib], capture_output=True, text=True, check=True).stdout.splitlines() if "rows_kernel" in l}
+    seen = set()
+    for dtype in (np.float32, np.float16, np.int8):
+        csr = synth.int8_csr(24, 40, 0.8, 2) if dtype == np.int8 else synth.uniform_csr(24, 40, 0.8, 2, dtype=dtype)
+        for vec in (1, 4) if dtype == np.int8 else (1, 2, 4):
+            plan = sp.inspect(csr.row_ptr, csr.col_idx, csr.vals, 24, 40, 64, host_only=True, kernel=sp.KERNEL_ROWS, vec=vec)
+            name = plan.kernel_name()
+            plan.destroy()
+            assert name in (mangled if dtype == np.float16 else demangled), name
+            seen.add(name)
+    ccsr, _ = synth.conv_weights_csr(4, 2, 0.5, 1, dtype=np.float16)
+    plan = sp.inspect(ccsr.row_ptr, ccsr.col_idx, ccsr.vals, 4, 18, 16, conv=(2, 4, 4), host_only=True, kernel=sp.KERNEL_ROWS)
+    assert plan.kernel_name() in mangled
+    plan.destroy()
+    assert len(seen) == 8
