@@ -308,7 +308,7 @@ def measure_traffic(args, layers, plan_path):
             # waves that prefetch their code bring most of it in through data requests, which the counter
             # halves like any other: there the plain scaling is the estimate (an upper one: what still
             # arrives as instruction fetches is counted in full)
-            split = fetch > code and not L.info.get("spec_prefetch")
+            split = code > 0 and fetch > code and not L.info.get("spec_prefetch")
             refined = (code + (fetch - code) * factor["FETCH_SIZE"]) if split else fetch * factor["FETCH_SIZE"]
             res["layers"].append({"layer": L.case.name, "kernel": name,
                                   "refined_how": "instruction fetches (8 x code, counted in full) taken out before scaling" if split
