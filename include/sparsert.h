@@ -98,7 +98,7 @@ typedef struct sparsert_options {
                                 0 = automatic */
     int32_t spec_mode;       /* sparsert_spec_mode; 0 = automatic: DIRECT, except that an fp32 SpMM plan with no
                                 other tiling field set takes the LDS-staged variant with eight waves when A is
-                                at least 94.5 % sparse, K >= 1024 and M x ceil(N / 64) x batch >= 131072 */
+                                at least 94.5 % sparse, M >= 2048, K >= 1024 and M x ceil(N / 64) x batch >= 131072 */
     int32_t spec_ksplit;     /* SPARSERT_KERNEL_SPEC, DIRECT: 2, 4 or 8 waves of a workgroup share one
                                 code block's rows and column tile and split its columns (equal
                                 nonzero shares, partial sums meet in LDS, in several phases if

@@ -720,10 +720,11 @@ static int choose_launch_shape(const HostPlan &h, const sparsert_options &opt, S
     // each fetch.  Over the shape sweep it is what the tuner picks from 95 % sparsity on once a
     // compute unit has 512 rows x tiles of C to itself (4096 x 4096 x 4096 at 98 %: 73 us against
     // 156 us for the DIRECT default; 2048 x 2048 x 3136, 392 per compute unit, is better off with
-    // DIRECT); below 95 % the multiply-adds dominate and DIRECT is as fast.
+    // DIRECT); below 95 % the multiply-adds dominate and DIRECT is as fast.  M >= 2048 keeps the rule
+    // to what was measured: eight waves with blocks of at least 32 rows and several workgroups per tile.
     bool auto_staged = false;
     if (!opt.spec_mode && !opt.spec_rows && !opt.spec_ksplit && !opt.spec_tiles && !opt.spec_lanes && opt.spec_vec <= 1 &&
-        h.dtype == SPARSERT_F32 && !h.conv && h.K >= 1024 && (int64_t)h.nnz * 18 <= (int64_t)M * h.K &&
+        h.dtype == SPARSERT_F32 && !h.conv && M >= 2048 && h.K >= 1024 && (int64_t)h.nnz * 18 <= (int64_t)M * h.K &&
         (int64_t)M * ((N + kWave - 1) / kWave) * std::max(1, h.batch) >= 131072) {
         sp.mode = SPARSERT_SPEC_LDS;
         auto_staged = true;

@@ -557,7 +557,8 @@ def test_staged_default_for_large_and_very_sparse_products():
     assert default_mode(2048, 1024, 4096, 0.97, dtype=np.float16)[0] == sp.SPEC_DIRECT
     assert default_mode(2048, 1024, 4096, 0.97, spec_rows=48)[0] == sp.SPEC_DIRECT   # any tiling option: the caller's call
     assert default_mode(2048, 1024, 4096, 0.97, spec_mode=sp.SPEC_DIRECT)[0] == sp.SPEC_DIRECT
-    assert default_mode(512, 1024, 4096, 0.97, batch=4)[:2] == (sp.SPEC_LDS, 8)       # the problems of a batch count
+    assert default_mode(2048, 1024, 2048, 0.97, batch=2)[:2] == (sp.SPEC_LDS, 8)      # the problems of a batch count
+    assert default_mode(512, 1024, 4096, 0.97, batch=4)[0] == sp.SPEC_DIRECT          # few rows: not what was measured
 
 
 def test_kernel_name_of_row_walk_plans_is_a_symbol_of_the_library():
